@@ -1,0 +1,358 @@
+"""Pins for the CPU oracle: everything here checks `oracle/` against something other than itself.
+
+  - library routines: numpy unique / floor_divide, torch dense conv3d / conv_transpose3d (+ autograd), fp64
+  - brute-force coordinate comparison on tiny inputs
+  - closed forms and invariants of the kernel map and of Eq. 2 (Sec. III-B)
+
+No GPU, no HIP code.  A plausible mistake in the oracle (dropped term, wrong sign, transposed
+operand, wrong offset numbering, truncation instead of floor) fails at least one test.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2012_13846_amd import spgen
+
+
+def offsets(K):
+    """Offset list in the oracle's documented numbering, written independently: z fastest, low to high."""
+    c = (K - 1) // 2 if K % 2 else 0
+    return [(ax - c, ay - c, az - c) for ax in range(K) for ay in range(K) for az in range(K)]
+
+
+def random_coords(rng, n, grid, batches=2, lo=0):
+    c = np.empty((n, 4), np.int32)
+    c[:, 0] = rng.integers(0, batches, n)
+    c[:, 1:] = rng.integers(lo, lo + grid, (n, 3))
+    return c
+
+
+def split_lists(pin, pout, counts):
+    out, base = [], 0
+    for c in counts:
+        out.append(np.stack([pin[base:base + c], pout[base:base + c]], 1))
+        base += c
+    return out
+
+
+# ------------------------------------------------------------------ coordinates
+def test_unique_matches_numpy_first_occurrence():
+    rng = np.random.default_rng(1)
+    raw = random_coords(rng, 5000, 9, batches=3, lo=-4)
+    c, inv = oracle.unique_coords(raw)
+    u, first, inverse = np.unique(raw, axis=0, return_index=True, return_inverse=True)
+    order = np.argsort(first)                       # first-occurrence order
+    assert np.array_equal(c, u[order])
+    rank = np.empty_like(order)
+    rank[order] = np.arange(len(order))
+    assert np.array_equal(inv, rank[inverse.reshape(-1)])
+    assert np.array_equal(c[inv], raw)
+
+
+def test_unique_empty_and_single():
+    c, inv = oracle.unique_coords(np.zeros((0, 4), np.int32))
+    assert c.shape == (0, 4) and inv.shape == (0,)
+    c, inv = oracle.unique_coords(np.array([[1, 2, 3, 4]] * 3, np.int32))
+    assert c.tolist() == [[1, 2, 3, 4]] and inv.tolist() == [0, 0, 0]
+
+
+def test_strided_coords_true_floor_with_negatives():
+    rng = np.random.default_rng(2)
+    cin, _ = oracle.unique_coords(random_coords(rng, 3000, 21, lo=-10))
+    for ts, s in ((1, 2), (2, 2), (1, 3)):
+        cin_ts = cin.copy()
+        cin_ts[:, 1:] *= ts
+        cout, parent, ts_out = oracle.strided_coords(cin_ts, ts, s)
+        assert ts_out == ts * s
+        fl = cin_ts.copy()
+        fl[:, 1:] = np.floor_divide(cin_ts[:, 1:], ts * s) * (ts * s)   # numpy's floor division
+        assert np.array_equal(cout[parent], fl)
+        u, first = np.unique(fl, axis=0, return_index=True)
+        assert np.array_equal(cout, u[np.argsort(first)])
+
+
+def test_stride1_keeps_coordinates():
+    cin, _ = oracle.unique_coords(random_coords(np.random.default_rng(3), 500, 8))
+    cout, parent, ts = oracle.strided_coords(cin, 4, 1)
+    assert np.array_equal(cout, cin) and ts == 4 and np.array_equal(parent, np.arange(len(cin)))
+
+
+# ------------------------------------------------------------------ kernel maps
+def brute_force_map(cin, cout, K, step):
+    """O(n_out * n_in * K^3) coordinate comparison, numpy broadcasting, no search structure."""
+    lists = []
+    for off in offsets(K):
+        tgt = cout.copy()
+        tgt[:, 1:] += np.asarray(off, np.int32) * step
+        eq = np.all(cin[:, None, :] == tgt[None, :, :], axis=2)     # [n_in][n_out]
+        i, o = np.nonzero(eq)                                       # row-major: sorted by (in, out)
+        lists.append(np.stack([i, o], 1).astype(np.int32))
+    return lists
+
+
+@pytest.mark.parametrize("K,stride,dil,ts", [(3, 1, 1, 1), (3, 1, 2, 1), (3, 1, 1, 2), (2, 2, 1, 1),
+                                             (3, 2, 1, 1), (2, 2, 1, 2), (5, 1, 1, 1), (1, 1, 1, 1)])
+def test_kmap_equals_brute_force(K, stride, dil, ts):
+    rng = np.random.default_rng(10 + K + stride + dil + ts)
+    cin, _ = oracle.unique_coords(random_coords(rng, 260, 7, lo=-3))
+    cin = cin[:200].copy()
+    cin[:, 1:] *= ts
+    cout, _, _ = oracle.strided_coords(cin, ts, stride)
+    pin, pout, counts = oracle.kernel_map(cin, cout, K, dil * ts)
+    got = split_lists(pin, pout, counts)
+    want = brute_force_map(cin, cout, K, dil * ts)
+    assert len(got) == K ** 3
+    for g, w in zip(got, want):
+        assert np.array_equal(g, w)
+
+
+def test_full_cube_closed_form_counts():
+    # full n^3 cube, K=3: offset (ix,iy,iz) links prod(n - |i_axis|) pairs; total (3n-2)^3
+    n = 6
+    g = np.stack(np.meshgrid(*[np.arange(n)] * 3, indexing="ij"), -1).reshape(-1, 3)
+    cin = np.concatenate([np.zeros((n ** 3, 1), np.int64), g], 1).astype(np.int32)
+    _, _, counts = oracle.kernel_map(cin, cin, 3, 1)
+    want = [np.prod([n - abs(a) for a in off]) for off in offsets(3)]
+    assert counts.tolist() == want
+    assert counts.sum() == (3 * n - 2) ** 3
+
+
+def test_stride1_symmetry_and_identity_centre():
+    cin, _ = oracle.unique_coords(spgen.coords_config(0))
+    N = len(cin)
+    pin, pout, counts = oracle.kernel_map(cin, cin, 3, 1)
+    L = split_lists(pin, pout, counts)
+    assert np.array_equal(L[13], np.stack([np.arange(N)] * 2, 1))
+    for k in range(27):
+        mirror = L[26 - k][:, ::-1]
+        mirror = mirror[np.lexsort((mirror[:, 1], mirror[:, 0]))]
+        assert np.array_equal(L[k], mirror)
+        assert counts[k] == counts[26 - k]
+
+
+def test_k2s2_every_input_in_exactly_one_pair():
+    cin, _ = oracle.unique_coords(spgen.coords_config(0))
+    cout, parent, _ = oracle.strided_coords(cin, 1, 2)
+    pin, pout, counts = oracle.kernel_map(cin, cout, 2, 1)
+    assert counts.sum() == len(cin)
+    assert np.array_equal(np.sort(pin), np.arange(len(cin)))
+    assert np.array_equal(np.unique(pout), np.arange(len(cout)))
+    assert np.array_equal(parent[pin], pout)        # the pair's output is the input's coarse parent
+    # the offset number is the child's position inside its 2x2x2 cell, z fastest
+    child = cin[:, 1:] - cout[parent][:, 1:]
+    k_of = (child[:, 0] * 2 + child[:, 1]) * 2 + child[:, 2]
+    k_pair = np.repeat(np.arange(8), counts)
+    assert np.array_equal(k_of[pin], k_pair)
+
+
+def test_transposed_map_pair_symmetry():
+    cin, _ = oracle.unique_coords(spgen.coords_config(0))
+    cout, _, _ = oracle.strided_coords(cin, 1, 2)
+    pin, pout, counts = oracle.kernel_map(cin, cout, 2, 1)
+    tin, tout, tcounts = oracle.transpose_map(pin, pout, counts)
+    assert np.array_equal(tcounts, counts)
+    for a, b in zip(split_lists(pin, pout, counts), split_lists(tin, tout, tcounts)):
+        assert {tuple(r) for r in a.tolist()} == {(o, i) for (i, o) in b.tolist()}
+        assert np.array_equal(b, b[np.lexsort((b[:, 1], b[:, 0]))])
+
+
+def test_no_pair_crosses_batches_and_batch_independence():
+    rng = np.random.default_rng(5)
+    a, _ = oracle.unique_coords(random_coords(rng, 400, 6, batches=1))
+    b, _ = oracle.unique_coords(random_coords(rng, 300, 6, batches=1))
+    b2 = b.copy()
+    b2[:, 0] = 1
+    both = np.concatenate([a, b2])
+    pin, pout, counts = oracle.kernel_map(both, both, 3, 1)
+    assert np.array_equal(both[pin, 0], both[pout, 0])
+    _, _, ca = oracle.kernel_map(a, a, 3, 1)
+    _, _, cb = oracle.kernel_map(b, b, 3, 1)
+    assert np.array_equal(counts, ca + cb)
+    X = spgen.features(1, len(both), 3)
+    W = spgen.weights(2, 27, 3, 5)
+    Y = oracle.conv_fwd(pin, pout, counts, X, W, len(both))
+    pa = oracle.kernel_map(a, a, 3, 1)
+    pb = oracle.kernel_map(b, b, 3, 1)
+    Ya = oracle.conv_fwd(*pa, X[:len(a)], W, len(a))
+    Yb = oracle.conv_fwd(*pb, X[len(a):], W, len(b))
+    assert np.array_equal(Y, np.concatenate([Ya, Yb]))
+
+
+def test_translation_by_stride_multiple_keeps_maps():
+    rng = np.random.default_rng(6)
+    cin, _ = oracle.unique_coords(random_coords(rng, 500, 12))
+    cout, _, _ = oracle.strided_coords(cin, 1, 2)
+    ref = oracle.kernel_map(cin, cout, 3, 1)
+    moved = cin.copy()
+    moved[:, 1:] += np.array([-40, 2, -6], np.int32)          # multiples of 2, into negatives
+    mout, _, _ = oracle.strided_coords(moved, 1, 2)
+    got = oracle.kernel_map(moved, mout, 3, 1)
+    for r, g in zip(ref, got):
+        assert np.array_equal(r, g)
+    assert np.array_equal(mout[:, 1:] - cout[:, 1:], np.broadcast_to([-40, 2, -6], cout[:, 1:].shape))
+
+
+def test_dilation_reduces_to_scaled_coordinates():
+    rng = np.random.default_rng(7)
+    c, _ = oracle.unique_coords(random_coords(rng, 600, 8))
+    c3 = c.copy()
+    c3[:, 1:] *= 3
+    for r, g in zip(oracle.kernel_map(c, c, 3, 1), oracle.kernel_map(c3, c3, 3, 3)):
+        assert np.array_equal(r, g)
+
+
+def test_row_permutation_equivariance():
+    rng = np.random.default_rng(8)
+    c, _ = oracle.unique_coords(random_coords(rng, 500, 7))
+    N = len(c)
+    perm = rng.permutation(N)
+    X = spgen.features(3, N, 4)
+    W = spgen.weights(4, 27, 4, 6)
+    Y = oracle.conv_fwd(*oracle.kernel_map(c, c, 3, 1), X, W, N)
+    Yp = oracle.conv_fwd(*oracle.kernel_map(c[perm], c[perm], 3, 1), X[perm], W, N)
+    assert np.allclose(Yp, Y[perm], rtol=0, atol=1e-12)
+
+
+# ------------------------------------------------------------------ convolution vs dense library conv
+def dense_case(seed, grid, n, cin_ch, cout_ch, batches=2, lo=0):
+    rng = np.random.default_rng(seed)
+    c, _ = oracle.unique_coords(random_coords(rng, n, grid, batches, lo))
+    X = rng.standard_normal((len(c), cin_ch)).astype(np.float32)
+    return rng, c, X
+
+
+def to_dense(c, F, batches, grid, lo=0):
+    d = torch.zeros(batches, F.shape[1], grid, grid, grid, dtype=torch.float64)
+    d[c[:, 0], :, c[:, 1] - lo, c[:, 2] - lo, c[:, 3] - lo] = torch.from_numpy(np.asarray(F, np.float64))
+    return d
+
+
+def dense_weight(W, K):
+    """[K^3][cout][cin] with z-fastest offset numbering -> torch conv3d weight [cout][cin][Kx][Ky][Kz]."""
+    kvol, cout, cin = W.shape
+    return torch.from_numpy(np.asarray(W, np.float64)).reshape(K, K, K, cout, cin).permute(3, 4, 0, 1, 2).contiguous()
+
+
+@pytest.mark.parametrize("K,dil", [(3, 1), (3, 2), (5, 1), (1, 1)])
+def test_fwd_bwd_equal_dense_conv3d_stride1(K, dil):
+    grid, B, ci, co = 9, 2, 3, 4
+    rng, c, X = dense_case(20 + K + dil, grid, 500, ci, co, B, lo=-4)
+    N = len(c)
+    W = rng.standard_normal((K ** 3, co, ci)).astype(np.float32)
+    dY = rng.standard_normal((N, co)).astype(np.float32)
+    maps = oracle.kernel_map(c, c, K, dil)
+    Y = oracle.conv_fwd(*maps, X, W, N)
+    dX = oracle.conv_bwd_data(*maps, dY, W, N)
+    dW = oracle.conv_bwd_weight(*maps, X, dY)
+
+    xd = to_dense(c, X, B, grid, lo=-4).requires_grad_(True)
+    wd = dense_weight(W, K).requires_grad_(True)
+    yd = torch.nn.functional.conv3d(xd, wd, padding=dil * (K - 1) // 2, dilation=dil)   # cross-correlation, Eq. 1
+    idx = (c[:, 0], slice(None), c[:, 1] + 4, c[:, 2] + 4, c[:, 3] + 4)
+    assert np.allclose(Y, yd[idx].detach().numpy(), rtol=0, atol=1e-12)
+    # gradient of <dY, Y restricted to active output sites>
+    (yd[idx] * torch.from_numpy(dY.astype(np.float64))).sum().backward()
+    assert np.allclose(dX, xd.grad[idx].numpy(), rtol=0, atol=1e-12)
+    dWd = wd.grad.permute(2, 3, 4, 0, 1).reshape(K ** 3, co, ci).numpy()
+    assert np.allclose(dW, dWd, rtol=0, atol=1e-11)
+
+
+@pytest.mark.parametrize("K", [2, 3])
+def test_fwd_bwd_equal_dense_conv3d_stride2(K):
+    grid, B, ci, co = 10, 2, 3, 5
+    rng, c, X = dense_case(40 + K, grid, 600, ci, co, B)
+    cout, _, ts = oracle.strided_coords(c, 1, 2)
+    assert ts == 2
+    W = rng.standard_normal((K ** 3, co, ci)).astype(np.float32)
+    dY = rng.standard_normal((len(cout), co)).astype(np.float32)
+    maps = oracle.kernel_map(c, cout, K, 1)
+    Y = oracle.conv_fwd(*maps, X, W, len(cout))
+    dX = oracle.conv_bwd_data(*maps, dY, W, len(c))
+    dW = oracle.conv_bwd_weight(*maps, X, dY)
+
+    xd = to_dense(c, X, B, grid).requires_grad_(True)
+    wd = dense_weight(W, K).requires_grad_(True)
+    if K == 2:      # offsets {0,1}^3: a stride-2 window starting at the coarse coordinate, no padding
+        yd = torch.nn.functional.conv3d(xd, wd, stride=2)
+    else:           # offsets {-1,0,1}^3 centred on the coarse coordinate (an even site)
+        yd = torch.nn.functional.conv3d(xd, wd, padding=1, stride=2)
+    idx_o = (cout[:, 0], slice(None), cout[:, 1] // 2, cout[:, 2] // 2, cout[:, 3] // 2)
+    idx_i = (c[:, 0], slice(None), c[:, 1], c[:, 2], c[:, 3])
+    assert np.allclose(Y, yd[idx_o].detach().numpy(), rtol=0, atol=1e-12)
+    (yd[idx_o] * torch.from_numpy(dY.astype(np.float64))).sum().backward()
+    assert np.allclose(dX, xd.grad[idx_i].numpy(), rtol=0, atol=1e-12)
+    assert np.allclose(dW, wd.grad.permute(2, 3, 4, 0, 1).reshape(K ** 3, co, ci).numpy(), rtol=0, atol=1e-11)
+
+
+def test_transposed_k2s2_equals_dense_conv_transpose3d():
+    grid, B, cf, cc = 10, 2, 3, 5            # fine channels (output of the upsampling), coarse channels (its input)
+    rng, c_fine, _ = dense_case(50, grid, 600, cf, cc, B)
+    c_coarse, _, _ = oracle.strided_coords(c_fine, 1, 2)
+    fwd = oracle.kernel_map(c_fine, c_coarse, 2, 1)
+    tin, tout, tcounts = oracle.transpose_map(*fwd)
+    Yc = rng.standard_normal((len(c_coarse), cc)).astype(np.float32)
+    V = rng.standard_normal((8, cf, cc)).astype(np.float32)          # [K^3][out = fine ch][in = coarse ch]
+    Z = oracle.conv_fwd(tin, tout, tcounts, Yc, V, len(c_fine))
+
+    yd = torch.zeros(B, cc, grid // 2, grid // 2, grid // 2, dtype=torch.float64)
+    yd[c_coarse[:, 0], :, c_coarse[:, 1] // 2, c_coarse[:, 2] // 2, c_coarse[:, 3] // 2] = torch.from_numpy(Yc.astype(np.float64))
+    # conv_transpose3d weight is [in][out][Kx][Ky][Kz]
+    wt = torch.from_numpy(V.astype(np.float64)).reshape(2, 2, 2, cf, cc).permute(4, 3, 0, 1, 2).contiguous()
+    zd = torch.nn.functional.conv_transpose3d(yd, wt, stride=2)
+    got = zd[c_fine[:, 0], :, c_fine[:, 1], c_fine[:, 2], c_fine[:, 3]].numpy()
+    assert np.allclose(Z, got, rtol=0, atol=1e-12)
+
+
+def test_identity_and_single_offset_shift():
+    c, _ = oracle.unique_coords(spgen.coords_config(0))
+    N, ch = len(c), 4
+    X = spgen.features(9, N, ch)
+    maps = oracle.kernel_map(c, c, 3, 1)
+    lookup = {tuple(r): j for j, r in enumerate(c.tolist())}
+    for k, off in enumerate(offsets(3)):
+        W = np.zeros((27, ch, ch), np.float32)
+        W[k] = np.eye(ch)
+        Y = oracle.conv_fwd(*maps, X, W, N)
+        want = np.zeros((N, ch))
+        for o, (b, x, y, z) in enumerate(c.tolist()):
+            j = lookup.get((b, x + off[0], y + off[1], z + off[2]))     # x_in[u + i], Eq. 2
+            if j is not None:
+                want[o] = X[j]
+        assert np.array_equal(Y, want)
+        if off == (0, 0, 0):
+            assert np.array_equal(Y, X.astype(np.float64))
+
+
+def test_adjoint_identities():
+    cfine, _ = oracle.unique_coords(spgen.coords_config(0))
+    for K, stride in ((3, 1), (2, 2), (3, 2)):
+        cout, _, _ = oracle.strided_coords(cfine, 1, stride)
+        maps = oracle.kernel_map(cfine, cout, K, 1)
+        ci, co = 5, 3
+        X = spgen.features(11, len(cfine), ci)
+        dY = spgen.features(12, len(cout), co)
+        W = spgen.weights(13, K ** 3, ci, co)
+        a = np.sum(dY * oracle.conv_fwd(*maps, X, W, len(cout)))
+        b = np.sum(oracle.conv_bwd_data(*maps, dY, W, len(cfine)) * X)
+        c = np.sum(oracle.conv_bwd_weight(*maps, X, dY) * W)
+        assert abs(a - b) <= 1e-9 * abs(a) and abs(a - c) <= 1e-9 * abs(a)
+
+
+def test_bf16_helpers_round_to_nearest_even():
+    x = np.array([1.0, 1.00390625, 1.005859375, -2.5, 3.140625, 1e-3, 65504.0], np.float32)
+    want = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()     # library rounding
+    assert np.array_equal(spgen.round_to_bf16(x), want)
+    r = np.random.default_rng(0).standard_normal(10000).astype(np.float32)
+    assert np.array_equal(spgen.round_to_bf16(r), torch.from_numpy(r).to(torch.bfloat16).to(torch.float32).numpy())
+
+
+def test_generated_occupancy_is_surface_like():
+    # the stand-in clouds live in the paper's thin-surface regime (Sec. IV: a few % of the grid occupied)
+    c, _ = oracle.unique_coords(spgen.coords_config(0))
+    assert 1200 < len(c) < 1800
+    assert 0.02 < len(c) / 32 ** 3 < 0.08
+    _, _, counts = oracle.kernel_map(c, c, 3, 1)
+    assert 4.0 < counts.sum() / len(c) < 12.0
