@@ -1,0 +1,136 @@
+/*
+ * sp_conv.h - C ABI of the MI355X (gfx950) generalized sparse convolution library.
+ *
+ * The library implements the three steps of the generalized sparse convolution
+ * (Sec. III-B: 1 output coordinates, 2 input/output mapping per kernel weight,
+ * 3 the sum of Eq. 2) and the gradients of Eq. 2 w.r.t. inputs and weights
+ * (Sec. II-A), all as HIP kernels.  There is no CPU fallback.
+ *
+ * Conventions
+ *   - A sparse tensor is (C, F) (Sec. III-B): C is int32 [N][4], rows (b, x, y, z),
+ *     batch index first; F is [N][channels], row j of F belongs to row j of C.
+ *     Both row-major, in device memory.
+ *   - Kernel weights are W[K^3][N_out][N_in] (Sec. III-B: K^D matrices of size
+ *     N_out x N_in), row-major, device memory.
+ *   - Kernel offset number k = (ax*K + ay)*K + az (z fastest); an odd K uses offsets
+ *     a - (K-1)/2 (centred, as V^1(3) = {-1,0,1}), an even K uses offsets a in 0..K-1.
+ *     Offsets are multiplied by dilation * (input tensor stride).
+ *   - Pointers named d_* are DEVICE pointers, h_* are HOST pointers.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
+ *     work of a call is enqueued on it.  Calls that "synchronise" block the host
+ *     until that stream has drained.
+ *   - Every function returns SP_OK (0) or a negative sp_status; sp_last_error()
+ *     gives a message for the calling thread's last failure.  Argument checks are
+ *     done on the host before anything is launched.
+ *   - Handles own their device memory (taken from a caching pool inside the
+ *     library) until destroyed.  Pointers returned by *_data/_pairs/_table/_tiles are
+ *     borrowed and die with the handle.  Feature / weight / gradient buffers are
+ *     owned by the caller and must stay alive until the stream passed the call.
+ *   - All calls that touch one handle must use the same stream (or be ordered by
+ *     the caller).  Coordinates must satisfy 0 <= b < 65536 and
+ *     -32768 <= x,y,z < 32768, else SP_ERR_RANGE.
+ */
+#ifndef SP_CONV_H
+#define SP_CONV_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SP_OK = 0,
+    SP_ERR_INVALID_ARG = -1, /* null pointer, negative size, bad kernel/stride/dilation/channels */
+    SP_ERR_RANGE = -2,       /* a coordinate cannot be packed into the 64-bit key */
+    SP_ERR_ALLOC = -3,       /* device or host allocation failed */
+    SP_ERR_HIP = -4,         /* a HIP runtime call failed */
+    SP_ERR_UNSUPPORTED = -5, /* valid request this build does not implement (dilation > 1 with stride > 1) */
+    SP_ERR_TABLE_FULL = -6   /* hash table overflow (cannot happen at the load factor used; checked anyway) */
+} sp_status;
+
+typedef enum { SP_F32 = 0, SP_BF16 = 1 } sp_dtype; /* storage type of features/weights; accumulation is fp32 */
+
+typedef struct sp_coords sp_coords_t; /* distinct coordinates + their hash table + tensor stride   */
+typedef struct sp_kmap sp_kmap_t;     /* kernel map of one (coords, kernel, stride, dilation)      */
+
+/* ---- step 0: the sparse tensor's coordinate set (Sec. III-B, sparse tensor definition) --------------
+ * Hashes d_raw [n_raw][4] into an open-addressing table, merges duplicate rows and numbers the
+ * distinct rows in first-occurrence order (unique row r = r-th distinct coordinate met walking the
+ * rows in order).  tensor_stride (>= 1) is recorded, coordinates are expected on that lattice.
+ * Synchronises `stream` once (the count N comes back to the host).  n_raw may be 0.
+ * *out receives a new handle (caller destroys).  d_raw is not referenced after the call returns. */
+int sp_coords_build(const int32_t* d_raw, int64_t n_raw, int32_t tensor_stride, void* stream, sp_coords_t** out);
+
+/* N and the tensor stride (host values, no synchronisation). Either out pointer may be NULL. */
+int sp_coords_size(const sp_coords_t* c, int64_t* n, int32_t* tensor_stride);
+
+/* d_coords: int32 [N][4]; d_inverse: int32 [n_raw], inverse[j] = distinct row that raw row j merged into. */
+int sp_coords_data(const sp_coords_t* c, const int32_t** d_coords, const int32_t** d_inverse, int64_t* n_raw);
+
+/* Drops one reference; the memory is returned to the pool when the last reference goes. */
+int sp_coords_destroy(sp_coords_t* c);
+
+/* ---- steps 1 + 2: output coordinates and the kernel map (Sec. III-B steps 1, 2) -----------------------
+ * kernel_size in 1..5, stride >= 1, dilation >= 1 (dilation > 1 needs stride == 1).
+ * Step 1: stride 1 keeps the coordinates (out_coords = a new reference to `in`); stride s > 1 floors
+ *   x,y,z to multiples of S = tensor_stride*s (true floor), merges duplicates in first-occurrence
+ *   order, and the new tensor stride is S.
+ * Step 2: M_k = {(i,o) : c_in[i] = c_out[o] + offset_k * dilation * tensor_stride, same batch index},
+ *   found by probing the input set's hash table.
+ * Synchronises `stream` (pair counts, and N_out when stride > 1, come back to the host).
+ * *kmap and *out_coords receive new handles (caller destroys both; out_coords may be NULL if unwanted). */
+int sp_kmap_build(const sp_coords_t* in, int32_t kernel_size, int32_t stride, int32_t dilation, void* stream,
+                  sp_kmap_t** kmap, sp_coords_t** out_coords);
+
+/* The map of the transposed (upsampling) convolution that undoes `fwd`'s coordinate change: the same
+ * pairs with the roles of input and output swapped, same offset numbering.  Its outputs are fwd's input
+ * coordinates (the cached finer level).  (The paper defines no transposed convolution; this is the
+ * coordinate-hierarchy-reusing reading.)  No device work; shares fwd's buffers.  Caller destroys. */
+int sp_kmap_transpose(const sp_kmap_t* fwd, sp_kmap_t** transposed);
+
+/* Host-side facts (no synchronisation). h_counts, if not NULL, receives kvol pair counts |M_k|. */
+int sp_kmap_info(const sp_kmap_t* m, int64_t* n_in, int64_t* n_out, int32_t* kvol, int64_t* total_pairs,
+                 int64_t* h_counts);
+
+/* Pair lists of all offsets concatenated in offset order: list k occupies
+ * [sum_{j<k} counts[j], +counts[k]) of both arrays; entry p links input row d_pair_in[p] to output row
+ * d_pair_out[p].  Order inside one offset's list is deterministic but unspecified. */
+int sp_kmap_pairs(const sp_kmap_t* m, const int32_t** d_pair_in, const int32_t** d_pair_out);
+
+/* Neighbour tables, offset-major: d_nbr_out [kvol][n_out] = input row linked to (o,k) or -1;
+ * d_nbr_in [kvol][n_in] = output row linked to (i,k) or -1.  A stride-1 map with an odd kernel stores one
+ * table for both (the link (i,o) at offset k is the link (o,i) at offset kvol-1-k): then *in_reversed (or,
+ * for its transpose, *out_reversed) is 1 and block k of that table holds offset kvol-1-k. */
+int sp_kmap_table(const sp_kmap_t* m, const int32_t** d_nbr_out, const int32_t** d_nbr_in, int32_t* out_reversed,
+                  int32_t* in_reversed);
+
+int sp_kmap_destroy(sp_kmap_t* m);
+
+/* ---- step 3 and its gradients (Eq. 2; Sec. II-A for the backward pass) --------------------------------
+ * cin / cout are N_in / N_out of W[kvol][cout][cin].  dt is the storage type of x, w, y, dy, dx
+ * (SP_BF16: 16-bit bfloat16, results rounded to nearest even once); accumulation is always fp32.
+ * Outputs are overwritten (rows / offsets without pairs become zero).  No host synchronisation.
+ * Channel counts that are multiples of 16 run on the matrix cores; others on a plain kernel.
+ *
+ *   sp_conv_fwd:        y[o,:]  = sum_k sum_{(i,o) in M_k} W_k   x[i,:]      x [n_in][cin]   -> y  [n_out][cout]
+ *   sp_conv_bwd_data:   dx[i,:] = sum_k sum_{(i,o) in M_k} W_k^T dy[o,:]     dy [n_out][cout] -> dx [n_in][cin]
+ *   sp_conv_bwd_weight: dw_k    = sum_{(i,o) in M_k} dy[o,:] x[i,:]^T        -> dw fp32 [kvol][cout][cin]
+ * For a transposed map the same formulas hold with that map's own n_in (coarse) / n_out (fine). */
+int sp_conv_fwd(const sp_kmap_t* m, const void* d_x, const void* d_w, void* d_y, int32_t cin, int32_t cout,
+                sp_dtype dt, void* stream);
+int sp_conv_bwd_data(const sp_kmap_t* m, const void* d_dy, const void* d_w, void* d_dx, int32_t cin, int32_t cout,
+                     sp_dtype dt, void* stream);
+int sp_conv_bwd_weight(const sp_kmap_t* m, const void* d_x, const void* d_dy, float* d_dw, int32_t cin,
+                       int32_t cout, sp_dtype dt, void* stream);
+
+/* ---- housekeeping -------------------------------------------------------------------------------------- */
+const char* sp_last_error(void);  /* message of the calling thread's last failure ("" if none) */
+int sp_pool_trim(void);           /* synchronises the device and frees all cached (unused) device memory */
+int64_t sp_pool_bytes(void);      /* device bytes currently held by the pool (in use + cached) */
+const char* sp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SP_CONV_H */

@@ -1,0 +1,242 @@
+"""ctypes binding of the C-ABI library (include/sp_conv.h).  Argument marshalling only.
+
+Function names equal the C entry points.  torch supplies device memory and the current
+stream; every step of the path runs in the library's HIP kernels.  If the library is
+missing this module raises: there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsp_conv.so")
+
+SP_F32, SP_BF16 = 0, 1
+_vp = C.c_void_p
+_lib = None
+
+
+class SpError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"sp_conv error {code}: {msg}")
+        self.code = code
+
+
+def lib() -> C.CDLL:
+    """Loads libsp_conv.so (built in-tree by paper_2012_13846_amd.build); raises if it is absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2012_13846_amd.build` "
+                               "(there is no CPU fallback)")
+        l = C.CDLL(LIB_PATH)
+        l.sp_last_error.restype = C.c_char_p
+        l.sp_version.restype = C.c_char_p
+        l.sp_pool_bytes.restype = C.c_int64
+        l.sp_coords_build.argtypes = [_vp, C.c_int64, C.c_int32, _vp, C.POINTER(_vp)]
+        l.sp_coords_size.argtypes = [_vp, C.POINTER(C.c_int64), C.POINTER(C.c_int32)]
+        l.sp_coords_data.argtypes = [_vp, C.POINTER(_vp), C.POINTER(_vp), C.POINTER(C.c_int64)]
+        l.sp_coords_destroy.argtypes = [_vp]
+        l.sp_kmap_build.argtypes = [_vp, C.c_int32, C.c_int32, C.c_int32, _vp, C.POINTER(_vp), C.POINTER(_vp)]
+        l.sp_kmap_transpose.argtypes = [_vp, C.POINTER(_vp)]
+        l.sp_kmap_info.argtypes = [_vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int32),
+                                   C.POINTER(C.c_int64), _vp]
+        l.sp_kmap_pairs.argtypes = [_vp, C.POINTER(_vp), C.POINTER(_vp)]
+        l.sp_kmap_table.argtypes = [_vp, C.POINTER(_vp), C.POINTER(_vp), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+        l.sp_kmap_destroy.argtypes = [_vp]
+        for name in ("sp_conv_fwd", "sp_conv_bwd_data", "sp_conv_bwd_weight"):
+            getattr(l, name).argtypes = [_vp, _vp, _vp, _vp, C.c_int32, C.c_int32, C.c_int32, _vp]
+        _lib = l
+    return _lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise SpError(rc, lib().sp_last_error().decode())
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+class _DevView:
+    """Borrowed device memory exposed through the CUDA array interface (torch wraps it without copying)."""
+
+    def __init__(self, ptr: int, shape, typestr: str):
+        self.__cuda_array_interface__ = {"shape": tuple(shape), "typestr": typestr, "data": (ptr, False), "version": 2}
+
+
+def _view(ptr, shape, typestr, dtype) -> torch.Tensor:
+    n = int(np.prod(shape))
+    if n == 0 or not ptr:
+        return torch.empty(tuple(shape), dtype=dtype, device="cuda")
+    return torch.as_tensor(_DevView(int(ptr), shape, typestr), device="cuda")
+
+
+class Coords:
+    """Owns one reference to an sp_coords_t."""
+
+    def __init__(self, handle):
+        self._h = handle
+        n, ts = C.c_int64(), C.c_int32()
+        _check(lib().sp_coords_size(self._h, C.byref(n), C.byref(ts)))
+        self.n, self.tensor_stride = n.value, ts.value
+
+    def _data(self):
+        pc, pi, nr = _vp(), _vp(), C.c_int64()
+        _check(lib().sp_coords_data(self._h, C.byref(pc), C.byref(pi), C.byref(nr)))
+        return pc.value, pi.value, nr.value
+
+    def coords(self) -> torch.Tensor:
+        """int32 [N][4] view of the distinct coordinates (borrowed: valid while this object lives)."""
+        pc, _, _ = self._data()
+        return _view(pc, (self.n, 4), "<i4", torch.int32)
+
+    def inverse(self) -> torch.Tensor:
+        """int32 [n_raw] view: distinct row each source row merged into."""
+        _, pi, nr = self._data()
+        return _view(pi, (nr,), "<i4", torch.int32)
+
+    def close(self):
+        if self._h:
+            lib().sp_coords_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class KMap:
+    """Owns an sp_kmap_t."""
+
+    def __init__(self, handle):
+        self._h = handle
+        ni, no, kv, tot = C.c_int64(), C.c_int64(), C.c_int32(), C.c_int64()
+        _check(lib().sp_kmap_info(self._h, C.byref(ni), C.byref(no), C.byref(kv), C.byref(tot), None))
+        self.n_in, self.n_out, self.kvol, self.total = ni.value, no.value, kv.value, tot.value
+        counts = np.zeros(self.kvol, dtype=np.int64)
+        _check(lib().sp_kmap_info(self._h, None, None, None, None, counts.ctypes.data_as(_vp)))
+        self.counts = counts
+
+    def pairs(self):
+        """(pair_in, pair_out): int32 [total] views, lists of all offsets concatenated in offset order."""
+        a, b = _vp(), _vp()
+        _check(lib().sp_kmap_pairs(self._h, C.byref(a), C.byref(b)))
+        return _view(a.value, (self.total,), "<i4", torch.int32), _view(b.value, (self.total,), "<i4", torch.int32)
+
+    def table(self):
+        """(nbr_out [kvol][n_out], nbr_in [kvol][n_in], out_reversed, in_reversed) views."""
+        a, b, ro, ri = _vp(), _vp(), C.c_int32(), C.c_int32()
+        _check(lib().sp_kmap_table(self._h, C.byref(a), C.byref(b), C.byref(ro), C.byref(ri)))
+        return (_view(a.value, (self.kvol, self.n_out), "<i4", torch.int32),
+                _view(b.value, (self.kvol, self.n_in), "<i4", torch.int32), bool(ro.value), bool(ri.value))
+
+    def close(self):
+        if self._h:
+            lib().sp_kmap_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def _need_cuda(t: torch.Tensor, dtype=None, name="tensor"):
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous CUDA tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}")
+
+
+def sp_coords_build(raw: torch.Tensor, tensor_stride: int = 1) -> Coords:
+    _need_cuda(raw, torch.int32, "raw")
+    if raw.ndim != 2 or raw.shape[1] != 4:
+        raise ValueError("raw must be [n][4] rows (b,x,y,z)")
+    h = _vp()
+    _check(lib().sp_coords_build(raw.data_ptr() if raw.numel() else None, raw.shape[0], tensor_stride, _stream(),
+                                 C.byref(h)))
+    return Coords(h)
+
+
+def sp_kmap_build(coords: Coords, kernel_size: int, stride: int = 1, dilation: int = 1):
+    """Returns (KMap, Coords of the output)."""
+    hk, hc = _vp(), _vp()
+    _check(lib().sp_kmap_build(coords._h, kernel_size, stride, dilation, _stream(), C.byref(hk), C.byref(hc)))
+    return KMap(hk), Coords(hc)
+
+
+def sp_kmap_transpose(kmap: KMap) -> KMap:
+    h = _vp()
+    _check(lib().sp_kmap_transpose(kmap._h, C.byref(h)))
+    return KMap(h)
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return SP_F32
+    if t.dtype == torch.bfloat16:
+        return SP_BF16
+    raise ValueError("features must be float32 or bfloat16")
+
+
+def sp_conv_fwd(kmap: KMap, x: torch.Tensor, w: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+    """y [n_out][cout] from x [n_in][cin], w [kvol][cout][cin]."""
+    _need_cuda(x, None, "x"), _need_cuda(w, x.dtype, "w")
+    kvol, cout, cin = w.shape
+    if kvol != kmap.kvol or tuple(x.shape) != (kmap.n_in, cin):
+        raise ValueError("shape mismatch between kmap, x and w")
+    y = out if out is not None else torch.empty((kmap.n_out, cout), dtype=x.dtype, device=x.device)
+    _need_cuda(y, x.dtype, "out")
+    if tuple(y.shape) != (kmap.n_out, cout):
+        raise ValueError("out has the wrong shape")
+    _check(lib().sp_conv_fwd(kmap._h, x.data_ptr(), w.data_ptr(), y.data_ptr(), cin, cout, _dt(x), _stream()))
+    return y
+
+
+def sp_conv_bwd_data(kmap: KMap, dy: torch.Tensor, w: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+    """dx [n_in][cin] from dy [n_out][cout], w [kvol][cout][cin]."""
+    _need_cuda(dy, None, "dy"), _need_cuda(w, dy.dtype, "w")
+    kvol, cout, cin = w.shape
+    if kvol != kmap.kvol or tuple(dy.shape) != (kmap.n_out, cout):
+        raise ValueError("shape mismatch between kmap, dy and w")
+    dx = out if out is not None else torch.empty((kmap.n_in, cin), dtype=dy.dtype, device=dy.device)
+    _need_cuda(dx, dy.dtype, "out")
+    if tuple(dx.shape) != (kmap.n_in, cin):
+        raise ValueError("out has the wrong shape")
+    _check(lib().sp_conv_bwd_data(kmap._h, dy.data_ptr(), w.data_ptr(), dx.data_ptr(), cin, cout, _dt(dy), _stream()))
+    return dx
+
+
+def sp_conv_bwd_weight(kmap: KMap, x: torch.Tensor, dy: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+    """dw fp32 [kvol][cout][cin] from x [n_in][cin], dy [n_out][cout]."""
+    _need_cuda(x, None, "x"), _need_cuda(dy, x.dtype, "dy")
+    cin, cout = x.shape[1], dy.shape[1]
+    if x.shape[0] != kmap.n_in or dy.shape[0] != kmap.n_out:
+        raise ValueError("shape mismatch between kmap, x and dy")
+    dw = out if out is not None else torch.empty((kmap.kvol, cout, cin), dtype=torch.float32, device=x.device)
+    _need_cuda(dw, torch.float32, "out")
+    if tuple(dw.shape) != (kmap.kvol, cout, cin):
+        raise ValueError("out has the wrong shape")
+    _check(lib().sp_conv_bwd_weight(kmap._h, x.data_ptr(), dy.data_ptr(), dw.data_ptr(), cin, cout, _dt(x), _stream()))
+    return dw
+
+
+def sp_pool_trim():
+    _check(lib().sp_pool_trim())
+
+
+def sp_pool_bytes() -> int:
+    return int(lib().sp_pool_bytes())
+
+
+def sp_version() -> str:
+    return lib().sp_version().decode()

@@ -1,0 +1,117 @@
+// Internal declarations shared by the library's translation units (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <memory>
+#include <vector>
+
+#include "sp_conv.h"
+
+namespace sp {
+
+// ---- errors -------------------------------------------------------------------------------------------
+void set_error(const char* fmt, ...);
+int fail(int code, const char* fmt, ...);
+
+#define SP_HIP(call)                                                                         \
+    do {                                                                                     \
+        hipError_t e_ = (call);                                                              \
+        if (e_ != hipSuccess) return sp::fail(SP_ERR_HIP, "%s: %s", #call, hipGetErrorString(e_)); \
+    } while (0)
+
+#define SP_TRY(expr)              \
+    do {                          \
+        int rc_ = (expr);         \
+        if (rc_ != SP_OK) return rc_; \
+    } while (0)
+
+// ---- device memory: size-class caching pool -------------------------------------------------------------
+// Blocks are handed back to the pool when the last owner drops them and may be reused by the next
+// allocation at once: correct as long as the work that used them and the work that reuses them are
+// ordered on one stream, which is the library's documented contract.
+struct DevBuf {
+    void* p = nullptr;
+    size_t bytes = 0;
+    ~DevBuf();
+};
+using Buf = std::shared_ptr<DevBuf>;
+Buf dev_alloc(size_t bytes);  // nullptr (and error set) on failure; bytes == 0 gives a valid tiny block
+template <class T>
+inline T* ptr(const Buf& b) { return b ? static_cast<T*>(b->p) : nullptr; }
+int pool_trim();
+int64_t pool_bytes();
+
+// Pinned host staging area for small read-backs (one per process, guarded by a mutex inside).
+int read_back(void* h_dst, const void* d_src, size_t bytes, hipStream_t s);  // async copy + stream sync
+
+// ---- hash table ---------------------------------------------------------------------------------------------
+struct HashTab {
+    Buf keys;          // uint64 [cap], EMPTY = ~0
+    Buf vals;          // int32  [cap], row index of the key
+    uint32_t cap = 0;  // power of two, >= 2 * entries
+};
+
+// ---- device-wide exclusive scan of int32 (sp_scan.hip) ---------------------------------------------------------
+// out[i] = sum_{j<i} in[j]; *d_total (device, may be null) = sum of all.  in == out allowed.  n >= 0.
+int exclusive_scan_i32(const int32_t* d_in, int32_t* d_out, int64_t n, int32_t* d_total, hipStream_t s);
+
+// ---- coords (sp_coords.hip) ---------------------------------------------------------------------------------------
+// Builds a coordinate set from d_src rows; floor_step > 1 floors x,y,z to multiples of it first.
+int coords_build_impl(const int32_t* d_src, int64_t n_src, int32_t floor_step, int32_t tensor_stride, hipStream_t s,
+                      sp_coords_t** out);
+
+constexpr int kTileRows = 256;   // rows per tile of the tile lists (= map-build block size)
+constexpr int kSubTiles = 4;     // 64-row sub-tiles (one wavefront ballot each) per tile
+
+}  // namespace sp
+
+struct sp_coords {
+    std::atomic<int> ref{1};
+    int64_t n = 0, n_raw = 0;
+    int32_t ts = 1;
+    sp::Buf coords;   // int32 [n][4]
+    sp::Buf inverse;  // int32 [n_raw]
+    sp::HashTab tab;
+};
+
+namespace sp {
+
+// One direction of a kernel map, as the gather-GEMM kernel consumes it: `n_rows` destination rows in tiles
+// of kTileRows; for (tile t, offset k, sub-tile q) the entries [off[(t*kvol+k)*4+q], off[(t*kvol+k)*4+q+1])
+// of src/row list the live (source row, destination row within the tile) links, destination rows ascending.
+struct MapSide {
+    int64_t n_rows = 0, n_src = 0;
+    Buf nbr;      // int32 [kvol][n_rows]: source row or -1
+    Buf tl_off;   // int32 [ntiles*kvol*4 + 1]
+    Buf tl_src;   // int32 [total]
+    Buf tl_row;   // uint16 [total]
+    bool flip = false;  // weight offset index = kvol-1-k (side derived by the stride-1 symmetry)
+};
+
+}  // namespace sp
+
+struct sp_kmap {
+    int64_t n_in = 0, n_out = 0, total = 0;
+    int32_t K = 0, kvol = 0, stride = 1, dilation = 1;
+    sp::MapSide out_side;  // destinations = output rows, sources = input rows   (forward)
+    sp::MapSide in_side;   // destinations = input rows,  sources = output rows  (data gradient)
+    sp::Buf pair_in, pair_out;  // int32 [total], offset-major
+    std::vector<int64_t> counts;   // [kvol]
+    std::vector<int64_t> koff;     // [kvol+1] exclusive prefix of counts
+    sp::Buf d_koff;                // int32 [kvol+1], the same prefix on the device
+    sp_coords* c_in = nullptr;     // references held
+    sp_coords* c_out = nullptr;
+};
+
+namespace sp {
+// conv launchers (sp_conv.hip / sp_wgrad.hip)
+int conv_gather(const MapSide& side, int kvol, const void* d_f, const void* d_w, bool w_transposed, void* d_g,
+                int cc, int co, sp_dtype dt, hipStream_t s);
+int conv_wgrad(const sp_kmap* m, const void* d_x, const void* d_dy, float* d_dw, int cin, int cout, sp_dtype dt,
+               hipStream_t s);
+}  // namespace sp

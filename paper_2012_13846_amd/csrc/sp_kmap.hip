@@ -1,0 +1,299 @@
+// Kernel maps (Sec. III-B step 2): for every kernel offset the (input row, output row) pairs it links,
+// found by probing the input coordinate set's hash table, then compacted with wavefront ballots and
+// prefix sums into (a) offset-major pair lists and (b) tile-major lists for the gather-GEMM kernels.
+#include "sp_hash.h"
+#include "sp_internal.h"
+
+namespace sp {
+namespace {
+
+constexpr int kThreads = kTileRows;  // one thread per row of a tile; 4 wavefronts = 4 sub-tiles
+
+__global__ __launch_bounds__(256) void fill_i32_kernel(int32_t* __restrict__ p, int64_t n, int32_t v) {
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// grid (tiles of n_out, kvol).  Thread (o, k) probes c_out[o] + offset_k * step in the input table.
+// Writes nbr_out[k][o]; scatters nbr_in[k][i] = o when nbr_in is given; counts live links per 64-row
+// sub-tile (sub_counts[(tile*kvol + k)*4 + wave]) and per tile (blk_counts[k*ntiles + tile]).
+__global__ __launch_bounds__(kThreads) void probe_kernel(const int4* __restrict__ c_out, int64_t n_out,
+                                                         const unsigned long long* __restrict__ keys,
+                                                         const int32_t* __restrict__ vals, uint32_t cap, int K,
+                                                         int step, int identity_k, int32_t* __restrict__ nbr_out,
+                                                         int32_t* __restrict__ nbr_in, int64_t n_in,
+                                                         int32_t* __restrict__ sub_counts,
+                                                         int32_t* __restrict__ blk_counts) {
+    __shared__ int s_cnt[kSubTiles];
+    const int k = blockIdx.y, kvol = gridDim.y;
+    const int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int az = k % K, ay = (k / K) % K, ax = k / (K * K);
+    const int centre = (K & 1) ? (K - 1) / 2 : 0;
+    int32_t v = -1;
+    if (o < n_out) {
+        if (k == identity_k) {
+            v = (int32_t)o;
+        } else {
+            int4 c = c_out[o];
+            uint64_t key;
+            if (pack_key(c.x, c.y + (ax - centre) * step, c.z + (ay - centre) * step, c.w + (az - centre) * step, &key))
+                v = hash_find(keys, vals, cap, key);
+        }
+        nbr_out[(int64_t)k * n_out + o] = v;
+        if (nbr_in && v >= 0) nbr_in[(int64_t)k * n_in + v] = (int32_t)o;
+    }
+    const unsigned long long live = __ballot(v >= 0);
+    const int w = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) {
+        int c = __popcll(live);
+        s_cnt[w] = c;
+        sub_counts[((int64_t)blockIdx.x * kvol + k) * kSubTiles + w] = c;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0 && blk_counts)
+        blk_counts[(int64_t)k * gridDim.x + blockIdx.x] = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
+}
+
+// Same counting from an existing table (the scattered input-side table of a strided map).
+__global__ __launch_bounds__(kThreads) void count_kernel(const int32_t* __restrict__ nbr, int64_t n_rows,
+                                                         int32_t* __restrict__ sub_counts) {
+    const int k = blockIdx.y, kvol = gridDim.y;
+    const int64_t r = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int32_t v = r < n_rows ? nbr[(int64_t)k * n_rows + r] : -1;
+    const unsigned long long live = __ballot(v >= 0);
+    if ((threadIdx.x & 63) == 0)
+        sub_counts[((int64_t)blockIdx.x * kvol + k) * kSubTiles + (threadIdx.x >> 6)] = __popcll(live);
+}
+
+// Compaction: every live (row, k) writes its entry at offset + (number of live lanes below it).
+__global__ __launch_bounds__(kThreads) void emit_kernel(const int32_t* __restrict__ nbr, int64_t n_rows,
+                                                        const int32_t* __restrict__ tl_off,
+                                                        int32_t* __restrict__ tl_src, uint16_t* __restrict__ tl_row,
+                                                        const int32_t* __restrict__ blk_off,
+                                                        int32_t* __restrict__ pair_in, int32_t* __restrict__ pair_out) {
+    __shared__ int s_cnt[kSubTiles];
+    const int k = blockIdx.y, kvol = gridDim.y;
+    const int64_t r = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int32_t v = r < n_rows ? nbr[(int64_t)k * n_rows + r] : -1;
+    const unsigned long long live = __ballot(v >= 0);
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int pos = __popcll(live & ((1ull << lane) - 1ull));
+    if (v >= 0) {
+        const int64_t e = (int64_t)tl_off[((int64_t)blockIdx.x * kvol + k) * kSubTiles + w] + pos;
+        tl_src[e] = v;
+        tl_row[e] = (uint16_t)threadIdx.x;
+    }
+    if (pair_in) {  // uniform branch
+        if (lane == 0) s_cnt[w] = __popcll(live);
+        __syncthreads();
+        int before = 0;
+        for (int j = 0; j < w; ++j) before += s_cnt[j];
+        if (v >= 0) {
+            const int64_t p = (int64_t)blk_off[(int64_t)k * gridDim.x + blockIdx.x] + before + pos;
+            pair_in[p] = v;
+            pair_out[p] = (int32_t)r;
+        }
+    }
+}
+
+__global__ void gather_koff_kernel(const int32_t* __restrict__ blk_off, int64_t ntiles, int kvol,
+                                   const int32_t* __restrict__ total, int32_t* __restrict__ koff) {
+    int k = threadIdx.x;
+    if (k < kvol) koff[k] = ntiles > 0 ? blk_off[(int64_t)k * ntiles] : 0;
+    if (k == kvol) koff[k] = ntiles > 0 ? *total : 0;
+}
+
+inline unsigned blocks256(int64_t n) { return (unsigned)((n + 255) / 256); }
+
+// Turns sub-tile counts (already in side.tl_off) into offsets and fills the tile lists.
+int finish_side(MapSide& side, int kvol, int64_t total, const int32_t* d_blk_off, int32_t* d_pair_in,
+                int32_t* d_pair_out, hipStream_t s) {
+    const int64_t ntiles = (side.n_rows + kTileRows - 1) / kTileRows;
+    side.tl_src = dev_alloc((size_t)(total ? total : 1) * 4);
+    side.tl_row = dev_alloc((size_t)(total ? total : 1) * 2);
+    if (!side.tl_src || !side.tl_row) return SP_ERR_ALLOC;
+    if (ntiles > 0 && total > 0)
+        hipLaunchKernelGGL(emit_kernel, dim3((unsigned)ntiles, kvol), dim3(kThreads), 0, s, ptr<int32_t>(side.nbr),
+                           side.n_rows, ptr<int32_t>(side.tl_off), ptr<int32_t>(side.tl_src),
+                           ptr<uint16_t>(side.tl_row), d_blk_off, d_pair_in, d_pair_out);
+    SP_HIP(hipGetLastError());
+    return SP_OK;
+}
+
+}  // namespace
+}  // namespace sp
+
+using namespace sp;
+
+extern "C" {
+
+int sp_kmap_build(const sp_coords_t* in, int32_t kernel_size, int32_t stride, int32_t dilation, void* stream,
+                  sp_kmap_t** kmap, sp_coords_t** out_coords) {
+    if (kmap) *kmap = nullptr;
+    if (out_coords) *out_coords = nullptr;
+    if (!in || !kmap) return fail(SP_ERR_INVALID_ARG, "coords handle or kmap out pointer is NULL");
+    if (kernel_size < 1 || kernel_size > 5) return fail(SP_ERR_INVALID_ARG, "kernel_size %d not in 1..5", kernel_size);
+    if (stride < 1 || dilation < 1) return fail(SP_ERR_INVALID_ARG, "stride and dilation must be >= 1");
+    if (stride > 1 && dilation > 1) return fail(SP_ERR_UNSUPPORTED, "dilation > 1 together with stride > 1");
+    if ((int64_t)in->ts * stride > 32768 || (int64_t)in->ts * dilation * kernel_size > 65536)
+        return fail(SP_ERR_RANGE, "tensor stride * stride / dilation leaves the packable coordinate range");
+    hipStream_t s = (hipStream_t)stream;
+    const int kvol = kernel_size * kernel_size * kernel_size;
+    if (in->n * (int64_t)kvol >= ((int64_t)1 << 31) - 4096)
+        return fail(SP_ERR_INVALID_ARG, "n * kernel volume exceeds 32-bit list offsets");
+
+    std::unique_ptr<sp_kmap, int (*)(sp_kmap*)> m(new sp_kmap, sp_kmap_destroy);
+    m->K = kernel_size;
+    m->kvol = kvol;
+    m->stride = stride;
+    m->dilation = dilation;
+    sp_coords* cin = const_cast<sp_coords*>(in);
+    cin->ref.fetch_add(1);
+    m->c_in = cin;
+    if (stride == 1) {
+        cin->ref.fetch_add(1);
+        m->c_out = cin;
+    } else {
+        sp_coords* co = nullptr;
+        SP_TRY(coords_build_impl(ptr<int32_t>(in->coords), in->n, in->ts * stride, in->ts * stride, s, &co));
+        m->c_out = co;
+    }
+    const int64_t n_in = in->n, n_out = m->c_out->n;
+    m->n_in = n_in;
+    m->n_out = n_out;
+    const bool symmetric = (stride == 1) && (kernel_size & 1);
+    const int64_t nt_out = (n_out + kTileRows - 1) / kTileRows, nt_in = (n_in + kTileRows - 1) / kTileRows;
+    const int step = dilation * in->ts;
+
+    MapSide& so = m->out_side;
+    so.n_rows = n_out;
+    so.n_src = n_in;
+    so.nbr = dev_alloc((size_t)(n_out ? n_out : 1) * kvol * 4);
+    so.tl_off = dev_alloc((size_t)(nt_out * kvol * kSubTiles + 1) * 4);
+    Buf blk = dev_alloc((size_t)(nt_out * kvol + 1) * 4);
+    Buf small = dev_alloc((size_t)(kvol + 2) * 4);  // [0..kvol] koff, [kvol+1] scratch total
+    if (!so.nbr || !so.tl_off || !blk || !small) return SP_ERR_ALLOC;
+    MapSide& si = m->in_side;
+    if (!symmetric) {
+        si.n_rows = n_in;
+        si.n_src = n_out;
+        si.nbr = dev_alloc((size_t)(n_in ? n_in : 1) * kvol * 4);
+        si.tl_off = dev_alloc((size_t)(nt_in * kvol * kSubTiles + 1) * 4);
+        if (!si.nbr || !si.tl_off) return SP_ERR_ALLOC;
+        if (n_in > 0)
+            hipLaunchKernelGGL(fill_i32_kernel, dim3(blocks256(n_in * kvol)), dim3(256), 0, s, ptr<int32_t>(si.nbr),
+                               n_in * kvol, -1);
+    }
+    int32_t* d_koff = ptr<int32_t>(small);
+    if (nt_out > 0) {
+        hipLaunchKernelGGL(probe_kernel, dim3((unsigned)nt_out, kvol), dim3(kThreads), 0, s,
+                           ptr<int4>(m->c_out->coords), n_out, ptr<unsigned long long>(in->tab.keys),
+                           ptr<int32_t>(in->tab.vals), in->tab.cap, kernel_size, step,
+                           symmetric ? (kvol - 1) / 2 : -1, ptr<int32_t>(so.nbr),
+                           symmetric ? (int32_t*)nullptr : ptr<int32_t>(si.nbr), n_in, ptr<int32_t>(so.tl_off),
+                           ptr<int32_t>(blk));
+    }
+    SP_HIP(hipGetLastError());
+    const int64_t n_sub = nt_out * kvol * kSubTiles;
+    SP_TRY(exclusive_scan_i32(ptr<int32_t>(so.tl_off), ptr<int32_t>(so.tl_off), n_sub, ptr<int32_t>(so.tl_off) + n_sub, s));
+    SP_TRY(exclusive_scan_i32(ptr<int32_t>(blk), ptr<int32_t>(blk), nt_out * kvol, d_koff + kvol + 1, s));
+    hipLaunchKernelGGL(gather_koff_kernel, dim3(1), dim3(128), 0, s, ptr<int32_t>(blk), nt_out, kvol,
+                       d_koff + kvol + 1, d_koff);
+    SP_HIP(hipGetLastError());
+    std::vector<int32_t> h_koff(kvol + 1);
+    SP_TRY(read_back(h_koff.data(), d_koff, (size_t)(kvol + 1) * 4, s));
+    m->koff.resize(kvol + 1);
+    m->counts.resize(kvol);
+    for (int k = 0; k <= kvol; ++k) m->koff[k] = h_koff[k];
+    for (int k = 0; k < kvol; ++k) m->counts[k] = m->koff[k + 1] - m->koff[k];
+    m->total = m->koff[kvol];
+    m->d_koff = small;
+
+    m->pair_in = dev_alloc((size_t)(m->total ? m->total : 1) * 4);
+    m->pair_out = dev_alloc((size_t)(m->total ? m->total : 1) * 4);
+    if (!m->pair_in || !m->pair_out) return SP_ERR_ALLOC;
+    SP_TRY(finish_side(so, kvol, m->total, ptr<int32_t>(blk), ptr<int32_t>(m->pair_in), ptr<int32_t>(m->pair_out), s));
+    if (symmetric) {
+        si = so;  // same lists; the link (i, o) at offset k is the link (o, i) at offset kvol-1-k
+        si.flip = true;
+    } else {
+        if (nt_in > 0)
+            hipLaunchKernelGGL(count_kernel, dim3((unsigned)nt_in, kvol), dim3(kThreads), 0, s, ptr<int32_t>(si.nbr),
+                               n_in, ptr<int32_t>(si.tl_off));
+        const int64_t n_sub_in = nt_in * kvol * kSubTiles;
+        SP_TRY(exclusive_scan_i32(ptr<int32_t>(si.tl_off), ptr<int32_t>(si.tl_off), n_sub_in,
+                                  ptr<int32_t>(si.tl_off) + n_sub_in, s));
+        SP_TRY(finish_side(si, kvol, m->total, nullptr, nullptr, nullptr, s));
+    }
+    if (out_coords) {
+        m->c_out->ref.fetch_add(1);
+        *out_coords = m->c_out;
+    }
+    *kmap = m.release();
+    return SP_OK;
+}
+
+int sp_kmap_transpose(const sp_kmap_t* f, sp_kmap_t** transposed) {
+    if (transposed) *transposed = nullptr;
+    if (!f || !transposed) return fail(SP_ERR_INVALID_ARG, "kmap handle or out pointer is NULL");
+    sp_kmap* t = new sp_kmap;
+    t->n_in = f->n_out;
+    t->n_out = f->n_in;
+    t->total = f->total;
+    t->K = f->K;
+    t->kvol = f->kvol;
+    t->stride = f->stride;
+    t->dilation = f->dilation;
+    t->out_side = f->in_side;
+    t->in_side = f->out_side;
+    t->pair_in = f->pair_out;
+    t->pair_out = f->pair_in;
+    t->counts = f->counts;
+    t->koff = f->koff;
+    t->d_koff = f->d_koff;
+    t->c_in = f->c_out;
+    t->c_out = f->c_in;
+    if (t->c_in) t->c_in->ref.fetch_add(1);
+    if (t->c_out) t->c_out->ref.fetch_add(1);
+    *transposed = t;
+    return SP_OK;
+}
+
+int sp_kmap_info(const sp_kmap_t* m, int64_t* n_in, int64_t* n_out, int32_t* kvol, int64_t* total_pairs,
+                 int64_t* h_counts) {
+    if (!m) return fail(SP_ERR_INVALID_ARG, "kmap handle is NULL");
+    if (n_in) *n_in = m->n_in;
+    if (n_out) *n_out = m->n_out;
+    if (kvol) *kvol = m->kvol;
+    if (total_pairs) *total_pairs = m->total;
+    if (h_counts)
+        for (int k = 0; k < m->kvol; ++k) h_counts[k] = m->counts[k];
+    return SP_OK;
+}
+
+int sp_kmap_pairs(const sp_kmap_t* m, const int32_t** d_pair_in, const int32_t** d_pair_out) {
+    if (!m) return fail(SP_ERR_INVALID_ARG, "kmap handle is NULL");
+    if (d_pair_in) *d_pair_in = ptr<int32_t>(m->pair_in);
+    if (d_pair_out) *d_pair_out = ptr<int32_t>(m->pair_out);
+    return SP_OK;
+}
+
+int sp_kmap_table(const sp_kmap_t* m, const int32_t** d_nbr_out, const int32_t** d_nbr_in, int32_t* out_reversed,
+                  int32_t* in_reversed) {
+    if (!m) return fail(SP_ERR_INVALID_ARG, "kmap handle is NULL");
+    if (d_nbr_out) *d_nbr_out = ptr<int32_t>(m->out_side.nbr);
+    if (d_nbr_in) *d_nbr_in = ptr<int32_t>(m->in_side.nbr);
+    if (out_reversed) *out_reversed = m->out_side.flip ? 1 : 0;
+    if (in_reversed) *in_reversed = m->in_side.flip ? 1 : 0;
+    return SP_OK;
+}
+
+int sp_kmap_destroy(sp_kmap_t* m) {
+    if (!m) return SP_OK;
+    sp_coords_destroy(m->c_in);
+    sp_coords_destroy(m->c_out);
+    delete m;
+    return SP_OK;
+}
+
+}  // extern "C"

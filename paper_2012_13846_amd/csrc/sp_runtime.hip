@@ -1,0 +1,175 @@
+// Host runtime of the library: error strings, the caching device-memory pool, pinned read-back staging.
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <string>
+
+#include "sp_internal.h"
+
+namespace sp {
+
+static thread_local std::string g_err;
+
+void set_error(const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+}
+
+int fail(int code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+// ---- pool -----------------------------------------------------------------------------------------------
+namespace {
+struct Pool {
+    std::mutex mu;
+    std::multimap<size_t, void*> free_blocks;  // size class -> block
+    std::map<void*, size_t> live;              // block -> size class
+    int64_t held = 0;
+
+    // Size classes: multiples of 1/8 of the power of two below the request (<= 12.5 % slack), min 512 B.
+    static size_t size_class(size_t b) {
+        if (b < 512) return 512;
+        size_t p = 512;
+        while ((p << 1) <= b) p <<= 1;
+        size_t g = p >> 3;
+        return (b + g - 1) / g * g;
+    }
+
+    void* alloc(size_t bytes) {
+        size_t c = size_class(bytes);
+        {
+            std::lock_guard<std::mutex> lk(mu);
+            auto it = free_blocks.find(c);
+            if (it != free_blocks.end()) {
+                void* p = it->second;
+                free_blocks.erase(it);
+                live[p] = c;
+                return p;
+            }
+        }
+        void* p = nullptr;
+        hipError_t e = hipMalloc(&p, c);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            trim();  // give cached blocks back and retry once
+            e = hipMalloc(&p, c);
+            if (e != hipSuccess) {
+                (void)hipGetLastError();
+                set_error("hipMalloc(%zu bytes) failed: %s", c, hipGetErrorString(e));
+                return nullptr;
+            }
+        }
+        std::lock_guard<std::mutex> lk(mu);
+        live[p] = c;
+        held += (int64_t)c;
+        return p;
+    }
+
+    void release(void* p) {
+        std::lock_guard<std::mutex> lk(mu);
+        auto it = live.find(p);
+        if (it == live.end()) return;
+        free_blocks.emplace(it->second, p);
+        live.erase(it);
+    }
+
+    int trim() {
+        std::multimap<size_t, void*> blocks;
+        {
+            std::lock_guard<std::mutex> lk(mu);
+            blocks.swap(free_blocks);
+        }
+        if (blocks.empty()) return SP_OK;
+        hipError_t e = hipDeviceSynchronize();
+        int64_t freed = 0;
+        for (auto& kv : blocks) {
+            (void)hipFree(kv.second);
+            freed += (int64_t)kv.first;
+        }
+        std::lock_guard<std::mutex> lk(mu);
+        held -= freed;
+        return e == hipSuccess ? SP_OK : fail(SP_ERR_HIP, "hipDeviceSynchronize: %s", hipGetErrorString(e));
+    }
+};
+
+Pool& pool() {
+    static Pool* p = new Pool;  // leaked on purpose: device memory goes with the process
+    return *p;
+}
+
+struct Stage {
+    std::mutex mu;
+    void* h = nullptr;
+    size_t bytes = 0;
+};
+Stage& stage() {
+    static Stage* s = new Stage;
+    return *s;
+}
+}  // namespace
+
+DevBuf::~DevBuf() {
+    if (p) pool().release(p);
+}
+
+Buf dev_alloc(size_t bytes) {
+    void* p = pool().alloc(bytes ? bytes : 1);
+    if (!p) return nullptr;
+    auto b = std::make_shared<DevBuf>();
+    b->p = p;
+    b->bytes = bytes;
+    return b;
+}
+
+int pool_trim() { return pool().trim(); }
+int64_t pool_bytes() {
+    std::lock_guard<std::mutex> lk(pool().mu);
+    return pool().held;
+}
+
+int read_back(void* h_dst, const void* d_src, size_t bytes, hipStream_t s) {
+    if (bytes == 0) {
+        SP_HIP(hipStreamSynchronize(s));
+        return SP_OK;
+    }
+    Stage& st = stage();
+    std::lock_guard<std::mutex> lk(st.mu);
+    if (st.bytes < bytes) {
+        if (st.h) (void)hipHostFree(st.h);
+        st.h = nullptr;
+        st.bytes = 0;
+        size_t want = bytes < 65536 ? 65536 : bytes;
+        hipError_t e = hipHostMalloc(&st.h, want, hipHostMallocDefault);
+        if (e != hipSuccess) {
+            st.h = nullptr;
+            return fail(SP_ERR_ALLOC, "hipHostMalloc(%zu): %s", want, hipGetErrorString(e));
+        }
+        st.bytes = want;
+    }
+    SP_HIP(hipMemcpyAsync(st.h, d_src, bytes, hipMemcpyDeviceToHost, s));
+    SP_HIP(hipStreamSynchronize(s));
+    memcpy(h_dst, st.h, bytes);
+    return SP_OK;
+}
+
+}  // namespace sp
+
+extern "C" {
+
+const char* sp_last_error(void) { return sp::g_err.c_str(); }
+int sp_pool_trim(void) { return sp::pool_trim(); }
+int64_t sp_pool_bytes(void) { return sp::pool_bytes(); }
+const char* sp_version(void) { return "sp_conv 0.1 (gfx950)"; }
+
+}  // extern "C"
