@@ -16,6 +16,7 @@ namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint16_t bf16_t;  // storage
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float((uint32_t)v << 16); }
@@ -36,6 +37,8 @@ struct GatherArgs {
     int kvol;
     int co_total;
     int flip;        // weight matrix of list k is kvol-1-k
+    int lds_per_wave;  // bytes of LDS of one wavefront in gather_wave_kernel
+    int w_transposed;  // host-side only: the stored weights are [k][cc][co] (data gradient) instead of [k][co][cc]
 };
 
 // ---------------------------------------------------------------------------------------------------------
@@ -76,7 +79,7 @@ __global__ __launch_bounds__(256) void gather_mma_kernel(GatherArgs a) {
     const int n16 = lane & 15, g = lane >> 4;
     constexpr int kPerTile = kTileRows / TR;             // workgroups per 256-row tile
     const int64_t tile = blockIdx.x / kPerTile;
-    const int q0 = (blockIdx.x % kPerTile) * (TR / 64);  // first 64-row sub-tile of this workgroup
+    const int q0 = (blockIdx.x % kPerTile) * (TR / 64);  // first 64-row sub-tile inside the 256-row tile
     constexpr int kNQ = TR / 64;
     const int co0 = blockIdx.y * COT;
 
@@ -85,10 +88,24 @@ __global__ __launch_bounds__(256) void gather_mma_kernel(GatherArgs a) {
     const T* __restrict__ F = static_cast<const T*>(a.f);
     const T* __restrict__ W = static_cast<const T*>(a.w);
 
+    const int64_t wt0 = (int64_t)blockIdx.x * kNQ;       // first 64-row sub-tile of this workgroup
     for (int kk = 0; kk < a.kvol; ++kk) {
-        const int64_t ob = (tile * a.kvol + kk) * kSubTiles + q0;
-        const int beg = a.tl_off[ob], end = a.tl_off[ob + kNQ];
-        if (beg == end) continue;
+        // the lists are sub-tile-major: this workgroup's links of offset kk are kNQ separate segments
+        int sb[kNQ], sl[kNQ], mtot = 0;
+#pragma unroll
+        for (int q = 0; q < kNQ; ++q) {
+            sb[q] = a.tl_off[(wt0 + q) * a.kvol + kk];
+            sl[q] = a.tl_off[(wt0 + q) * a.kvol + kk + 1] - sb[q];
+            mtot += sl[q];
+        }
+        if (mtot == 0) continue;
+        auto entry = [&](int p) {
+            int q = 0;
+#pragma unroll
+            for (int j = 0; j < kNQ - 1; ++j)
+                if (q == j && p >= sl[j]) { p -= sl[j]; ++q; }
+            return sb[q] + p;
+        };
         const int wk = a.flip ? a.kvol - 1 - kk : kk;
         // this wavefront's weight slice: B[cc][n16] = W[wk][co0 + cs*16 + n16][cc]
         const T* wrow = W + ((size_t)wk * a.co_total + co0 + cs * 16 + n16) * CC;
@@ -101,17 +118,17 @@ __global__ __launch_bounds__(256) void gather_mma_kernel(GatherArgs a) {
             else
                 bh[s] = *reinterpret_cast<const bf16x8*>(wrow + s * 32 + g * 8);
         }
-        for (int c0 = beg; c0 < end; c0 += Cfg::kChunk) {
-            const int m = min(Cfg::kChunk, end - c0);
+        for (int c0 = 0; c0 < mtot; c0 += Cfg::kChunk) {
+            const int m = min(Cfg::kChunk, mtot - c0);
             __syncthreads();  // everyone is done with the previous staging buffer and its accumulator updates
             for (int idx = tid; idx < m * Cfg::kPiecesPerRow; idx += 256) {
                 const int p = idx / Cfg::kPiecesPerRow, piece = idx % Cfg::kPiecesPerRow;
-                const int32_t src = a.tl_src[c0 + p];
+                const int32_t src = a.tl_src[entry(c0 + p)];
                 const uint4 v = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(F) +
                                                                 ((size_t)src * CC * Cfg::kElt + piece * 16));
                 *reinterpret_cast<uint4*>(abuf + (size_t)p * Cfg::kRowBytes + piece * 16) = v;
             }
-            if (tid < m) s_row[tid] = (uint16_t)(a.tl_row[c0 + tid] - q0 * 64);
+            if (tid < m) s_row[tid] = (uint16_t)(a.tl_row[entry(c0 + tid)] - q0 * 64);
             __syncthreads();
             const int nblk = (m + 15) >> 4;
             for (int blk = bs; blk < nblk; blk += Cfg::kNBS) {
@@ -160,6 +177,290 @@ __global__ __launch_bounds__(256) void gather_mma_kernel(GatherArgs a) {
     }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// Narrow-channel variant: every wavefront owns 64 destination rows (one sub-tile) and all COT channels of a
+// channel tile, and runs on its own: no workgroup barrier anywhere.  Its links of all offsets are one
+// contiguous stretch of the sub-tile-major lists.
+//
+//  - The wavefront first cuts its links into blocks of up to 16 links of one offset and writes one packed
+//    descriptor per block into LDS, so that block b+n is addressable without walking a cursor.
+//  - Everything a block needs is requested well ahead of its use and kept in registers: link entries
+//    (source row, destination row) 2*kDepth blocks ahead, the gathered source rows kDepth blocks ahead,
+//    the next offset's weight matrix while the current one is in use.
+//  - Source rows are gathered with coalesced 16-byte loads (adjacent lanes = adjacent pieces of one row; a
+//    fragment-shaped global load would cost one L1 tag lookup per lane) and pass through a small
+//    wavefront-private LDS buffer to be re-read as MFMA fragments, one block ahead of the MFMAs using them.
+//  - The offset's weight matrix is the MFMA A operand (rows = destination channels), read from a
+//    fragment-major copy of the weights so that one wavefront load is 1 KB of consecutive bytes.
+//  - The gathered rows are the B operand (columns = links), so the product comes out transposed: a lane
+//    holds 4 consecutive channels of ONE link and adds them with one 16-byte LDS read-modify-write to that
+//    link's destination row in the wavefront's private fp32 accumulator.
+// ---------------------------------------------------------------------------------------------------------
+template <typename T, int CC, int COT>
+struct WaveCfg {
+    static constexpr bool kIsF32 = std::is_same<T, float>::value;
+    static constexpr int kGroup = kIsF32 ? 16 : 32;       // contraction channels per 16-byte fragment group
+    static constexpr int kGroups = CC / kGroup;
+    static constexpr int kNCT = COT / 16;
+    static constexpr int kStride = COT + 4;               // floats per accumulator row
+    static constexpr int kAccBytes = 64 * kStride * 4;
+    static constexpr int kRowBytes = CC * (int)sizeof(T); // one source row
+    static constexpr int kPieces = kRowBytes / 16;        // 16-byte pieces per source row
+    static constexpr int kXStride = kRowBytes + 16;       // staged row + pad
+    static constexpr int kXBytes = 16 * kXStride;
+    static constexpr int kXLoads = (16 * kPieces + 63) / 64;  // coalesced load instructions per 16-link block
+    static int per_wave_bytes(int kvol) { return kAccBytes + kXBytes + ((kvol * 4 + 3) / 4) * 16; }
+    // fragment-major weights: [kvol][co_total/COT][kNCT][kGroups][64 lanes][16 bytes]
+    static constexpr size_t kWFragBytesPerOffsetTile = (size_t)kNCT * kGroups * 64 * 16;
+};
+
+__device__ __forceinline__ void wave_sync() {
+    // LDS traffic of one wavefront is processed in order; this only stops the compiler from moving
+    // the wavefront's own LDS accesses across the point.
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+constexpr int kWavesPerGroup = 1;  // wavefronts are independent; small groups give the scheduler the most freedom
+
+template <typename T, int CC, int COT>
+__global__ __launch_bounds__(64 * kWavesPerGroup) void gather_wave_kernel(GatherArgs a) {
+    using Cfg = WaveCfg<T, CC, COT>;
+    constexpr bool kIsF32 = Cfg::kIsF32;
+    constexpr int kGroups = Cfg::kGroups, kNCT = Cfg::kNCT, kPieces = Cfg::kPieces, kXLoads = Cfg::kXLoads;
+    using Frag = typename std::conditional<kIsF32, f32x4, bf16x8>::type;  // 16 bytes
+    static_assert(CC % Cfg::kGroup == 0, "contraction channels must fill whole fragment groups");
+    static_assert(kPieces % 4 == 0, "a source row must be a multiple of 64 bytes");
+    constexpr int kDepth = 3;  // blocks whose gathers are in flight
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t wt = (int64_t)blockIdx.x * kWavesPerGroup + wave;  // this wavefront's sub-tile
+    if (wt >= (a.n_rows + 63) / 64) return;             // whole wavefront leaves; nobody waits for it
+    unsigned char* base = smem + (size_t)wave * a.lds_per_wave;
+    float* acc = reinterpret_cast<float*>(base);
+    unsigned char* xbuf = base + Cfg::kAccBytes;
+    int* s_blk = reinterpret_cast<int*>(xbuf + Cfg::kXBytes);
+    const int n16 = lane & 15, g = lane >> 4;
+    const int kvol = a.kvol;
+
+    for (int i = lane; i < Cfg::kAccBytes / 16; i += 64) reinterpret_cast<f32x4*>(acc)[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // ---- block descriptors: k | (links-1) << 7 | (blocks left in this offset - 1) << 11 | (first link - off0) << 13
+    const int32_t* __restrict__ offp = a.tl_off + wt * kvol;
+    const int off0 = offp[0];
+    int nblk = 0;
+    for (int kb = 0; kb < kvol; kb += 64) {
+        const int k = kb + lane;
+        const int o0 = k < kvol ? offp[k] : 0, o1 = k < kvol ? offp[k + 1] : 0;
+        const int cnt = o1 - o0, nb = (cnt + 15) >> 4;
+        int inc = nb;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int t = __shfl_up(inc, d, 64);
+            if (lane >= d) inc += t;
+        }
+        const int ex = nblk + inc - nb;
+        for (int i = 0; i < nb; ++i)
+            s_blk[ex + i] = k | ((min(16, cnt - 16 * i) - 1) << 7) | ((nb - i - 1) << 11) | ((o0 - off0 + 16 * i) << 13);
+        nblk += __shfl(inc, 63, 64);
+    }
+    wave_sync();
+
+    const unsigned char* __restrict__ F = static_cast<const unsigned char*>(a.f);
+    const unsigned char* __restrict__ WF = static_cast<const unsigned char*>(a.w) +
+                                           (size_t)blockIdx.y * Cfg::kWFragBytesPerOffsetTile + (size_t)lane * 16;
+    const size_t w_offset_stride = (size_t)(a.co_total / COT) * Cfg::kWFragBytesPerOffsetTile;
+    const int32_t* __restrict__ tl_src = a.tl_src;
+    const uint16_t* __restrict__ tl_row = a.tl_row;
+
+    auto load_weights = [&](int k, Frag (&wf)[kNCT][kGroups]) __attribute__((always_inline)) {
+        const int wk = a.flip ? kvol - 1 - k : k;
+        const unsigned char* p = WF + (size_t)wk * w_offset_stride;
+#pragma unroll
+        for (int ct = 0; ct < kNCT; ++ct)
+#pragma unroll
+            for (int s = 0; s < kGroups; ++s)
+                wf[ct][s] = *reinterpret_cast<const Frag*>(p + (size_t)(ct * kGroups + s) * 1024);
+    };
+
+    // The main loop is straight-line code with the same loads in every turn (blocks past the end are
+    // clamped to the last one and their results dropped): the compiler can then count outstanding loads
+    // exactly and wait only for the oldest, instead of draining the whole prefetch queue at every branch.
+    struct Slot {
+        int dc;                   // descriptor of the block whose gathered rows / weights are in x / w
+        int drow;                 // destination row of that block's link n16
+        int de;                   // descriptor of the block whose entries are in esrc / erow
+        int esrc[kXLoads];        // source row of the link this lane gathers a piece of, per load
+        int erow;                 // destination row of link n16
+        u32x4 x[kXLoads];         // gathered pieces, coalesced layout: piece (t*64 + lane) of the block
+        Frag w[kNCT][kGroups];    // the block's weight matrix
+    };
+    const int last = nblk - 1;
+    auto load_entries = [&](Slot& sl, int b) __attribute__((always_inline)) {
+        sl.de = s_blk[min(b, last)];
+        const int cnt = ((sl.de >> 7) & 15) + 1, e0 = off0 + (sl.de >> 13);
+#pragma unroll
+        for (int t = 0; t < kXLoads; ++t) sl.esrc[t] = tl_src[e0 + min((t * 64 + lane) / kPieces, cnt - 1)];
+        sl.erow = tl_row[e0 + min(n16, cnt - 1)];
+    };
+    auto issue_gather = [&](Slot& sl) __attribute__((always_inline)) {
+        sl.dc = sl.de;
+        sl.drow = sl.erow & 63;
+#pragma unroll
+        for (int t = 0; t < kXLoads; ++t)
+            sl.x[t] = *reinterpret_cast<const u32x4*>(F + (size_t)sl.esrc[t] * Cfg::kRowBytes +
+                                                       ((t * 64 + lane) % kPieces) * 16);
+        load_weights(sl.dc & 127, sl.w);
+    };
+    auto stage = [&](const Slot& sl) __attribute__((always_inline)) {  // gathered rows -> LDS, row-major, padded
+#pragma unroll
+        for (int t = 0; t < kXLoads; ++t) {
+            const int idx = t * 64 + lane;
+            *reinterpret_cast<u32x4*>(xbuf + (idx / kPieces) * Cfg::kXStride + (idx % kPieces) * 16) = sl.x[t];
+        }
+    };
+    auto read_frags = [&](Frag (&xf)[kGroups]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int s = 0; s < kGroups; ++s)
+            xf[s] = *reinterpret_cast<const Frag*>(xbuf + n16 * Cfg::kXStride + s * 64 + g * 16);
+    };
+
+    static_assert(kDepth == 3, "three named slots");
+    if (nblk > 0) {
+        Slot slot0 = {}, slot1 = {}, slot2 = {};
+        load_entries(slot0, 0);
+        load_entries(slot1, 1);
+        load_entries(slot2, 2);
+        issue_gather(slot0);
+        issue_gather(slot1);
+        issue_gather(slot2);
+        load_entries(slot0, 3);
+        load_entries(slot1, 4);
+        load_entries(slot2, 5);
+        Frag xf_c[kGroups];
+        stage(slot0);
+        wave_sync();
+        read_frags(xf_c);
+        wave_sync();
+
+        // one block: sl holds block b, sn holds block b + 1
+        auto body = [&](int b, Slot& sl, const Slot& sn) __attribute__((always_inline)) {
+            const int cnt = ((sl.dc >> 7) & 15) + 1;
+            const bool valid = n16 < cnt;
+            float* dst = acc + sl.drow * Cfg::kStride + g * 4;
+            stage(sn);  // the next block's rows (this block's fragments are already in registers)
+            wave_sync();
+            f32x4 av[kNCT];
+#pragma unroll
+            for (int ct = 0; ct < kNCT; ++ct) av[ct] = *reinterpret_cast<f32x4*>(dst + ct * 16);
+            Frag xf_n[kGroups];
+            read_frags(xf_n);
+
+            f32x4 d[kNCT];
+#pragma unroll
+            for (int ct = 0; ct < kNCT; ++ct) d[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < kGroups; ++s)
+#pragma unroll
+                for (int ct = 0; ct < kNCT; ++ct) {
+                    if constexpr (kIsF32) {
+                        d[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(sl.w[ct][s][0], xf_c[s][0], d[ct], 0, 0, 0);
+                        d[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(sl.w[ct][s][1], xf_c[s][1], d[ct], 0, 0, 0);
+                        d[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(sl.w[ct][s][2], xf_c[s][2], d[ct], 0, 0, 0);
+                        d[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(sl.w[ct][s][3], xf_c[s][3], d[ct], 0, 0, 0);
+                    } else {
+                        d[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sl.w[ct][s], xf_c[s], d[ct], 0, 0, 0);
+                    }
+                }
+            issue_gather(sl);               // block b + kDepth: its entries arrived a turn ago
+            load_entries(sl, b + 2 * kDepth);
+            // d[ct][i] = channel ct*16 + 4*g + i of link e0 + n16
+            if (valid) {
+#pragma unroll
+                for (int ct = 0; ct < kNCT; ++ct) *reinterpret_cast<f32x4*>(dst + ct * 16) = av[ct] + d[ct];
+            }
+#pragma unroll
+            for (int s = 0; s < kGroups; ++s) xf_c[s] = xf_n[s];
+        };
+        for (int b = 0; b < nblk; b += 3) {
+            body(b, slot0, slot1);
+            if (b + 1 >= nblk) break;
+            body(b + 1, slot1, slot2);
+            if (b + 2 >= nblk) break;
+            body(b + 2, slot2, slot0);
+        }
+    }
+    wave_sync();
+    const int co0 = blockIdx.y * COT;
+    constexpr int kQuads = COT / 4;
+    for (int idx = lane; idx < 64 * kQuads; idx += 64) {
+        const int r = idx / kQuads, c4 = (idx % kQuads) * 4;
+        const int64_t row = wt * 64 + r;
+        if (row >= a.n_rows) break;
+        const f32x4 v = *reinterpret_cast<const f32x4*>(acc + r * Cfg::kStride + c4);
+        if constexpr (kIsF32) {
+            *reinterpret_cast<f32x4*>(static_cast<float*>(a.g) + row * a.co_total + co0 + c4) = v;
+        } else {
+            ushort4 o;
+            o.x = f32_to_bf16(v[0]);
+            o.y = f32_to_bf16(v[1]);
+            o.z = f32_to_bf16(v[2]);
+            o.w = f32_to_bf16(v[3]);
+            *reinterpret_cast<ushort4*>(static_cast<bf16_t*>(a.g) + row * a.co_total + co0 + c4) = o;
+        }
+    }
+}
+
+// Weights as stored (element (k, co, cc) at w[k*per + co*s_co + cc*s_cc]) -> fragment-major copy for
+// gather_wave_kernel: [k][co tile][ct][s][lane = n16 + 16*g][16 bytes] holding channels
+// co = tile*COT + ct*16 + n16, cc = s*kGroup + g*(kGroup/4) + 0..kGroup/4-1.
+template <typename T, int CC, int COT>
+__global__ __launch_bounds__(256) void weight_frag_kernel(const T* __restrict__ w, T* __restrict__ wf, int kvol,
+                                                          int co_total, int s_co, int s_cc) {
+    using Cfg = WaveCfg<T, CC, COT>;
+    constexpr int kPer = Cfg::kGroup / 4;  // elements per 16-byte fragment
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t total = (int64_t)kvol * co_total * CC;
+    if (idx >= total) return;
+    int64_t r = idx;
+    const int i = (int)(r % kPer); r /= kPer;
+    const int lane = (int)(r % 64); r /= 64;
+    const int s = (int)(r % Cfg::kGroups); r /= Cfg::kGroups;
+    const int ct = (int)(r % Cfg::kNCT); r /= Cfg::kNCT;
+    const int tile = (int)(r % (co_total / COT)); r /= (co_total / COT);
+    const int k = (int)r;
+    const int co = tile * COT + ct * 16 + (lane & 15);
+    const int cc = s * Cfg::kGroup + (lane >> 4) * kPer + i;
+    wf[idx] = w[(size_t)k * co_total * CC + (size_t)co * s_co + (size_t)cc * s_cc];
+}
+
+template <typename T, int CC, int COT>
+int launch_wave(GatherArgs a, hipStream_t s) {
+    using Cfg = WaveCfg<T, CC, COT>;
+    auto kern = gather_wave_kernel<T, CC, COT>;
+    a.lds_per_wave = Cfg::per_wave_bytes(a.kvol);
+    const int lds = kWavesPerGroup * a.lds_per_wave;
+    static int attr_lds = 0;  // largest dynamic LDS size opted into so far
+    if (lds > attr_lds) {
+        SP_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+        attr_lds = lds;
+    }
+    // fragment-major copy of the weights (also undoes the data gradient's transposition)
+    const int64_t n = (int64_t)a.kvol * a.co_total * CC;
+    Buf wf = dev_alloc((size_t)n * sizeof(T));
+    if (!wf) return SP_ERR_ALLOC;
+    const int s_co = a.w_transposed ? 1 : CC, s_cc = a.w_transposed ? a.co_total : 1;
+    hipLaunchKernelGGL((weight_frag_kernel<T, CC, COT>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
+                       static_cast<const T*>(a.w), ptr<T>(wf), a.kvol, a.co_total, s_co, s_cc);
+    a.w = wf->p;
+    const int64_t nwt = (a.n_rows + 63) / 64;
+    dim3 grid((unsigned)((nwt + kWavesPerGroup - 1) / kWavesPerGroup), (unsigned)(a.co_total / COT));
+    hipLaunchKernelGGL(kern, grid, dim3(64 * kWavesPerGroup), lds, s, a);
+    SP_HIP(hipGetLastError());
+    return SP_OK;  // wf goes back to the pool; later users are ordered behind this launch on the stream
+}
+
 // Plain kernel for channel counts the matrix-core kernel does not take: one thread per (row, channel),
 // walking the neighbour table.  Weights as stored, W[kvol][cout][cin]; (w_cc, w_co) are the element strides
 // of the contraction / destination channel inside one offset's matrix.
@@ -205,7 +506,7 @@ __global__ __launch_bounds__(256) void transpose_w_kernel(const T* __restrict__ 
 }
 
 template <typename T, int CC, int COT, int TR>
-int launch_gather(const GatherArgs& a, hipStream_t s) {
+int launch_gather(GatherArgs a, hipStream_t s) {
     using Cfg = GatherCfg<T, CC, COT, TR>;
     auto kern = gather_mma_kernel<T, CC, COT, TR>;
     static bool attr_set = false;  // one-time opt-in to > 64 KB of dynamic LDS
@@ -213,6 +514,15 @@ int launch_gather(const GatherArgs& a, hipStream_t s) {
         SP_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                    (int)Cfg::kLds));
         attr_set = true;
+    }
+    Buf wt;
+    if (a.w_transposed) {  // stored matrix is [cout = cc][cin = co]; the kernel wants [co][cc]
+        const int64_t n = (int64_t)a.kvol * CC * a.co_total;
+        wt = dev_alloc((size_t)n * sizeof(T));
+        if (!wt) return SP_ERR_ALLOC;
+        hipLaunchKernelGGL(transpose_w_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
+                           static_cast<const T*>(a.w), ptr<T>(wt), a.kvol, CC, a.co_total);
+        a.w = wt->p;
     }
     const int64_t ntiles = (a.n_rows + kTileRows - 1) / kTileRows;
     dim3 grid((unsigned)(ntiles * (kTileRows / TR)), (unsigned)(a.co_total / COT));
@@ -223,7 +533,17 @@ int launch_gather(const GatherArgs& a, hipStream_t s) {
 
 template <typename T, int CC>
 int dispatch_co(const GatherArgs& a, hipStream_t s) {
-    // rows per workgroup: keep the accumulator + staging within ~64 KB so two workgroups share a CU
+    // Narrow layers: the wavefront-private kernel, with the widest channel tile whose weight matrix fits
+    // in 32 fragment registers (CC/group * COT/16 fragments of 4 registers each).
+    constexpr int kGroups = CC / (std::is_same<T, float>::value ? 16 : 32);
+    if constexpr (kGroups * 4 <= 8)
+        if (a.co_total % 64 == 0) return launch_wave<T, CC, 64>(a, s);
+    if constexpr (kGroups * 2 <= 8)
+        if (a.co_total % 32 == 0) return launch_wave<T, CC, 32>(a, s);
+    if constexpr (kGroups <= 2)
+        if (a.co_total == 16 || a.co_total == 48) return launch_wave<T, CC, 16>(a, s);
+    // Wide layers: workgroup-cooperative kernel; rows per workgroup keep accumulator + staging within
+    // ~64 KB so two workgroups share a CU
     if (a.co_total % 64 == 0) return launch_gather<T, CC, 64, 128>(a, s);
     if (a.co_total % 32 == 0) return launch_gather<T, CC, 32, 128>(a, s);
     return launch_gather<T, CC, 16, 128>(a, s);
@@ -257,29 +577,14 @@ bool mma_shape_ok(int cc, int co, sp_dtype dt) {
 int conv_gather(const MapSide& side, int kvol, const void* d_f, const void* d_w, bool w_transposed, void* d_g, int cc,
                 int co, sp_dtype dt, hipStream_t s) {
     if (side.n_rows == 0) return SP_OK;
-    const size_t elt = dt == SP_F32 ? 4 : 2;
     if (mma_shape_ok(cc, co, dt)) {
-        Buf wt;
-        const void* w_use = d_w;
-        if (w_transposed) {
-            const int64_t n = (int64_t)kvol * cc * co;
-            wt = dev_alloc((size_t)n * elt);
-            if (!wt) return SP_ERR_ALLOC;
-            // stored matrix is [cout = cc][cin = co]; the kernel wants [co][cc]
-            if (dt == SP_F32)
-                hipLaunchKernelGGL(transpose_w_kernel<float>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
-                                   static_cast<const float*>(d_w), ptr<float>(wt), kvol, cc, co);
-            else
-                hipLaunchKernelGGL(transpose_w_kernel<bf16_t>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
-                                   static_cast<const bf16_t*>(d_w), ptr<bf16_t>(wt), kvol, cc, co);
-            w_use = wt->p;
-        }
         GatherArgs a;
         a.tl_off = ptr<int32_t>(side.tl_off);
         a.tl_src = ptr<int32_t>(side.tl_src);
         a.tl_row = ptr<uint16_t>(side.tl_row);
         a.f = d_f;
-        a.w = w_use;
+        a.w = d_w;
+        a.w_transposed = w_transposed ? 1 : 0;
         a.g = d_g;
         a.n_rows = side.n_rows;
         a.kvol = kvol;

@@ -82,12 +82,12 @@ struct sp_coords {
 namespace sp {
 
 // One direction of a kernel map, as the gather-GEMM kernel consumes it: `n_rows` destination rows in tiles
-// of kTileRows; for (tile t, offset k, sub-tile q) the entries [off[(t*kvol+k)*4+q], off[(t*kvol+k)*4+q+1])
+// of kTileRows; for (64-row sub-tile u, offset k) the entries [off[u*kvol+k], off[u*kvol+k+1])
 // of src/row list the live (source row, destination row within the tile) links, destination rows ascending.
 struct MapSide {
     int64_t n_rows = 0, n_src = 0;
     Buf nbr;      // int32 [kvol][n_rows]: source row or -1
-    Buf tl_off;   // int32 [ntiles*kvol*4 + 1]
+    Buf tl_off;   // int32 [nsub*kvol + 1], nsub = 4*ntiles, index sub*kvol + k (sub-tile-major)
     Buf tl_src;   // int32 [total]
     Buf tl_row;   // uint16 [total]
     bool flip = false;  // weight offset index = kvol-1-k (side derived by the stride-1 symmetry)

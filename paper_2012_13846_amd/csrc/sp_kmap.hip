@@ -16,7 +16,7 @@ __global__ __launch_bounds__(256) void fill_i32_kernel(int32_t* __restrict__ p, 
 
 // grid (tiles of n_out, kvol).  Thread (o, k) probes c_out[o] + offset_k * step in the input table.
 // Writes nbr_out[k][o]; scatters nbr_in[k][i] = o when nbr_in is given; counts live links per 64-row
-// sub-tile (sub_counts[(tile*kvol + k)*4 + wave]) and per tile (blk_counts[k*ntiles + tile]).
+// sub-tile (sub_counts[(tile*4 + wave)*kvol + k]) and per tile (blk_counts[k*ntiles + tile]).
 __global__ __launch_bounds__(kThreads) void probe_kernel(const int4* __restrict__ c_out, int64_t n_out,
                                                          const unsigned long long* __restrict__ keys,
                                                          const int32_t* __restrict__ vals, uint32_t cap, int K,
@@ -47,7 +47,7 @@ __global__ __launch_bounds__(kThreads) void probe_kernel(const int4* __restrict_
     if ((threadIdx.x & 63) == 0) {
         int c = __popcll(live);
         s_cnt[w] = c;
-        sub_counts[((int64_t)blockIdx.x * kvol + k) * kSubTiles + w] = c;
+        sub_counts[((int64_t)blockIdx.x * kSubTiles + w) * kvol + k] = c;
     }
     __syncthreads();
     if (threadIdx.x == 0 && blk_counts)
@@ -62,7 +62,7 @@ __global__ __launch_bounds__(kThreads) void count_kernel(const int32_t* __restri
     const int32_t v = r < n_rows ? nbr[(int64_t)k * n_rows + r] : -1;
     const unsigned long long live = __ballot(v >= 0);
     if ((threadIdx.x & 63) == 0)
-        sub_counts[((int64_t)blockIdx.x * kvol + k) * kSubTiles + (threadIdx.x >> 6)] = __popcll(live);
+        sub_counts[((int64_t)blockIdx.x * kSubTiles + (threadIdx.x >> 6)) * kvol + k] = __popcll(live);
 }
 
 // Compaction: every live (row, k) writes its entry at offset + (number of live lanes below it).
@@ -79,7 +79,7 @@ __global__ __launch_bounds__(kThreads) void emit_kernel(const int32_t* __restric
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int pos = __popcll(live & ((1ull << lane) - 1ull));
     if (v >= 0) {
-        const int64_t e = (int64_t)tl_off[((int64_t)blockIdx.x * kvol + k) * kSubTiles + w] + pos;
+        const int64_t e = (int64_t)tl_off[((int64_t)blockIdx.x * kSubTiles + w) * kvol + k] + pos;
         tl_src[e] = v;
         tl_row[e] = (uint16_t)threadIdx.x;
     }
