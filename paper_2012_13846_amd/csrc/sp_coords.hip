@@ -1,5 +1,10 @@
 // Coordinate sets: hash insertion, duplicate merging in first-occurrence order, strided (coarser)
 // coordinate generation.  Sec. III-B: sparse tensor definition and step 1.
+//
+// Five launches: fill the table; insert every row (slot.first = smallest row carrying the key); count the
+// first occurrences per 1024-row block; number them (each block adds up the counts of the blocks before
+// it, then ranks its own rows with ballots) and write coordinates + row numbers; read the row numbers
+// back per source row (the inverse map).
 #include "sp_hash.h"
 #include "sp_internal.h"
 
@@ -7,6 +12,8 @@ namespace sp {
 namespace {
 
 constexpr int kThreads = 256;
+constexpr int kRowsPerThread = 4;
+constexpr int kBlockRows = kThreads * kRowsPerThread;  // rows numbered by one block
 
 __device__ __forceinline__ int32_t floor_to_multiple(int32_t v, int32_t s) {
     int32_t q = v / s;
@@ -14,88 +21,138 @@ __device__ __forceinline__ int32_t floor_to_multiple(int32_t v, int32_t s) {
     return q * s;
 }
 
-__global__ __launch_bounds__(kThreads) void fill_table_kernel(unsigned long long* __restrict__ keys,
-                                                              int32_t* __restrict__ vals, uint32_t cap) {
-    uint32_t i = blockIdx.x * kThreads + threadIdx.x;
-    if (i < cap) {
-        keys[i] = kEmptyKey;
-        vals[i] = kNoRow;
-    }
-}
-
-__global__ __launch_bounds__(kThreads) void zero_i32_kernel(int32_t* __restrict__ p, int n) {
-    int i = blockIdx.x * kThreads + threadIdx.x;
-    if (i < n) p[i] = 0;
-}
-
-// Every source row inserts its key; the slot's value becomes the smallest source row carrying that key.
-__global__ __launch_bounds__(kThreads) void insert_kernel(const int4* __restrict__ src, int64_t n, int32_t floor_step,
-                                                          unsigned long long* __restrict__ keys,
-                                                          int32_t* __restrict__ vals, uint32_t cap,
-                                                          int32_t* __restrict__ slot_of, int32_t* __restrict__ err) {
-    int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (i >= n) return;
+__device__ __forceinline__ int4 load_row(const int4* __restrict__ src, int64_t i, int32_t floor_step) {
     int4 c = src[i];
     if (floor_step > 1) {
         c.y = floor_to_multiple(c.y, floor_step);
         c.z = floor_to_multiple(c.z, floor_step);
         c.w = floor_to_multiple(c.w, floor_step);
     }
+    return c;
+}
+
+__global__ __launch_bounds__(kThreads) void fill_table_kernel(HashSlot* __restrict__ tab, uint32_t cap,
+                                                              int32_t* __restrict__ small, int n_small) {
+    const uint32_t i = blockIdx.x * kThreads + threadIdx.x;
+    if (i < cap) {
+        uint4 v;
+        v.x = 0xffffffffu;
+        v.y = 0xffffffffu;
+        v.z = (uint32_t)kNoRow;
+        v.w = (uint32_t)-1;
+        *reinterpret_cast<uint4*>(&tab[i]) = v;
+    }
+    if (i < (uint32_t)n_small) small[i] = 0;
+}
+
+// Every source row inserts its key; slot.first becomes the smallest source row carrying that key.
+__global__ __launch_bounds__(kThreads) void insert_kernel(const int4* __restrict__ src, int64_t n, int32_t floor_step,
+                                                          HashSlot* __restrict__ tab, uint32_t cap,
+                                                          int32_t* __restrict__ slot_of, int32_t* __restrict__ err) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= n) return;
+    const int4 c = load_row(src, i, floor_step);
     uint64_t key;
     if (!pack_key(c.x, c.y, c.z, c.w, &key)) {
         atomicOr(err, 1);
         slot_of[i] = -1;
         return;
     }
-    int64_t slot = hash_insert(keys, cap, key);
+    const int64_t slot = hash_insert(tab, cap, key);
     if (slot < 0) {
         atomicOr(err, 2);
         slot_of[i] = -1;
         return;
     }
-    atomicMin(&vals[slot], (int32_t)i);
+    atomicMin(&tab[slot].first, (int32_t)i);
     slot_of[i] = (int32_t)slot;
 }
 
-__global__ __launch_bounds__(kThreads) void flag_first_kernel(const int32_t* __restrict__ slot_of,
-                                                              const int32_t* __restrict__ vals, int64_t n,
-                                                              int32_t* __restrict__ flags) {
-    int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (i >= n) return;
-    int32_t s = slot_of[i];
-    flags[i] = (s >= 0 && vals[s] == (int32_t)i) ? 1 : 0;
+__device__ __forceinline__ bool is_first(const HashSlot* __restrict__ tab, const int32_t* __restrict__ slot_of,
+                                         int64_t i, int64_t n) {
+    if (i >= n) return false;
+    const int32_t s = slot_of[i];
+    return s >= 0 && tab[s].first == (int32_t)i;
 }
 
-// First occurrences write their (floored) row at their rank and relabel the table slot with that rank.
-// `flags` was fixed by the previous kernel, so relabelling in place cannot disturb another thread's test.
+// Block b counts the first occurrences among rows [b*1024, b*1024+1024).
+__global__ __launch_bounds__(kThreads) void count_first_kernel(const HashSlot* __restrict__ tab,
+                                                               const int32_t* __restrict__ slot_of, int64_t n,
+                                                               int32_t* __restrict__ block_counts) {
+    __shared__ int s_cnt[kThreads / 64];
+    const int64_t base = (int64_t)blockIdx.x * kBlockRows;
+    int c = 0;
+#pragma unroll
+    for (int j = 0; j < kRowsPerThread; ++j)
+        c += __popcll(__ballot(is_first(tab, slot_of, base + j * kThreads + threadIdx.x, n)));
+    if ((threadIdx.x & 63) == 0) s_cnt[threadIdx.x >> 6] = c;
+    __syncthreads();
+    if (threadIdx.x == 0) block_counts[blockIdx.x] = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
+}
+
+// Block b numbers its first occurrences: rank = (firsts in earlier blocks) + (firsts before it in this
+// block, row order).  Writes the (floored) coordinates at that rank and the rank into the table slot.
+// block_base: if `scanned`, block_counts already holds exclusive prefixes.
 __global__ __launch_bounds__(kThreads) void emit_first_kernel(const int4* __restrict__ src, int64_t n,
-                                                              int32_t floor_step, const int32_t* __restrict__ slot_of,
-                                                              const int32_t* __restrict__ flags,
-                                                              const int32_t* __restrict__ rank,
-                                                              int4* __restrict__ coords, int32_t* __restrict__ vals) {
-    int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (i >= n || !flags[i]) return;
-    int4 c = src[i];
-    if (floor_step > 1) {
-        c.y = floor_to_multiple(c.y, floor_step);
-        c.z = floor_to_multiple(c.z, floor_step);
-        c.w = floor_to_multiple(c.w, floor_step);
+                                                              int32_t floor_step, HashSlot* __restrict__ tab,
+                                                              const int32_t* __restrict__ slot_of,
+                                                              const int32_t* __restrict__ block_counts, int scanned,
+                                                              int4* __restrict__ coords, int32_t* __restrict__ total) {
+    __shared__ int s_red[kThreads / 64];
+    __shared__ int s_row[kRowsPerThread][kThreads / 64];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    // firsts in the blocks before this one
+    int before = 0;
+    if (scanned) {
+        before = block_counts[blockIdx.x];
+    } else {
+        int s = 0;
+        for (int b = threadIdx.x; b < (int)blockIdx.x; b += kThreads) s += block_counts[b];
+#pragma unroll
+        for (int d = 32; d > 0; d >>= 1) s += __shfl_down(s, d, 64);
+        if (lane == 0) s_red[w] = s;
+        __syncthreads();
+        before = s_red[0] + s_red[1] + s_red[2] + s_red[3];
     }
-    int32_t r = rank[i];
-    coords[r] = c;
-    vals[slot_of[i]] = r;
+    const int64_t base = (int64_t)blockIdx.x * kBlockRows;
+    bool f[kRowsPerThread];
+    int pos[kRowsPerThread];
+#pragma unroll
+    for (int j = 0; j < kRowsPerThread; ++j) {
+        f[j] = is_first(tab, slot_of, base + j * kThreads + threadIdx.x, n);
+        const unsigned long long m = __ballot(f[j]);
+        pos[j] = __popcll(m & ((1ull << lane) - 1ull));
+        if (lane == 0) s_row[j][w] = __popcll(m);
+    }
+    __syncthreads();
+    int run = before;
+#pragma unroll
+    for (int j = 0; j < kRowsPerThread; ++j) {
+        int mine = run;
+        for (int ww = 0; ww < kThreads / 64; ++ww) {
+            if (ww < w) mine += s_row[j][ww];
+            run += s_row[j][ww];
+        }
+        if (f[j]) {
+            const int64_t i = base + j * kThreads + threadIdx.x;
+            const int32_t r = mine + pos[j];
+            coords[r] = load_row(src, i, floor_step);
+            tab[slot_of[i]].row = r;
+        }
+    }
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) *total = run;
 }
 
-__global__ __launch_bounds__(kThreads) void inverse_kernel(const int32_t* __restrict__ slot_of,
-                                                           const int32_t* __restrict__ vals, int64_t n,
+__global__ __launch_bounds__(kThreads) void inverse_kernel(const HashSlot* __restrict__ tab,
+                                                           const int32_t* __restrict__ slot_of, int64_t n,
                                                            int32_t* __restrict__ inverse) {
-    int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (i >= n) return;
-    int32_t s = slot_of[i];
-    inverse[i] = s >= 0 ? vals[s] : -1;
+    const int32_t s = slot_of[i];
+    inverse[i] = s >= 0 ? tab[s].row : -1;
 }
 
-inline unsigned blocks_for(int64_t n) { return (unsigned)((n + kThreads - 1) / kThreads); }
+inline unsigned blocks_for(int64_t n, int per) { return (unsigned)((n + per - 1) / per); }
 
 }  // namespace
 
@@ -108,35 +165,37 @@ int coords_build_impl(const int32_t* d_src, int64_t n_src, int32_t floor_step, i
     uint32_t cap = 1024;
     while ((int64_t)cap < 2 * n_src) cap <<= 1;
     c->tab.cap = cap;
-    c->tab.keys = dev_alloc((size_t)cap * 8);
-    c->tab.vals = dev_alloc((size_t)cap * 4);
+    c->tab.slots = dev_alloc((size_t)cap * sizeof(HashSlot));
     c->coords = dev_alloc((size_t)(n_src ? n_src : 1) * 16);
     c->inverse = dev_alloc((size_t)(n_src ? n_src : 1) * 4);
     Buf slot_of = dev_alloc((size_t)(n_src ? n_src : 1) * 4);
-    Buf flags = dev_alloc((size_t)(n_src ? n_src : 1) * 4);
+    const int64_t nb = (n_src + kBlockRows - 1) / kBlockRows;
+    Buf block_counts = dev_alloc((size_t)(nb ? nb : 1) * 4);
     Buf small = dev_alloc(8);  // [0] total, [1] error bits
-    if (!c->tab.keys || !c->tab.vals || !c->coords || !c->inverse || !slot_of || !flags || !small) return SP_ERR_ALLOC;
-    auto* keys = ptr<unsigned long long>(c->tab.keys);
-    auto* vals = ptr<int32_t>(c->tab.vals);
+    if (!c->tab.slots || !c->coords || !c->inverse || !slot_of || !block_counts || !small) return SP_ERR_ALLOC;
+    HashSlot* tab = ptr<HashSlot>(c->tab.slots);
     int32_t* d_small = ptr<int32_t>(small);
 
-    hipLaunchKernelGGL(fill_table_kernel, dim3(blocks_for(cap)), dim3(kThreads), 0, s, keys, vals, cap);
-    hipLaunchKernelGGL(zero_i32_kernel, dim3(1), dim3(kThreads), 0, s, d_small, 2);
+    hipLaunchKernelGGL(fill_table_kernel, dim3(blocks_for(cap, kThreads)), dim3(kThreads), 0, s, tab, cap, d_small, 2);
     int32_t host_small[2] = {0, 0};
     if (n_src > 0) {
         const int4* src = reinterpret_cast<const int4*>(d_src);
-        hipLaunchKernelGGL(insert_kernel, dim3(blocks_for(n_src)), dim3(kThreads), 0, s, src, n_src, floor_step, keys,
-                           vals, cap, ptr<int32_t>(slot_of), d_small + 1);
-        hipLaunchKernelGGL(flag_first_kernel, dim3(blocks_for(n_src)), dim3(kThreads), 0, s, ptr<int32_t>(slot_of),
-                           vals, n_src, ptr<int32_t>(flags));
-        Buf rank = dev_alloc((size_t)n_src * 4);
-        if (!rank) return SP_ERR_ALLOC;
-        SP_TRY(exclusive_scan_i32(ptr<int32_t>(flags), ptr<int32_t>(rank), n_src, d_small, s));
-        hipLaunchKernelGGL(emit_first_kernel, dim3(blocks_for(n_src)), dim3(kThreads), 0, s, src, n_src, floor_step,
-                           ptr<int32_t>(slot_of), ptr<int32_t>(flags), ptr<int32_t>(rank),
-                           ptr<int4>(c->coords), vals);
-        hipLaunchKernelGGL(inverse_kernel, dim3(blocks_for(n_src)), dim3(kThreads), 0, s, ptr<int32_t>(slot_of), vals,
-                           n_src, ptr<int32_t>(c->inverse));
+        hipLaunchKernelGGL(insert_kernel, dim3(blocks_for(n_src, kThreads)), dim3(kThreads), 0, s, src, n_src,
+                           floor_step, tab, cap, ptr<int32_t>(slot_of), d_small + 1);
+        hipLaunchKernelGGL(count_first_kernel, dim3((unsigned)nb), dim3(kThreads), 0, s, tab, ptr<int32_t>(slot_of),
+                           n_src, ptr<int32_t>(block_counts));
+        int scanned = 0;
+        if (nb > 4096) {  // too many blocks for every block to add up its predecessors: scan the counts first
+            ScanJob job;
+            job.data = ptr<int32_t>(block_counts);
+            job.n = nb;
+            SP_TRY(exclusive_scan_jobs(&job, 1, s));
+            scanned = 1;
+        }
+        hipLaunchKernelGGL(emit_first_kernel, dim3((unsigned)nb), dim3(kThreads), 0, s, src, n_src, floor_step, tab,
+                           ptr<int32_t>(slot_of), ptr<int32_t>(block_counts), scanned, ptr<int4>(c->coords), d_small);
+        hipLaunchKernelGGL(inverse_kernel, dim3(blocks_for(n_src, kThreads)), dim3(kThreads), 0, s, tab,
+                           ptr<int32_t>(slot_of), n_src, ptr<int32_t>(c->inverse));
         SP_HIP(hipGetLastError());
     }
     SP_TRY(read_back(host_small, d_small, 8, s));

@@ -1,6 +1,7 @@
 // Device-side open-addressing hash table on 64-bit packed coordinates (the GPU hashmap of Sec. III-B,
-// used for the insertions and searches of step 2).  Linear probing; keys are 8 bytes, so the 16 slots
-// after the home slot share one 128-byte line and a probe sequence almost always stays inside it.
+// used for the insertions and searches of step 2).  One slot is 16 bytes {key, first, row}, so a search
+// resolves key and row with a single 16-byte access, and the 8 slots after the home slot share its
+// 128-byte line: with linear probing at load factor <= 0.5 a probe sequence almost always stays inside it.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -11,6 +12,12 @@ namespace sp {
 
 constexpr uint64_t kEmptyKey = ~0ull;
 constexpr int32_t kNoRow = 0x7fffffff;
+
+struct __align__(16) HashSlot {
+    unsigned long long key;  // packed (b,x,y,z) or kEmptyKey
+    int32_t first;           // smallest source row that carried this key (atomicMin while inserting)
+    int32_t row;             // row number of the key among the distinct coordinates
+};
 
 // b in [0, 65536), x,y,z in [-32768, 32768).  Returns false when the row cannot be packed.
 __device__ __forceinline__ bool pack_key(int32_t b, int32_t x, int32_t y, int32_t z, uint64_t* key) {
@@ -31,14 +38,14 @@ __device__ __forceinline__ uint32_t hash_key(uint64_t k) {
 }
 
 // Insert-or-find.  Returns the slot of `key`, or -1 if the table is full (never at load factor <= 0.5).
-__device__ __forceinline__ int64_t hash_insert(unsigned long long* __restrict__ keys, uint32_t cap, uint64_t key) {
+__device__ __forceinline__ int64_t hash_insert(HashSlot* __restrict__ tab, uint32_t cap, uint64_t key) {
     const uint32_t mask = cap - 1;
     uint32_t slot = hash_key(key) & mask;
     for (uint32_t probe = 0; probe < cap; ++probe) {
-        unsigned long long cur = keys[slot];
+        unsigned long long cur = tab[slot].key;
         if (cur == key) return slot;
         if (cur == kEmptyKey) {
-            unsigned long long prev = atomicCAS(&keys[slot], (unsigned long long)kEmptyKey, (unsigned long long)key);
+            unsigned long long prev = atomicCAS(&tab[slot].key, (unsigned long long)kEmptyKey, (unsigned long long)key);
             if (prev == kEmptyKey || prev == key) return slot;
         }
         slot = (slot + 1) & mask;
@@ -46,14 +53,14 @@ __device__ __forceinline__ int64_t hash_insert(unsigned long long* __restrict__ 
     return -1;
 }
 
-// Row index stored for `key`, or -1 when absent.
-__device__ __forceinline__ int32_t hash_find(const unsigned long long* __restrict__ keys,
-                                             const int32_t* __restrict__ vals, uint32_t cap, uint64_t key) {
+// Row number stored for `key`, or -1 when absent.  One 16-byte load per probed slot.
+__device__ __forceinline__ int32_t hash_find(const HashSlot* __restrict__ tab, uint32_t cap, uint64_t key) {
     const uint32_t mask = cap - 1;
     uint32_t slot = hash_key(key) & mask;
     for (uint32_t probe = 0; probe < cap; ++probe) {
-        unsigned long long cur = keys[slot];
-        if (cur == key) return vals[slot];
+        const uint4 raw = *reinterpret_cast<const uint4*>(&tab[slot]);
+        const unsigned long long cur = ((unsigned long long)raw.y << 32) | raw.x;
+        if (cur == key) return (int32_t)raw.w;
         if (cur == kEmptyKey) return -1;
         slot = (slot + 1) & mask;
     }

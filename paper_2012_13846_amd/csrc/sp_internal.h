@@ -51,14 +51,22 @@ int read_back(void* h_dst, const void* d_src, size_t bytes, hipStream_t s);  // 
 
 // ---- hash table ---------------------------------------------------------------------------------------------
 struct HashTab {
-    Buf keys;          // uint64 [cap], EMPTY = ~0
-    Buf vals;          // int32  [cap], row index of the key
+    Buf slots;         // HashSlot [cap] (sp_hash.h): 16 bytes {key, first source row, row number}
     uint32_t cap = 0;  // power of two, >= 2 * entries
 };
 
-// ---- device-wide exclusive scan of int32 (sp_scan.hip) ---------------------------------------------------------
-// out[i] = sum_{j<i} in[j]; *d_total (device, may be null) = sum of all.  in == out allowed.  n >= 0.
-int exclusive_scan_i32(const int32_t* d_in, int32_t* d_out, int64_t n, int32_t* d_total, hipStream_t s);
+// ---- device-wide exclusive scans of int32 (sp_scan.hip) --------------------------------------------------------
+// In place: data[i] = sum_{j<i} data[j].  *total (device, may be null) = sum of all.  With koff set,
+// koff[i] = the exclusive prefix at element i*koff_stride for i < koff_n, and koff[koff_n] = the total.
+struct ScanJob {
+    int32_t* data = nullptr;
+    int64_t n = 0;
+    int32_t* total = nullptr;
+    int32_t* koff = nullptr;
+    int64_t koff_stride = 1;
+    int32_t koff_n = 0;
+};
+int exclusive_scan_jobs(const ScanJob* jobs, int njobs /* 1 or 2 */, hipStream_t s);
 
 // ---- coords (sp_coords.hip) ---------------------------------------------------------------------------------------
 // Builds a coordinate set from d_src rows; floor_step > 1 floors x,y,z to multiples of it first.

@@ -18,8 +18,7 @@ __global__ __launch_bounds__(256) void fill_i32_kernel(int32_t* __restrict__ p, 
 // Writes nbr_out[k][o]; scatters nbr_in[k][i] = o when nbr_in is given; counts live links per 64-row
 // sub-tile (sub_counts[(tile*4 + wave)*kvol + k]) and per tile (blk_counts[k*ntiles + tile]).
 __global__ __launch_bounds__(kThreads) void probe_kernel(const int4* __restrict__ c_out, int64_t n_out,
-                                                         const unsigned long long* __restrict__ keys,
-                                                         const int32_t* __restrict__ vals, uint32_t cap, int K,
+                                                         const HashSlot* __restrict__ tab, uint32_t cap, int K,
                                                          int step, int identity_k, int32_t* __restrict__ nbr_out,
                                                          int32_t* __restrict__ nbr_in, int64_t n_in,
                                                          int32_t* __restrict__ sub_counts,
@@ -37,7 +36,7 @@ __global__ __launch_bounds__(kThreads) void probe_kernel(const int4* __restrict_
             int4 c = c_out[o];
             uint64_t key;
             if (pack_key(c.x, c.y + (ax - centre) * step, c.z + (ay - centre) * step, c.w + (az - centre) * step, &key))
-                v = hash_find(keys, vals, cap, key);
+                v = hash_find(tab, cap, key);
         }
         nbr_out[(int64_t)k * n_out + o] = v;
         if (nbr_in && v >= 0) nbr_in[(int64_t)k * n_in + v] = (int32_t)o;
@@ -94,13 +93,6 @@ __global__ __launch_bounds__(kThreads) void emit_kernel(const int32_t* __restric
             pair_out[p] = (int32_t)r;
         }
     }
-}
-
-__global__ void gather_koff_kernel(const int32_t* __restrict__ blk_off, int64_t ntiles, int kvol,
-                                   const int32_t* __restrict__ total, int32_t* __restrict__ koff) {
-    int k = threadIdx.x;
-    if (k < kvol) koff[k] = ntiles > 0 ? blk_off[(int64_t)k * ntiles] : 0;
-    if (k == kvol) koff[k] = ntiles > 0 ? *total : 0;
 }
 
 inline unsigned blocks256(int64_t n) { return (unsigned)((n + 255) / 256); }
@@ -187,19 +179,28 @@ int sp_kmap_build(const sp_coords_t* in, int32_t kernel_size, int32_t stride, in
     int32_t* d_koff = ptr<int32_t>(small);
     if (nt_out > 0) {
         hipLaunchKernelGGL(probe_kernel, dim3((unsigned)nt_out, kvol), dim3(kThreads), 0, s,
-                           ptr<int4>(m->c_out->coords), n_out, ptr<unsigned long long>(in->tab.keys),
-                           ptr<int32_t>(in->tab.vals), in->tab.cap, kernel_size, step,
+                           ptr<int4>(m->c_out->coords), n_out, ptr<HashSlot>(in->tab.slots), in->tab.cap,
+                           kernel_size, step,
                            symmetric ? (kvol - 1) / 2 : -1, ptr<int32_t>(so.nbr),
                            symmetric ? (int32_t*)nullptr : ptr<int32_t>(si.nbr), n_in, ptr<int32_t>(so.tl_off),
                            ptr<int32_t>(blk));
     }
     SP_HIP(hipGetLastError());
-    const int64_t n_sub = nt_out * kvol * kSubTiles;
-    SP_TRY(exclusive_scan_i32(ptr<int32_t>(so.tl_off), ptr<int32_t>(so.tl_off), n_sub, ptr<int32_t>(so.tl_off) + n_sub, s));
-    SP_TRY(exclusive_scan_i32(ptr<int32_t>(blk), ptr<int32_t>(blk), nt_out * kvol, d_koff + kvol + 1, s));
-    hipLaunchKernelGGL(gather_koff_kernel, dim3(1), dim3(128), 0, s, ptr<int32_t>(blk), nt_out, kvol,
-                       d_koff + kvol + 1, d_koff);
-    SP_HIP(hipGetLastError());
+    // both scans in one launch pair: sub-tile-major list offsets, and offset-major pair-list offsets whose
+    // values at the start of each offset (every nt_out-th element) are the per-offset prefix koff[]
+    {
+        const int64_t n_sub = nt_out * kvol * kSubTiles;
+        ScanJob jobs[2];
+        jobs[0].data = ptr<int32_t>(so.tl_off);
+        jobs[0].n = n_sub;
+        jobs[0].total = ptr<int32_t>(so.tl_off) + n_sub;
+        jobs[1].data = ptr<int32_t>(blk);
+        jobs[1].n = nt_out * kvol;
+        jobs[1].koff = d_koff;
+        jobs[1].koff_stride = nt_out > 0 ? nt_out : 1;
+        jobs[1].koff_n = kvol;
+        SP_TRY(exclusive_scan_jobs(jobs, 2, s));
+    }
     std::vector<int32_t> h_koff(kvol + 1);
     SP_TRY(read_back(h_koff.data(), d_koff, (size_t)(kvol + 1) * 4, s));
     m->koff.resize(kvol + 1);
@@ -221,8 +222,11 @@ int sp_kmap_build(const sp_coords_t* in, int32_t kernel_size, int32_t stride, in
             hipLaunchKernelGGL(count_kernel, dim3((unsigned)nt_in, kvol), dim3(kThreads), 0, s, ptr<int32_t>(si.nbr),
                                n_in, ptr<int32_t>(si.tl_off));
         const int64_t n_sub_in = nt_in * kvol * kSubTiles;
-        SP_TRY(exclusive_scan_i32(ptr<int32_t>(si.tl_off), ptr<int32_t>(si.tl_off), n_sub_in,
-                                  ptr<int32_t>(si.tl_off) + n_sub_in, s));
+        ScanJob job;
+        job.data = ptr<int32_t>(si.tl_off);
+        job.n = n_sub_in;
+        job.total = ptr<int32_t>(si.tl_off) + n_sub_in;
+        SP_TRY(exclusive_scan_jobs(&job, 1, s));
         SP_TRY(finish_side(si, kvol, m->total, nullptr, nullptr, nullptr, s));
     }
     if (out_coords) {

@@ -64,20 +64,41 @@ __global__ __launch_bounds__(256) void wgrad_partial_kernel(const int32_t* __res
 #pragma unroll
         for (int b = 0; b < NCI; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    for (int64_t p0 = it.beg + wave * 4; p0 < it.end; p0 += 16) {
-        const int64_t p = p0 + g;
+    // software pipeline: link indices two steps ahead, rows one step ahead of the MFMAs that use them
+    const int64_t first_p = it.beg + wave * 4 + g;
+    auto load_idx = [&](int64_t p, int32_t& o, int32_t& i) {
         const bool live = p < it.end;
-        const int32_t o = live ? pair_out[p] : 0, i = live ? pair_in[p] : 0;
-        float av[NCO], bv[NCI];
+        o = live ? pair_out[p] : -1;
+        i = live ? pair_in[p] : 0;
+    };
+    auto load_rows = [&](int32_t o, int32_t i, float (&av)[NCO], float (&bv)[NCI]) {
+        const bool live = o >= 0;
 #pragma unroll
         for (int a = 0; a < NCO; ++a) av[a] = live ? load_f32(dY + (size_t)o * cout + co0 + a * 16 + n16) : 0.f;
 #pragma unroll
         for (int b = 0; b < NCI; ++b) bv[b] = live ? load_f32(X + (size_t)i * cin + ci0 + b * 16 + n16) : 0.f;
+    };
+    int32_t o1, i1, o2, i2;
+    float av[NCO], bv[NCI];
+    load_idx(first_p, o1, i1);
+    load_idx(first_p + 16, o2, i2);
+    load_rows(o1, i1, av, bv);
+    for (int64_t p = first_p; p - g < it.end; p += 16) {
+        float an[NCO], bn[NCI];
+        int32_t o3, i3;
+        load_idx(p + 32, o3, i3);
+        load_rows(o2, i2, an, bn);
 #pragma unroll
         for (int a = 0; a < NCO; ++a)
 #pragma unroll
             for (int b = 0; b < NCI; ++b)
                 acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[a], bv[b], acc[a][b], 0, 0, 0);
+#pragma unroll
+        for (int a = 0; a < NCO; ++a) av[a] = an[a];
+#pragma unroll
+        for (int b = 0; b < NCI; ++b) bv[b] = bn[b];
+        o2 = o3;
+        i2 = i3;
     }
     // acc[a][b][j] is element (co = a*16 + 4*g + j, ci = b*16 + n16); add the 4 wavefronts in order
     for (int w = 0; w < 4; ++w) {
@@ -101,19 +122,32 @@ __global__ __launch_bounds__(256) void wgrad_partial_kernel(const int32_t* __res
     }
 }
 
-// dW[k][e] = sum of the partials of offset k's items, in item order.
+// dW[k][e] = sum of the partials of offset k's items, in a fixed order: 4 interleaved running sums per
+// element (one per wavefront of the block), each over every 4th item, then added 0+1+2+3.
+// grid (per/64, kvol), block 256 = 64 elements x 4 item groups.
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ part,
                                                            const int32_t* __restrict__ koff, int kvol, int chunk,
                                                            int per, float* __restrict__ dw) {
+    __shared__ float red[4][64];
     const int k = blockIdx.y;
-    const int e = blockIdx.x * 256 + threadIdx.x;
-    if (e >= per) return;
+    const int el = threadIdx.x & 63, grp = threadIdx.x >> 6;
+    const int e = blockIdx.x * 64 + el;
     int first = 0;
     for (int j = 0; j < k; ++j) first += (koff[j + 1] - koff[j] + chunk - 1) / chunk;
     const int ni = (koff[k + 1] - koff[k] + chunk - 1) / chunk;
-    float s = 0.f;
-    for (int it = 0; it < ni; ++it) s += part[(size_t)(first + it) * per + e];
-    dw[(size_t)k * per + e] = s;
+    float s0 = 0.f, s1 = 0.f;
+    if (e < per) {
+        const float* p = part + (size_t)first * per + e;
+        int it = grp;
+        for (; it + 4 < ni; it += 8) {  // two independent loads in flight
+            s0 += p[(size_t)it * per];
+            s1 += p[(size_t)(it + 4) * per];
+        }
+        if (it < ni) s0 += p[(size_t)it * per];
+    }
+    red[grp][el] = s0 + s1;
+    __syncthreads();
+    if (grp == 0 && e < per) dw[(size_t)k * per + e] = ((red[0][el] + red[1][el]) + red[2][el]) + red[3][el];
 }
 
 // Plain kernel for channel counts that are not multiples of 16: one thread per weight element.
@@ -170,7 +204,7 @@ int wgrad_typed(const sp_kmap* m, const void* x, const void* dy, float* dw, int 
         else if (ci32) launch_partial<T, 16, 32>(m, (int)items, (int)chunk, x, dy, cin, cout, ptr<float>(part), s);
         else launch_partial<T, 16, 16>(m, (int)items, (int)chunk, x, dy, cin, cout, ptr<float>(part), s);
     }
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((per + 255) / 256, kvol), dim3(256), 0, s, ptr<float>(part),
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((per + 63) / 64, kvol), dim3(256), 0, s, ptr<float>(part),
                        ptr<int32_t>(m->d_koff), kvol, (int)chunk, per, dw);
     SP_HIP(hipGetLastError());
     return SP_OK;
