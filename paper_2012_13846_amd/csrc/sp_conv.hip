@@ -38,6 +38,8 @@ struct GatherArgs {
     int co_total;
     int flip;        // weight matrix of list k is kvol-1-k
     int lds_per_wave;  // bytes of LDS of one wavefront in gather_wave_kernel
+    uint32_t f_bytes, w_bytes, src_bytes, row_bytes;  // sizes of f / w / tl_src / tl_row for buffer addressing (< 4 GiB)
+    int wave_ok;       // host-side only: buffers small enough for 32-bit buffer addressing
     int w_transposed;  // host-side only: the stored weights are [k][cc][co] (data gradient) instead of [k][co][cc]
 };
 
@@ -267,21 +269,28 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void gather_wave_kernel(Gather
     }
     wave_sync();
 
-    const unsigned char* __restrict__ F = static_cast<const unsigned char*>(a.f);
-    const unsigned char* __restrict__ WF = static_cast<const unsigned char*>(a.w) +
-                                           (size_t)blockIdx.y * Cfg::kWFragBytesPerOffsetTile + (size_t)lane * 16;
-    const size_t w_offset_stride = (size_t)(a.co_total / COT) * Cfg::kWFragBytesPerOffsetTile;
-    const int32_t* __restrict__ tl_src = a.tl_src;
-    const uint16_t* __restrict__ tl_row = a.tl_row;
+    // Buffer addressing: a 32-bit byte offset per lane against a descriptor in scalar registers costs one
+    // integer multiply-add per load instead of 64-bit pointer arithmetic, and reads past the end return 0.
+    constexpr int kRsrcFlags = 0x00020000;
+    const __amdgpu_buffer_rsrc_t rF = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(a.f), 0, (int)a.f_bytes, kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t rW = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(a.w), 0, (int)a.w_bytes, kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t rSrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t*>(a.tl_src), 0, (int)a.src_bytes, kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t rRow =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.tl_row), 0, (int)a.row_bytes, kRsrcFlags);
+    const uint32_t w_tile_off = (uint32_t)(blockIdx.y * Cfg::kWFragBytesPerOffsetTile);
+    const uint32_t w_offset_stride = (uint32_t)((a.co_total / COT) * Cfg::kWFragBytesPerOffsetTile);
 
     auto load_weights = [&](int k, Frag (&wf)[kNCT][kGroups]) __attribute__((always_inline)) {
         const int wk = a.flip ? kvol - 1 - k : k;
-        const unsigned char* p = WF + (size_t)wk * w_offset_stride;
+        // the offset index is the same in every lane, but it came through LDS: tell the compiler
+        const int soff = __builtin_amdgcn_readfirstlane((int)(w_tile_off + (uint32_t)wk * w_offset_stride));
 #pragma unroll
         for (int ct = 0; ct < kNCT; ++ct)
 #pragma unroll
             for (int s = 0; s < kGroups; ++s)
-                wf[ct][s] = *reinterpret_cast<const Frag*>(p + (size_t)(ct * kGroups + s) * 1024);
+                wf[ct][s] = __builtin_bit_cast(
+                    Frag, __builtin_amdgcn_raw_buffer_load_b128(rW, lane * 16 + (ct * kGroups + s) * 1024, soff, 0));
     };
 
     // The main loop is straight-line code with the same loads in every turn (blocks past the end are
@@ -301,16 +310,16 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void gather_wave_kernel(Gather
         sl.de = s_blk[min(b, last)];
         const int cnt = ((sl.de >> 7) & 15) + 1, e0 = off0 + (sl.de >> 13);
 #pragma unroll
-        for (int t = 0; t < kXLoads; ++t) sl.esrc[t] = tl_src[e0 + min((t * 64 + lane) / kPieces, cnt - 1)];
-        sl.erow = tl_row[e0 + min(n16, cnt - 1)];
+        for (int t = 0; t < kXLoads; ++t)
+            sl.esrc[t] = (int)__builtin_amdgcn_raw_buffer_load_b32(rSrc, (e0 + min((t * 64 + lane) / kPieces, cnt - 1)) * 4, 0, 0);
+        sl.erow = (int)__builtin_amdgcn_raw_buffer_load_b16(rRow, (e0 + min(n16, cnt - 1)) * 2, 0, 0);
     };
     auto issue_gather = [&](Slot& sl) __attribute__((always_inline)) {
         sl.dc = sl.de;
         sl.drow = sl.erow & 63;
 #pragma unroll
         for (int t = 0; t < kXLoads; ++t)
-            sl.x[t] = *reinterpret_cast<const u32x4*>(F + (size_t)sl.esrc[t] * Cfg::kRowBytes +
-                                                       ((t * 64 + lane) % kPieces) * 16);
+            sl.x[t] = __builtin_amdgcn_raw_buffer_load_b128(rF, sl.esrc[t] * Cfg::kRowBytes + ((t * 64 + lane) % kPieces) * 16, 0, 0);
         load_weights(sl.dc & 127, sl.w);
     };
     auto stage = [&](const Slot& sl) __attribute__((always_inline)) {  // gathered rows -> LDS, row-major, padded
@@ -344,52 +353,97 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void gather_wave_kernel(Gather
         read_frags(xf_c);
         wave_sync();
 
-        // one block: sl holds block b, sn holds block b + 1
-        auto body = [&](int b, Slot& sl, const Slot& sn) __attribute__((always_inline)) {
+        // One block: sl holds block b, sn holds block b + 1.  A wavefront issues in order, so the block's
+        // MFMAs only overlap with its other work if that work does not depend on them and is interleaved
+        // with them: the accumulator update of block b-1, the staging of block b+1 and the loads for
+        // blocks b+3 / b+6 are therefore issued between the MFMAs of block b.
+        // Three result sets rotate with the three slots, so a block's products stay where the MFMAs left
+        // them until the next block's turn adds them to the accumulator.
+        struct Result {
+            f32x4 d[kNCT];  // d[ct][i] = channel ct*16 + 4*g + i of link n16 of the block
+            float* dst;     // accumulator row of that link (+ 4*g)
+            bool valid;     // this lane's link exists
+        };
+        Result res0 = {}, res1 = {}, res2 = {};
+        res0.dst = res1.dst = res2.dst = acc + g * 4;
+        // the accumulator rows are read at the start of a turn and written back at its end, so the LDS
+        // latency is paid once, under the turn's MFMAs
+        auto flush_read = [&](const Result& r, f32x4 (&av)[kNCT]) __attribute__((always_inline)) {
+#pragma unroll
+            for (int ct = 0; ct < kNCT; ++ct) av[ct] = *reinterpret_cast<const f32x4*>(r.dst + ct * 16);
+        };
+        auto flush_write = [&](const Result& r, const f32x4 (&av)[kNCT]) __attribute__((always_inline)) {
+            if (r.valid) {
+#pragma unroll
+                for (int ct = 0; ct < kNCT; ++ct) *reinterpret_cast<f32x4*>(r.dst + ct * 16) = av[ct] + r.d[ct];
+            }
+        };
+        auto body = [&](int b, Slot& sl, const Slot& sn, Result& cur, const Result& prev) __attribute__((always_inline)) {
             const int cnt = ((sl.dc >> 7) & 15) + 1;
-            const bool valid = n16 < cnt;
-            float* dst = acc + sl.drow * Cfg::kStride + g * 4;
+            cur.valid = n16 < cnt;
+            cur.dst = acc + sl.drow * Cfg::kStride + g * 4;
             stage(sn);  // the next block's rows (this block's fragments are already in registers)
             wave_sync();
             f32x4 av[kNCT];
-#pragma unroll
-            for (int ct = 0; ct < kNCT; ++ct) av[ct] = *reinterpret_cast<f32x4*>(dst + ct * 16);
+            flush_read(prev, av);
             Frag xf_n[kGroups];
             read_frags(xf_n);
 
-            f32x4 d[kNCT];
 #pragma unroll
-            for (int ct = 0; ct < kNCT; ++ct) d[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int ct = 0; ct < kNCT; ++ct) cur.d[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int s = 0; s < kGroups; ++s)
 #pragma unroll
                 for (int ct = 0; ct < kNCT; ++ct) {
                     if constexpr (kIsF32) {
-                        d[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(sl.w[ct][s][0], xf_c[s][0], d[ct], 0, 0, 0);
-                        d[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(sl.w[ct][s][1], xf_c[s][1], d[ct], 0, 0, 0);
-                        d[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(sl.w[ct][s][2], xf_c[s][2], d[ct], 0, 0, 0);
-                        d[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(sl.w[ct][s][3], xf_c[s][3], d[ct], 0, 0, 0);
+                        cur.d[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(sl.w[ct][s][0], xf_c[s][0], cur.d[ct], 0, 0, 0);
+                        cur.d[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(sl.w[ct][s][1], xf_c[s][1], cur.d[ct], 0, 0, 0);
+                        cur.d[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(sl.w[ct][s][2], xf_c[s][2], cur.d[ct], 0, 0, 0);
+                        cur.d[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(sl.w[ct][s][3], xf_c[s][3], cur.d[ct], 0, 0, 0);
                     } else {
-                        d[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sl.w[ct][s], xf_c[s], d[ct], 0, 0, 0);
+                        cur.d[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sl.w[ct][s], xf_c[s], cur.d[ct], 0, 0, 0);
                     }
                 }
             issue_gather(sl);               // block b + kDepth: its entries arrived a turn ago
             load_entries(sl, b + 2 * kDepth);
-            // d[ct][i] = channel ct*16 + 4*g + i of link e0 + n16
-            if (valid) {
-#pragma unroll
-                for (int ct = 0; ct < kNCT; ++ct) *reinterpret_cast<f32x4*>(dst + ct * 16) = av[ct] + d[ct];
-            }
+            flush_write(prev, av);
 #pragma unroll
             for (int s = 0; s < kGroups; ++s) xf_c[s] = xf_n[s];
+            // scheduling hint: one MFMA, then a few of the other instructions, repeated
+            if constexpr (kIsF32) {
+#pragma unroll
+                for (int r = 0; r < 8; ++r) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);  // VALU
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // VMEM read
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // DS write
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                }
+            }
         };
+        int done = 0;  // number of blocks computed; the last one's result is still to be added
         for (int b = 0; b < nblk; b += 3) {
-            body(b, slot0, slot1);
+            body(b, slot0, slot1, res0, res2);
+            done = b + 1;
             if (b + 1 >= nblk) break;
-            body(b + 1, slot1, slot2);
+            body(b + 1, slot1, slot2, res1, res0);
+            done = b + 2;
             if (b + 2 >= nblk) break;
-            body(b + 2, slot2, slot0);
+            body(b + 2, slot2, slot0, res2, res1);
+            done = b + 3;
         }
+        const int last_set = (done + 2) % 3;  // set of block done-1
+        f32x4 av[kNCT];
+        if (last_set == 0) { flush_read(res0, av); flush_write(res0, av); }
+        else if (last_set == 1) { flush_read(res1, av); flush_write(res1, av); }
+        else { flush_read(res2, av); flush_write(res2, av); }
     }
     wave_sync();
     const int co0 = blockIdx.y * COT;
@@ -440,6 +494,7 @@ int launch_wave(GatherArgs a, hipStream_t s) {
     using Cfg = WaveCfg<T, CC, COT>;
     auto kern = gather_wave_kernel<T, CC, COT>;
     a.lds_per_wave = Cfg::per_wave_bytes(a.kvol);
+    a.w_bytes = (uint32_t)((size_t)a.kvol * a.co_total * CC * sizeof(T));
     const int lds = kWavesPerGroup * a.lds_per_wave;
     static int attr_lds = 0;  // largest dynamic LDS size opted into so far
     if (lds > attr_lds) {
@@ -537,11 +592,11 @@ int dispatch_co(const GatherArgs& a, hipStream_t s) {
     // in 32 fragment registers (CC/group * COT/16 fragments of 4 registers each).
     constexpr int kGroups = CC / (std::is_same<T, float>::value ? 16 : 32);
     if constexpr (kGroups * 4 <= 8)
-        if (a.co_total % 64 == 0) return launch_wave<T, CC, 64>(a, s);
+        if (a.wave_ok && a.co_total % 64 == 0) return launch_wave<T, CC, 64>(a, s);
     if constexpr (kGroups * 2 <= 8)
-        if (a.co_total % 32 == 0) return launch_wave<T, CC, 32>(a, s);
+        if (a.wave_ok && a.co_total % 32 == 0) return launch_wave<T, CC, 32>(a, s);
     if constexpr (kGroups <= 2)
-        if (a.co_total == 16 || a.co_total == 48) return launch_wave<T, CC, 16>(a, s);
+        if (a.wave_ok && (a.co_total == 16 || a.co_total == 48)) return launch_wave<T, CC, 16>(a, s);
     // Wide layers: workgroup-cooperative kernel; rows per workgroup keep accumulator + staging within
     // ~64 KB so two workgroups share a CU
     if (a.co_total % 64 == 0) return launch_gather<T, CC, 64, 128>(a, s);
@@ -574,9 +629,10 @@ bool mma_shape_ok(int cc, int co, sp_dtype dt) {
 
 // side: which rows are destinations.  w_transposed = false: W[k][co][cc] as stored (forward);
 // true: the stored W is [k][cc][co] (data gradient), transposed into pool memory first for the MFMA path.
-int conv_gather(const MapSide& side, int kvol, const void* d_f, const void* d_w, bool w_transposed, void* d_g, int cc,
-                int co, sp_dtype dt, hipStream_t s) {
+int conv_gather(const MapSide& side, int kvol, int64_t total_links, const void* d_f, const void* d_w, bool w_transposed,
+                void* d_g, int cc, int co, sp_dtype dt, hipStream_t s) {
     if (side.n_rows == 0) return SP_OK;
+    const size_t elt = dt == SP_F32 ? 4 : 2;
     if (mma_shape_ok(cc, co, dt)) {
         GatherArgs a;
         a.tl_off = ptr<int32_t>(side.tl_off);
@@ -585,6 +641,11 @@ int conv_gather(const MapSide& side, int kvol, const void* d_f, const void* d_w,
         a.f = d_f;
         a.w = d_w;
         a.w_transposed = w_transposed ? 1 : 0;
+        const uint64_t fb = (uint64_t)side.n_src * cc * elt, sb = (uint64_t)total_links * 4;
+        a.wave_ok = fb < 0xffffffffull && sb < 0xffffffffull;
+        a.f_bytes = (uint32_t)fb;
+        a.src_bytes = (uint32_t)sb;
+        a.row_bytes = (uint32_t)((uint64_t)total_links * 2);
         a.g = d_g;
         a.n_rows = side.n_rows;
         a.kvol = kvol;
@@ -631,13 +692,13 @@ extern "C" {
 int sp_conv_fwd(const sp_kmap_t* m, const void* d_x, const void* d_w, void* d_y, int32_t cin, int32_t cout,
                 sp_dtype dt, void* stream) {
     SP_TRY(check_conv_args(m, d_x, m ? m->n_in : 0, d_w, d_y, m ? m->n_out : 0, cin, cout, dt));
-    return conv_gather(m->out_side, m->kvol, d_x, d_w, false, d_y, cin, cout, dt, (hipStream_t)stream);
+    return conv_gather(m->out_side, m->kvol, m->total, d_x, d_w, false, d_y, cin, cout, dt, (hipStream_t)stream);
 }
 
 int sp_conv_bwd_data(const sp_kmap_t* m, const void* d_dy, const void* d_w, void* d_dx, int32_t cin, int32_t cout,
                      sp_dtype dt, void* stream) {
     SP_TRY(check_conv_args(m, d_dy, m ? m->n_out : 0, d_w, d_dx, m ? m->n_in : 0, cin, cout, dt));
-    return conv_gather(m->in_side, m->kvol, d_dy, d_w, true, d_dx, cout, cin, dt, (hipStream_t)stream);
+    return conv_gather(m->in_side, m->kvol, m->total, d_dy, d_w, true, d_dx, cout, cin, dt, (hipStream_t)stream);
 }
 
 }  // extern "C"
