@@ -14,43 +14,59 @@ __global__ __launch_bounds__(256) void fill_i32_kernel(int32_t* __restrict__ p, 
     if (i < n) p[i] = v;
 }
 
-// grid (tiles of n_out, kvol).  Thread (o, k) probes c_out[o] + offset_k * step in the input table.
+// grid (tiles of n_out, K*K).  Thread (o, ax, ay) probes the K offsets (ax, ay, 0..K-1): the K searches of
+// one thread are independent, so their memory latencies overlap, and the row's coordinates are read once.
 // Writes nbr_out[k][o]; scatters nbr_in[k][i] = o when nbr_in is given; counts live links per 64-row
 // sub-tile (sub_counts[(tile*4 + wave)*kvol + k]) and per tile (blk_counts[k*ntiles + tile]).
+template <int K>
 __global__ __launch_bounds__(kThreads) void probe_kernel(const int4* __restrict__ c_out, int64_t n_out,
-                                                         const HashSlot* __restrict__ tab, uint32_t cap, int K,
-                                                         int step, int identity_k, int32_t* __restrict__ nbr_out,
+                                                         const HashSlot* __restrict__ tab, uint32_t cap, int step,
+                                                         int identity_k, int32_t* __restrict__ nbr_out,
                                                          int32_t* __restrict__ nbr_in, int64_t n_in,
                                                          int32_t* __restrict__ sub_counts,
                                                          int32_t* __restrict__ blk_counts) {
-    __shared__ int s_cnt[kSubTiles];
-    const int k = blockIdx.y, kvol = gridDim.y;
+    __shared__ int s_cnt[K][kSubTiles];
+    constexpr int kvol = K * K * K;
+    const int ay = blockIdx.y % K, ax = blockIdx.y / K;
     const int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    const int az = k % K, ay = (k / K) % K, ax = k / (K * K);
-    const int centre = (K & 1) ? (K - 1) / 2 : 0;
-    int32_t v = -1;
+    constexpr int centre = (K & 1) ? (K - 1) / 2 : 0;
+    const int k0 = (ax * K + ay) * K;
+    int32_t v[K];
+#pragma unroll
+    for (int az = 0; az < K; ++az) v[az] = -1;
     if (o < n_out) {
-        if (k == identity_k) {
-            v = (int32_t)o;
-        } else {
-            int4 c = c_out[o];
-            uint64_t key;
-            if (pack_key(c.x, c.y + (ax - centre) * step, c.z + (ay - centre) * step, c.w + (az - centre) * step, &key))
-                v = hash_find(tab, cap, key);
+        const int4 c = c_out[o];
+        uint64_t key[K];
+        bool ok[K];
+#pragma unroll
+        for (int az = 0; az < K; ++az)
+            ok[az] = pack_key(c.x, c.y + (ax - centre) * step, c.z + (ay - centre) * step, c.w + (az - centre) * step,
+                              &key[az]);
+#pragma unroll
+        for (int az = 0; az < K; ++az) {
+            if (k0 + az == identity_k) v[az] = (int32_t)o;
+            else if (ok[az]) v[az] = hash_find(tab, cap, key[az]);
         }
-        nbr_out[(int64_t)k * n_out + o] = v;
-        if (nbr_in && v >= 0) nbr_in[(int64_t)k * n_in + v] = (int32_t)o;
+#pragma unroll
+        for (int az = 0; az < K; ++az) {
+            nbr_out[(int64_t)(k0 + az) * n_out + o] = v[az];
+            if (nbr_in && v[az] >= 0) nbr_in[(int64_t)(k0 + az) * n_in + v[az]] = (int32_t)o;
+        }
     }
-    const unsigned long long live = __ballot(v >= 0);
     const int w = threadIdx.x >> 6;
-    if ((threadIdx.x & 63) == 0) {
-        int c = __popcll(live);
-        s_cnt[w] = c;
-        sub_counts[((int64_t)blockIdx.x * kSubTiles + w) * kvol + k] = c;
+#pragma unroll
+    for (int az = 0; az < K; ++az) {
+        const unsigned long long live = __ballot(v[az] >= 0);
+        if ((threadIdx.x & 63) == 0) {
+            const int c = __popcll(live);
+            s_cnt[az][w] = c;
+            sub_counts[((int64_t)blockIdx.x * kSubTiles + w) * kvol + k0 + az] = c;
+        }
     }
     __syncthreads();
-    if (threadIdx.x == 0 && blk_counts)
-        blk_counts[(int64_t)k * gridDim.x + blockIdx.x] = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
+    if (threadIdx.x < K && blk_counts)
+        blk_counts[(int64_t)(k0 + threadIdx.x) * gridDim.x + blockIdx.x] =
+            s_cnt[threadIdx.x][0] + s_cnt[threadIdx.x][1] + s_cnt[threadIdx.x][2] + s_cnt[threadIdx.x][3];
 }
 
 // Same counting from an existing table (the scattered input-side table of a strided map).
@@ -178,12 +194,21 @@ int sp_kmap_build(const sp_coords_t* in, int32_t kernel_size, int32_t stride, in
     }
     int32_t* d_koff = ptr<int32_t>(small);
     if (nt_out > 0) {
-        hipLaunchKernelGGL(probe_kernel, dim3((unsigned)nt_out, kvol), dim3(kThreads), 0, s,
-                           ptr<int4>(m->c_out->coords), n_out, ptr<HashSlot>(in->tab.slots), in->tab.cap,
-                           kernel_size, step,
-                           symmetric ? (kvol - 1) / 2 : -1, ptr<int32_t>(so.nbr),
-                           symmetric ? (int32_t*)nullptr : ptr<int32_t>(si.nbr), n_in, ptr<int32_t>(so.tl_off),
-                           ptr<int32_t>(blk));
+        const dim3 grid((unsigned)nt_out, (unsigned)(kernel_size * kernel_size));
+        const int identity_k = symmetric ? (kvol - 1) / 2 : -1;
+        int32_t* nbr_in_arg = symmetric ? (int32_t*)nullptr : ptr<int32_t>(si.nbr);
+#define SP_LAUNCH_PROBE(KS)                                                                                     \
+    hipLaunchKernelGGL(probe_kernel<KS>, grid, dim3(kThreads), 0, s, ptr<int4>(m->c_out->coords), n_out,          \
+                       ptr<HashSlot>(in->tab.slots), in->tab.cap, step, identity_k, ptr<int32_t>(so.nbr), nbr_in_arg, \
+                       n_in, ptr<int32_t>(so.tl_off), ptr<int32_t>(blk))
+        switch (kernel_size) {
+            case 1: SP_LAUNCH_PROBE(1); break;
+            case 2: SP_LAUNCH_PROBE(2); break;
+            case 3: SP_LAUNCH_PROBE(3); break;
+            case 4: SP_LAUNCH_PROBE(4); break;
+            default: SP_LAUNCH_PROBE(5); break;
+        }
+#undef SP_LAUNCH_PROBE
     }
     SP_HIP(hipGetLastError());
     // both scans in one launch pair: sub-tile-major list offsets, and offset-major pair-list offsets whose

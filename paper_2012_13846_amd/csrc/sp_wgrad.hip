@@ -64,41 +64,59 @@ __global__ __launch_bounds__(256) void wgrad_partial_kernel(const int32_t* __res
 #pragma unroll
         for (int b = 0; b < NCI; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // software pipeline: link indices two steps ahead, rows one step ahead of the MFMAs that use them
-    const int64_t first_p = it.beg + wave * 4 + g;
-    auto load_idx = [&](int64_t p, int32_t& o, int32_t& i) {
-        const bool live = p < it.end;
-        o = live ? pair_out[p] : -1;
-        i = live ? pair_in[p] : 0;
-    };
-    auto load_rows = [&](int32_t o, int32_t i, float (&av)[NCO], float (&bv)[NCI]) {
-        const bool live = o >= 0;
+    // Software pipeline in super-steps of kU steps (kU * 4 links per wavefront): the rows of super-step s+1
+    // and the link indices of super-step s+2 are requested before the MFMAs of super-step s are issued.
+    constexpr int kU = 4;
+    const int64_t first_p = it.beg + wave * 4 + g;  // this lane's link in step 0; step j is 16*j further
+    auto load_idx = [&](int64_t p, int32_t (&o)[kU], int32_t (&i)[kU]) {
 #pragma unroll
-        for (int a = 0; a < NCO; ++a) av[a] = live ? load_f32(dY + (size_t)o * cout + co0 + a * 16 + n16) : 0.f;
-#pragma unroll
-        for (int b = 0; b < NCI; ++b) bv[b] = live ? load_f32(X + (size_t)i * cin + ci0 + b * 16 + n16) : 0.f;
+        for (int u = 0; u < kU; ++u) {
+            const bool live = p + 16 * u < it.end;
+            o[u] = live ? pair_out[p + 16 * u] : -1;
+            i[u] = live ? pair_in[p + 16 * u] : 0;
+        }
     };
-    int32_t o1, i1, o2, i2;
-    float av[NCO], bv[NCI];
-    load_idx(first_p, o1, i1);
-    load_idx(first_p + 16, o2, i2);
-    load_rows(o1, i1, av, bv);
-    for (int64_t p = first_p; p - g < it.end; p += 16) {
-        float an[NCO], bn[NCI];
-        int32_t o3, i3;
-        load_idx(p + 32, o3, i3);
+    auto load_rows = [&](const int32_t (&o)[kU], const int32_t (&i)[kU], float (&av)[kU][NCO], float (&bv)[kU][NCI]) {
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const bool live = o[u] >= 0;
+            const T* dyp = dY + (size_t)(live ? o[u] : 0) * cout + co0 + n16;
+            const T* xp = X + (size_t)(live ? i[u] : 0) * cin + ci0 + n16;
+#pragma unroll
+            for (int a = 0; a < NCO; ++a) av[u][a] = live ? load_f32(dyp + a * 16) : 0.f;
+#pragma unroll
+            for (int b = 0; b < NCI; ++b) bv[u][b] = live ? load_f32(xp + b * 16) : 0.f;
+        }
+    };
+    int32_t o2[kU], i2[kU];
+    float av[kU][NCO], bv[kU][NCI];
+    {
+        int32_t o1[kU], i1[kU];
+        load_idx(first_p, o1, i1);
+        load_idx(first_p + 16 * kU, o2, i2);
+        load_rows(o1, i1, av, bv);
+    }
+    for (int64_t p = first_p; p - g < it.end; p += 16 * kU) {
+        float an[kU][NCO], bn[kU][NCI];
+        int32_t o3[kU], i3[kU];
+        load_idx(p + 32 * kU, o3, i3);
         load_rows(o2, i2, an, bn);
 #pragma unroll
-        for (int a = 0; a < NCO; ++a)
+        for (int u = 0; u < kU; ++u)
 #pragma unroll
-            for (int b = 0; b < NCI; ++b)
-                acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[a], bv[b], acc[a][b], 0, 0, 0);
+            for (int a = 0; a < NCO; ++a)
 #pragma unroll
-        for (int a = 0; a < NCO; ++a) av[a] = an[a];
+                for (int b = 0; b < NCI; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][a], bv[u][b], acc[a][b], 0, 0, 0);
 #pragma unroll
-        for (int b = 0; b < NCI; ++b) bv[b] = bn[b];
-        o2 = o3;
-        i2 = i3;
+        for (int u = 0; u < kU; ++u) {
+#pragma unroll
+            for (int a = 0; a < NCO; ++a) av[u][a] = an[u][a];
+#pragma unroll
+            for (int b = 0; b < NCI; ++b) bv[u][b] = bn[u][b];
+            o2[u] = o3[u];
+            i2[u] = i3[u];
+        }
     }
     // acc[a][b][j] is element (co = a*16 + 4*g + j, ci = b*16 + n16); add the 4 wavefronts in order
     for (int w = 0; w < 4; ++w) {
