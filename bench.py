@@ -28,6 +28,12 @@ PEAK_F32_MFMA_TFLOPS = 157.3   # MI355X dense fp32 matrix-core peak
 PEAK_BF16_MFMA_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
 
+# HBM-side bytes per launch of the forward gather kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each
+# scaled by what the counter reads for a plain copy of known size (see the files under profiles/).
+MEASURED_TRAFFIC_BYTES = {
+    "cfg1_k3s1_c32x64_f32": 92.2e6,   # profiles/step_cfg1_k3s1_c32x64_f32.txt: 66.4 MB read + 25.8 MB written
+}
+
 WORKLOADS = {
     # name: (config index, kernel, stride, dilation, cin, cout, bf16)
     "cfg1_k3s1_c32x64_f32": (1, 3, 1, 1, 32, 64, False),
@@ -72,6 +78,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg1_k3s1_c32x64_f32", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain device copy of known size (256 MiB read + 256 MiB written per launch): "
+                         "the reference the FETCH_SIZE / WRITE_SIZE counters are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (no collectives, no sharding); run with --gpus 1",
@@ -85,6 +94,15 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     sp.lib()
+    if args.copy_calibration:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": True, "bytes_read_per_launch": src.numel() * 4,
+                          "bytes_written_per_launch": src.numel() * 4, "launches": 10}))
+        return
 
     cfg, K, stride, dil, cin, cout, bf16 = WORKLOADS[args.workload]
     seed = spgen.seed_for(cfg, 0, stream=1)
@@ -140,12 +158,27 @@ def main():
     value = 3.0 * flops_conv / (ms_per_step * 1e-3) / 1e12
     peak = PEAK_BF16_MFMA_TFLOPS if bf16 else PEAK_F32_MFMA_TFLOPS
 
-    # dominant kernel: the gather-GEMM kernel of sp_conv_fwd (one launch per call; the same kernel serves
-    # the data gradient).  Its duration is the event-bracketed time of the call on the launch stream.
-    fwd_s = stage_ms["conv_fwd"] * 1e-3
-    roofline = {"bound": "mfma", "kernel": "gather_mma_kernel (sp_conv_fwd)",
+    # Dominant kernel: the gather-GEMM kernel of sp_conv_fwd (the same kernel serves the data gradient).
+    # Timed live with events on the launch stream over a run of back-to-back calls on the last step's map;
+    # each call is that kernel plus the ~3 us fragment-major weight copy that precedes it.
+    c = sp.sp_coords_build(raw, 1)
+    km, co = sp.sp_kmap_build(c, K, stride, dil)
+    reps = 30
+    for _ in range(3):
+        sp.sp_conv_fwd(km, x, w, out=y)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        sp.sp_conv_fwd(km, x, w, out=y)
+    e1.record()
+    torch.cuda.synchronize()
+    fwd_s = e0.elapsed_time(e1) / reps * 1e-3
+    km.close(), co.close(), c.close()
+    traffic = MEASURED_TRAFFIC_BYTES.get(args.workload)
+    roofline = {"bound": "mfma", "kernel": "gather_wave_kernel (sp_conv_fwd)",
                 "achieved": flops_conv / fwd_s / 1e12, "peak": peak, "unit": "TFLOP/s",
-                "frac": flops_conv / fwd_s / 1e12 / peak, "traffic": None}
+                "frac": flops_conv / fwd_s / 1e12 / peak, "traffic": traffic,
+                "launch_us": round(fwd_s * 1e6, 2), "flops_per_launch": flops_conv}
     esz = 2 if bf16 else 4
     compulsory = n_in * cin * esz + n_out * cout * esz + pairs * 6 + K ** 3 * cin * cout * esz
     stages = {n: {"ms": round(stage_ms[n], 4)} for n in names}
