@@ -38,6 +38,7 @@ struct GatherArgs {
     int co_total;
     int flip;        // weight matrix of list k is kvol-1-k
     int lds_per_wave;  // bytes of LDS of one wavefront in gather_wave_kernel
+    int split_blocks;  // sub-tiles with at least this many 16-link blocks are shared by two wavefronts
     uint32_t f_bytes, w_bytes, src_bytes, row_bytes;  // sizes of f / w / tl_src / tl_row for buffer addressing (< 4 GiB)
     int wave_ok;       // host-side only: buffers small enough for 32-bit buffer addressing
     int w_transposed;  // host-side only: the stored weights are [k][cc][co] (data gradient) instead of [k][co][cc]
@@ -96,8 +97,8 @@ __global__ __launch_bounds__(256) void gather_mma_kernel(GatherArgs a) {
         int sb[kNQ], sl[kNQ], mtot = 0;
 #pragma unroll
         for (int q = 0; q < kNQ; ++q) {
-            sb[q] = a.tl_off[(wt0 + q) * a.kvol + kk];
-            sl[q] = a.tl_off[(wt0 + q) * a.kvol + kk + 1] - sb[q];
+            sb[q] = a.tl_off[((wt0 + q) * a.kvol + kk) * kHalves];
+            sl[q] = a.tl_off[((wt0 + q) * a.kvol + kk + 1) * kHalves] - sb[q];
             mtot += sl[q];
         }
         if (mtot == 0) continue;
@@ -223,10 +224,8 @@ __device__ __forceinline__ void wave_sync() {
     __builtin_amdgcn_wave_barrier();
 }
 
-constexpr int kWavesPerGroup = 1;  // wavefronts are independent; small groups give the scheduler the most freedom
-
 template <typename T, int CC, int COT>
-__global__ __launch_bounds__(64 * kWavesPerGroup) void gather_wave_kernel(GatherArgs a) {
+__global__ __launch_bounds__(64) void gather_wave_kernel(GatherArgs a) {
     using Cfg = WaveCfg<T, CC, COT>;
     constexpr bool kIsF32 = Cfg::kIsF32;
     constexpr int kGroups = Cfg::kGroups, kNCT = Cfg::kNCT, kPieces = Cfg::kPieces, kXLoads = Cfg::kXLoads;
@@ -236,10 +235,14 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void gather_wave_kernel(Gather
     constexpr int kDepth = 3;  // blocks whose gathers are in flight
 
     extern __shared__ __align__(16) unsigned char smem[];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t wt = (int64_t)blockIdx.x * kWavesPerGroup + wave;  // this wavefront's sub-tile
-    if (wt >= (a.n_rows + 63) / 64) return;             // whole wavefront leaves; nobody waits for it
-    unsigned char* base = smem + (size_t)wave * a.lds_per_wave;
+    const int lane = threadIdx.x & 63;
+    // grid.x = 2 * sub-tiles: the first half of the grid takes half 0 (or the whole sub-tile), the second half
+    // of the grid half 1.  (Workgroups are dealt to the 8 XCDs round-robin: pairing (u,0),(u,1) on adjacent
+    // indices would leave every other XCD with nothing but wavefronts that leave at once.)
+    const int64_t nwt = (a.n_rows + 63) / 64;
+    const int half = blockIdx.x >= nwt ? 1 : 0;     // which 32-row half it takes if the sub-tile is split
+    const int64_t wt = (int64_t)blockIdx.x - (half ? nwt : 0);  // this wavefront's sub-tile
+    unsigned char* base = smem;
     float* acc = reinterpret_cast<float*>(base);
     unsigned char* xbuf = base + Cfg::kAccBytes;
     int* s_blk = reinterpret_cast<int*>(xbuf + Cfg::kXBytes);
@@ -249,12 +252,31 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void gather_wave_kernel(Gather
     for (int i = lane; i < Cfg::kAccBytes / 16; i += 64) reinterpret_cast<f32x4*>(acc)[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     // ---- block descriptors: k | (links-1) << 7 | (blocks left in this offset - 1) << 11 | (first link - off0) << 13
-    const int32_t* __restrict__ offp = a.tl_off + wt * kvol;
+    // Two wavefronts are launched per sub-tile.  When the launch is small (a.split_blocks set by the host)
+    // and the sub-tile is long, each takes one 32-row half, which halves the longest dependent chain of the
+    // launch; otherwise the first takes all 64 rows and the second leaves.
+    const int32_t* __restrict__ offp = a.tl_off + wt * kvol * kHalves;
     const int off0 = offp[0];
+    int nblk_whole = 0;
+    for (int kb = 0; kb < kvol; kb += 64) {
+        const int k = kb + lane;
+        int nb = k < kvol ? (offp[(k + 1) * kHalves] - offp[k * kHalves] + 15) >> 4 : 0;
+#pragma unroll
+        for (int d = 32; d > 0; d >>= 1) nb += __shfl_xor(nb, d, 64);
+        nblk_whole += nb;
+    }
+    const bool split = nblk_whole >= a.split_blocks;
+    if (!split && half == 1) return;
+    const int row_base = split ? 32 * half : 0;
+    const int row_count = split ? 32 : 64;
     int nblk = 0;
     for (int kb = 0; kb < kvol; kb += 64) {
         const int k = kb + lane;
-        const int o0 = k < kvol ? offp[k] : 0, o1 = k < kvol ? offp[k + 1] : 0;
+        int o0 = 0, o1 = 0;
+        if (k < kvol) {
+            o0 = offp[k * kHalves + (split ? half : 0)];
+            o1 = offp[k * kHalves + (split ? half + 1 : kHalves)];
+        }
         const int cnt = o1 - o0, nb = (cnt + 15) >> 4;
         int inc = nb;
 #pragma unroll
@@ -316,7 +338,7 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void gather_wave_kernel(Gather
     };
     auto issue_gather = [&](Slot& sl) __attribute__((always_inline)) {
         sl.dc = sl.de;
-        sl.drow = sl.erow & 63;
+        sl.drow = (sl.erow & 63) - row_base;
 #pragma unroll
         for (int t = 0; t < kXLoads; ++t)
             sl.x[t] = __builtin_amdgcn_raw_buffer_load_b128(rF, sl.esrc[t] * Cfg::kRowBytes + ((t * 64 + lane) % kPieces) * 16, 0, 0);
@@ -448,9 +470,9 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void gather_wave_kernel(Gather
     wave_sync();
     const int co0 = blockIdx.y * COT;
     constexpr int kQuads = COT / 4;
-    for (int idx = lane; idx < 64 * kQuads; idx += 64) {
+    for (int idx = lane; idx < row_count * kQuads; idx += 64) {
         const int r = idx / kQuads, c4 = (idx % kQuads) * 4;
-        const int64_t row = wt * 64 + r;
+        const int64_t row = wt * 64 + row_base + r;
         if (row >= a.n_rows) break;
         const f32x4 v = *reinterpret_cast<const f32x4*>(acc + r * Cfg::kStride + c4);
         if constexpr (kIsF32) {
@@ -495,7 +517,7 @@ int launch_wave(GatherArgs a, hipStream_t s) {
     auto kern = gather_wave_kernel<T, CC, COT>;
     a.lds_per_wave = Cfg::per_wave_bytes(a.kvol);
     a.w_bytes = (uint32_t)((size_t)a.kvol * a.co_total * CC * sizeof(T));
-    const int lds = kWavesPerGroup * a.lds_per_wave;
+    const int lds = a.lds_per_wave;  // one wavefront per workgroup: they are independent, small groups place freely
     static int attr_lds = 0;  // largest dynamic LDS size opted into so far
     if (lds > attr_lds) {
         SP_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds));
@@ -510,8 +532,14 @@ int launch_wave(GatherArgs a, hipStream_t s) {
                        static_cast<const T*>(a.w), ptr<T>(wf), a.kvol, a.co_total, s_co, s_cc);
     a.w = wf->p;
     const int64_t nwt = (a.n_rows + 63) / 64;
-    dim3 grid((unsigned)((nwt + kWavesPerGroup - 1) / kWavesPerGroup), (unsigned)(a.co_total / COT));
-    hipLaunchKernelGGL(kern, grid, dim3(64 * kWavesPerGroup), lds, s, a);
+    // A launch whose sub-tiles fit the GPU's LDS at once runs as long as its longest wavefront: then long
+    // sub-tiles (48 blocks and more, against a typical 27-35; measured best of 32..64) are shared by two
+    // wavefronts.  Larger launches
+    // run in several rounds, where splitting would only add padding.
+    const int64_t resident_tiles = 256 * (160 * 1024 / (int64_t)a.lds_per_wave);
+    a.split_blocks = (nwt * (a.co_total / COT) * 5 / 4 <= resident_tiles) ? 48 : 0x7fffffff;
+    dim3 grid((unsigned)(2 * nwt), (unsigned)(a.co_total / COT));
+    hipLaunchKernelGGL(kern, grid, dim3(64), lds, s, a);
     SP_HIP(hipGetLastError());
     return SP_OK;  // wf goes back to the pool; later users are ordered behind this launch on the stream
 }

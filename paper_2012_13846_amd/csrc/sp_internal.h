@@ -75,6 +75,7 @@ int coords_build_impl(const int32_t* d_src, int64_t n_src, int32_t floor_step, i
 
 constexpr int kTileRows = 256;   // rows per tile of the tile lists (= map-build block size)
 constexpr int kSubTiles = 4;     // 64-row sub-tiles (one wavefront ballot each) per tile
+constexpr int kHalves = 2;       // list offsets are kept per 32-row half of a sub-tile
 
 }  // namespace sp
 
@@ -90,12 +91,12 @@ struct sp_coords {
 namespace sp {
 
 // One direction of a kernel map, as the gather-GEMM kernel consumes it: `n_rows` destination rows in tiles
-// of kTileRows; for (64-row sub-tile u, offset k) the entries [off[u*kvol+k], off[u*kvol+k+1])
+// of kTileRows; for (64-row sub-tile u, offset k, 32-row half h) the entries [off[(u*kvol+k)*2+h], off[(u*kvol+k)*2+h+1])
 // of src/row list the live (source row, destination row within the tile) links, destination rows ascending.
 struct MapSide {
     int64_t n_rows = 0, n_src = 0;
     Buf nbr;      // int32 [kvol][n_rows]: source row or -1
-    Buf tl_off;   // int32 [nsub*kvol + 1], nsub = 4*ntiles, index sub*kvol + k (sub-tile-major)
+    Buf tl_off;   // int32 [nsub*kvol*2 + 1], nsub = 4*ntiles, index (sub*kvol + k)*2 + half (sub-tile-major)
     Buf tl_src;   // int32 [total]
     Buf tl_row;   // uint16 [total]
     bool flip = false;  // weight offset index = kvol-1-k (side derived by the stride-1 symmetry)

@@ -17,7 +17,7 @@ __global__ __launch_bounds__(256) void fill_i32_kernel(int32_t* __restrict__ p, 
 // grid (tiles of n_out, K*K).  Thread (o, ax, ay) probes the K offsets (ax, ay, 0..K-1): the K searches of
 // one thread are independent, so their memory latencies overlap, and the row's coordinates are read once.
 // Writes nbr_out[k][o]; scatters nbr_in[k][i] = o when nbr_in is given; counts live links per 64-row
-// sub-tile (sub_counts[(tile*4 + wave)*kvol + k]) and per tile (blk_counts[k*ntiles + tile]).
+// half sub-tile (sub_counts[((tile*4 + wave)*kvol + k)*2 + half]) and per tile (blk_counts[k*ntiles + tile]).
 template <int K>
 __global__ __launch_bounds__(kThreads) void probe_kernel(const int4* __restrict__ c_out, int64_t n_out,
                                                          const HashSlot* __restrict__ tab, uint32_t cap, int step,
@@ -58,9 +58,11 @@ __global__ __launch_bounds__(kThreads) void probe_kernel(const int4* __restrict_
     for (int az = 0; az < K; ++az) {
         const unsigned long long live = __ballot(v[az] >= 0);
         if ((threadIdx.x & 63) == 0) {
-            const int c = __popcll(live);
-            s_cnt[az][w] = c;
-            sub_counts[((int64_t)blockIdx.x * kSubTiles + w) * kvol + k0 + az] = c;
+            const int lo = __popc((unsigned)live), hi = __popc((unsigned)(live >> 32));
+            s_cnt[az][w] = lo + hi;
+            int32_t* dst = sub_counts + (((int64_t)blockIdx.x * kSubTiles + w) * kvol + k0 + az) * kHalves;
+            dst[0] = lo;
+            dst[1] = hi;
         }
     }
     __syncthreads();
@@ -76,8 +78,11 @@ __global__ __launch_bounds__(kThreads) void count_kernel(const int32_t* __restri
     const int64_t r = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     const int32_t v = r < n_rows ? nbr[(int64_t)k * n_rows + r] : -1;
     const unsigned long long live = __ballot(v >= 0);
-    if ((threadIdx.x & 63) == 0)
-        sub_counts[((int64_t)blockIdx.x * kSubTiles + (threadIdx.x >> 6)) * kvol + k] = __popcll(live);
+    if ((threadIdx.x & 63) == 0) {
+        int32_t* dst = sub_counts + (((int64_t)blockIdx.x * kSubTiles + (threadIdx.x >> 6)) * kvol + k) * kHalves;
+        dst[0] = __popc((unsigned)live);
+        dst[1] = __popc((unsigned)(live >> 32));
+    }
 }
 
 // Compaction: every live (row, k) writes its entry at offset + (number of live lanes below it).
@@ -92,9 +97,11 @@ __global__ __launch_bounds__(kThreads) void emit_kernel(const int32_t* __restric
     const int32_t v = r < n_rows ? nbr[(int64_t)k * n_rows + r] : -1;
     const unsigned long long live = __ballot(v >= 0);
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int pos = __popcll(live & ((1ull << lane) - 1ull));
+    const int pos = __popcll(live & ((1ull << lane) - 1ull));  // among the wavefront's 64 rows
     if (v >= 0) {
-        const int64_t e = (int64_t)tl_off[((int64_t)blockIdx.x * kSubTiles + w) * kvol + k] + pos;
+        // the two 32-row halves of a sub-tile are adjacent in the list, so the position inside the sub-tile's
+        // stretch is the plain 64-lane rank
+        const int64_t e = (int64_t)tl_off[(((int64_t)blockIdx.x * kSubTiles + w) * kvol + k) * kHalves] + pos;
         tl_src[e] = v;
         tl_row[e] = (uint16_t)threadIdx.x;
     }
@@ -177,7 +184,7 @@ int sp_kmap_build(const sp_coords_t* in, int32_t kernel_size, int32_t stride, in
     so.n_rows = n_out;
     so.n_src = n_in;
     so.nbr = dev_alloc((size_t)(n_out ? n_out : 1) * kvol * 4);
-    so.tl_off = dev_alloc((size_t)(nt_out * kvol * kSubTiles + 1) * 4);
+    so.tl_off = dev_alloc((size_t)(nt_out * kvol * kSubTiles * kHalves + 1) * 4);
     Buf blk = dev_alloc((size_t)(nt_out * kvol + 1) * 4);
     Buf small = dev_alloc((size_t)(kvol + 2) * 4);  // [0..kvol] koff, [kvol+1] scratch total
     if (!so.nbr || !so.tl_off || !blk || !small) return SP_ERR_ALLOC;
@@ -186,7 +193,7 @@ int sp_kmap_build(const sp_coords_t* in, int32_t kernel_size, int32_t stride, in
         si.n_rows = n_in;
         si.n_src = n_out;
         si.nbr = dev_alloc((size_t)(n_in ? n_in : 1) * kvol * 4);
-        si.tl_off = dev_alloc((size_t)(nt_in * kvol * kSubTiles + 1) * 4);
+        si.tl_off = dev_alloc((size_t)(nt_in * kvol * kSubTiles * kHalves + 1) * 4);
         if (!si.nbr || !si.tl_off) return SP_ERR_ALLOC;
         if (n_in > 0)
             hipLaunchKernelGGL(fill_i32_kernel, dim3(blocks256(n_in * kvol)), dim3(256), 0, s, ptr<int32_t>(si.nbr),
@@ -214,7 +221,7 @@ int sp_kmap_build(const sp_coords_t* in, int32_t kernel_size, int32_t stride, in
     // both scans in one launch pair: sub-tile-major list offsets, and offset-major pair-list offsets whose
     // values at the start of each offset (every nt_out-th element) are the per-offset prefix koff[]
     {
-        const int64_t n_sub = nt_out * kvol * kSubTiles;
+        const int64_t n_sub = nt_out * kvol * kSubTiles * kHalves;
         ScanJob jobs[2];
         jobs[0].data = ptr<int32_t>(so.tl_off);
         jobs[0].n = n_sub;
@@ -246,7 +253,7 @@ int sp_kmap_build(const sp_coords_t* in, int32_t kernel_size, int32_t stride, in
         if (nt_in > 0)
             hipLaunchKernelGGL(count_kernel, dim3((unsigned)nt_in, kvol), dim3(kThreads), 0, s, ptr<int32_t>(si.nbr),
                                n_in, ptr<int32_t>(si.tl_off));
-        const int64_t n_sub_in = nt_in * kvol * kSubTiles;
+        const int64_t n_sub_in = nt_in * kvol * kSubTiles * kHalves;
         ScanJob job;
         job.data = ptr<int32_t>(si.tl_off);
         job.n = n_sub_in;
