@@ -124,6 +124,45 @@ int sp_conv_bwd_data(const sp_kmap_t* m, const void* d_dy, const void* d_w, void
 int sp_conv_bwd_weight(const sp_kmap_t* m, const void* d_x, const void* d_dy, float* d_dw, int32_t cin,
                        int32_t cout, sp_dtype dt, void* stream);
 
+/* ---- the layers between sparse convolutions ----------------------------------------------------------------
+ * (Sec. III, caption of the partition-overview figure: batch normalisation, activation and pooling layers sit
+ * between the SparseConv blocks; Sec. IV-A: a 40-category classifier.)  The paper gives no formulas; these are
+ * the standard definitions.  Features are [n][c] row-major of storage type dt; parameters, statistics and
+ * everything per cloud are fp32.  Reductions are two-level with a fixed order (reproducible); no host
+ * synchronisation.
+ *
+ * sp_bn_relu_fwd: training-mode batch normalisation over the n rows, per channel, biased variance:
+ *   y = gamma * (x - mean) * rstd + beta, rstd = 1/sqrt(var + eps), then max(y, 0) if relu != 0.
+ *   d_mean / d_rstd [c] are outputs (the backward pass needs them).
+ * sp_bn_relu_bwd: with dyh = dy (masked where y <= 0 if relu), xhat = (x - mean) * rstd:
+ *   dbeta = sum dyh, dgamma = sum dyh * xhat, dx = gamma * rstd / n * (n * dyh - dbeta - xhat * dgamma).
+ *   d_y (the forward output) is only read when relu != 0. */
+int sp_bn_relu_fwd(const void* d_x, int64_t n, int32_t c, const float* d_gamma, const float* d_beta, float eps,
+                   int32_t relu, void* d_y, float* d_mean, float* d_rstd, sp_dtype dt, void* stream);
+int sp_bn_relu_bwd(const void* d_x, const void* d_y, const void* d_dy, int64_t n, int32_t c, const float* d_gamma,
+                   const float* d_mean, const float* d_rstd, int32_t relu, void* d_dx, float* d_dgamma,
+                   float* d_dbeta, sp_dtype dt, void* stream);
+
+/* Global average pooling per cloud: d_out [n_clouds][c] = mean of the rows whose batch index (column 0 of
+ * d_coords [n][4]) is that cloud, zero for an empty cloud; d_counts [n_clouds] = rows per cloud (as float).
+ * Rows with a batch index outside [0, n_clouds) are ignored.  Backward: dx[r] = dout[b(r)] / count[b(r)]. */
+int sp_pool_avg_fwd(const int32_t* d_coords, const void* d_x, int64_t n, int32_t c, int32_t n_clouds, float* d_out,
+                    float* d_counts, sp_dtype dt, void* stream);
+int sp_pool_avg_bwd(const int32_t* d_coords, const float* d_dout, const float* d_counts, int64_t n, int32_t c,
+                    int32_t n_clouds, void* d_dx, sp_dtype dt, void* stream);
+
+/* Linear layer on the pooled features: out [n_clouds][m] = in [n_clouds][c] * w[m][c]^T + bias[m] (bias may be
+ * NULL); backward gives din, dw [m][c], dbias [m]. */
+int sp_linear_fwd(const float* d_in, const float* d_w, const float* d_bias, int32_t n_clouds, int32_t c, int32_t m,
+                  float* d_out, void* stream);
+int sp_linear_bwd(const float* d_in, const float* d_w, const float* d_dout, int32_t n_clouds, int32_t c, int32_t m,
+                  float* d_din, float* d_dw, float* d_dbias, void* stream);
+
+/* Mean over the clouds of -log softmax(logits)[label]: d_loss [1], d_dlogits [n_clouds][m] (gradient of the
+ * mean loss).  labels int32 [n_clouds] in [0, m). */
+int sp_softmax_ce(const float* d_logits, const int32_t* d_labels, int32_t n_clouds, int32_t m, float* d_loss,
+                  float* d_dlogits, void* stream);
+
 /* ---- housekeeping -------------------------------------------------------------------------------------- */
 const char* sp_last_error(void);  /* message of the calling thread's last failure ("" if none) */
 int sp_pool_trim(void);           /* synchronises the device and frees all cached (unused) device memory */

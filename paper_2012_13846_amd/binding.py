@@ -240,3 +240,95 @@ def sp_pool_bytes() -> int:
 
 def sp_version() -> str:
     return lib().sp_version().decode()
+
+
+# ---- the layers between sparse convolutions --------------------------------------------------------------
+def _glue_argtypes():
+    l = lib()
+    if getattr(l, "_glue_ready", False):
+        return l
+    f = C.c_float
+    l.sp_bn_relu_fwd.argtypes = [_vp, C.c_int64, C.c_int32, _vp, _vp, f, C.c_int32, _vp, _vp, _vp, C.c_int32, _vp]
+    l.sp_bn_relu_bwd.argtypes = [_vp, _vp, _vp, C.c_int64, C.c_int32, _vp, _vp, _vp, C.c_int32, _vp, _vp, _vp,
+                                 C.c_int32, _vp]
+    l.sp_pool_avg_fwd.argtypes = [_vp, _vp, C.c_int64, C.c_int32, C.c_int32, _vp, _vp, C.c_int32, _vp]
+    l.sp_pool_avg_bwd.argtypes = [_vp, _vp, _vp, C.c_int64, C.c_int32, C.c_int32, _vp, C.c_int32, _vp]
+    l.sp_linear_fwd.argtypes = [_vp, _vp, _vp, C.c_int32, C.c_int32, C.c_int32, _vp, _vp]
+    l.sp_linear_bwd.argtypes = [_vp, _vp, _vp, C.c_int32, C.c_int32, C.c_int32, _vp, _vp, _vp, _vp]
+    l.sp_softmax_ce.argtypes = [_vp, _vp, C.c_int32, C.c_int32, _vp, _vp, _vp]
+    l._glue_ready = True
+    return l
+
+
+def _f32(shape, dev):
+    return torch.empty(shape, dtype=torch.float32, device=dev)
+
+
+def sp_bn_relu_fwd(x: torch.Tensor, gamma: torch.Tensor, beta: torch.Tensor, eps: float = 1e-5, relu: bool = True):
+    """Returns (y, mean, rstd)."""
+    _need_cuda(x, None, "x"), _need_cuda(gamma, torch.float32, "gamma"), _need_cuda(beta, torch.float32, "beta")
+    n, c = x.shape
+    y, mean, rstd = torch.empty_like(x), _f32((c,), x.device), _f32((c,), x.device)
+    _check(_glue_argtypes().sp_bn_relu_fwd(x.data_ptr(), n, c, gamma.data_ptr(), beta.data_ptr(), eps, int(relu),
+                                           y.data_ptr(), mean.data_ptr(), rstd.data_ptr(), _dt(x), _stream()))
+    return y, mean, rstd
+
+
+def sp_bn_relu_bwd(x, y, dy, gamma, mean, rstd, relu: bool = True):
+    """Returns (dx, dgamma, dbeta)."""
+    _need_cuda(x, None, "x"), _need_cuda(y, x.dtype, "y"), _need_cuda(dy, x.dtype, "dy")
+    n, c = x.shape
+    dx, dgamma, dbeta = torch.empty_like(x), _f32((c,), x.device), _f32((c,), x.device)
+    _check(_glue_argtypes().sp_bn_relu_bwd(x.data_ptr(), y.data_ptr(), dy.data_ptr(), n, c, gamma.data_ptr(),
+                                           mean.data_ptr(), rstd.data_ptr(), int(relu), dx.data_ptr(),
+                                           dgamma.data_ptr(), dbeta.data_ptr(), _dt(x), _stream()))
+    return dx, dgamma, dbeta
+
+
+def sp_pool_avg_fwd(coords: torch.Tensor, x: torch.Tensor, n_clouds: int):
+    """coords: int32 [n][4] (device).  Returns (pooled fp32 [n_clouds][c], counts fp32 [n_clouds])."""
+    _need_cuda(coords, torch.int32, "coords"), _need_cuda(x, None, "x")
+    n, c = x.shape
+    out, counts = _f32((n_clouds, c), x.device), _f32((n_clouds,), x.device)
+    _check(_glue_argtypes().sp_pool_avg_fwd(coords.data_ptr(), x.data_ptr(), n, c, n_clouds, out.data_ptr(),
+                                            counts.data_ptr(), _dt(x), _stream()))
+    return out, counts
+
+
+def sp_pool_avg_bwd(coords, dout, counts, n: int, dtype):
+    _need_cuda(coords, torch.int32, "coords"), _need_cuda(dout, torch.float32, "dout")
+    n_clouds, c = dout.shape
+    dx = torch.empty((n, c), dtype=dtype, device=dout.device)
+    _check(_glue_argtypes().sp_pool_avg_bwd(coords.data_ptr(), dout.data_ptr(), counts.data_ptr(), n, c, n_clouds,
+                                            dx.data_ptr(), _dt(dx), _stream()))
+    return dx
+
+
+def sp_linear_fwd(x, w, bias):
+    _need_cuda(x, torch.float32, "x"), _need_cuda(w, torch.float32, "w")
+    nb, c = x.shape
+    m = w.shape[0]
+    out = _f32((nb, m), x.device)
+    _check(_glue_argtypes().sp_linear_fwd(x.data_ptr(), w.data_ptr(), bias.data_ptr() if bias is not None else None,
+                                          nb, c, m, out.data_ptr(), _stream()))
+    return out
+
+
+def sp_linear_bwd(x, w, dout):
+    """Returns (dx, dw, dbias)."""
+    nb, c = x.shape
+    m = w.shape[0]
+    dx, dw, db = _f32((nb, c), x.device), _f32((m, c), x.device), _f32((m,), x.device)
+    _check(_glue_argtypes().sp_linear_bwd(x.data_ptr(), w.data_ptr(), dout.data_ptr(), nb, c, m, dx.data_ptr(),
+                                          dw.data_ptr(), db.data_ptr(), _stream()))
+    return dx, dw, db
+
+
+def sp_softmax_ce(logits, labels):
+    """labels int32 [n_clouds].  Returns (loss fp32 [1], dlogits)."""
+    _need_cuda(logits, torch.float32, "logits"), _need_cuda(labels, torch.int32, "labels")
+    nb, m = logits.shape
+    loss, d = _f32((1,), logits.device), torch.empty_like(logits)
+    _check(_glue_argtypes().sp_softmax_ce(logits.data_ptr(), labels.data_ptr(), nb, m, loss.data_ptr(), d.data_ptr(),
+                                          _stream()))
+    return loss, d

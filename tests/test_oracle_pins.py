@@ -356,3 +356,48 @@ def test_generated_occupancy_is_surface_like():
     assert 0.02 < len(c) / 32 ** 3 < 0.08
     _, _, counts = oracle.kernel_map(c, c, 3, 1)
     assert 4.0 < counts.sum() / len(c) < 12.0
+
+
+# ------------------------------------------------------------------ layers between the convolutions
+def test_glue_layers_match_torch_library_routines():
+    from oracle import glue
+    rng = np.random.default_rng(77)
+    n, c, B, m = 500, 6, 3, 5
+    x = rng.standard_normal((n, c)) * 2 + 0.5
+    gamma, beta = rng.standard_normal(c), rng.standard_normal(c)
+    bidx = np.sort(rng.integers(0, B, n))
+    labels = rng.integers(0, m, B)
+    w, bias = rng.standard_normal((m, c)), rng.standard_normal(m)
+
+    xt = torch.tensor(x, requires_grad=True)
+    gt, bt = torch.tensor(gamma, requires_grad=True), torch.tensor(beta, requires_grad=True)
+    wt, bit = torch.tensor(w, requires_grad=True), torch.tensor(bias, requires_grad=True)
+    yt = torch.relu(torch.nn.functional.batch_norm(xt, None, None, gt, bt, training=True, eps=1e-5))
+    yt.retain_grad()
+    onehot = torch.nn.functional.one_hot(torch.tensor(bidx), B).double()
+    pt = (onehot.T @ yt) / onehot.sum(0)[:, None]
+    pt.retain_grad()
+    lt = torch.nn.functional.linear(pt, wt, bit)
+    lt.retain_grad()
+    loss_t = torch.nn.functional.cross_entropy(lt, torch.tensor(labels))
+    loss_t.backward()
+
+    y, mean, rstd = glue.bn_relu_fwd(x, gamma, beta, 1e-5, True)
+    pooled, counts = glue.pool_avg_fwd(bidx, y, B)
+    logits = glue.linear_fwd(pooled, w, bias)
+    loss, dlogits = glue.softmax_ce(logits, labels)
+    dpool, dw, dbias = glue.linear_bwd(pooled, w, dlogits)
+    dy = glue.pool_avg_bwd(bidx, dpool, counts)
+    dx, dgamma, dbeta = glue.bn_relu_bwd(x, y, dy, gamma, mean, rstd, True)
+    for got, want in ((y, yt), (pooled, pt), (logits, lt), (loss, loss_t), (dlogits, lt.grad), (dpool, pt.grad),
+                      (dw, wt.grad), (dbias, bit.grad), (dy, yt.grad), (dx, xt.grad), (dgamma, gt.grad),
+                      (dbeta, bt.grad)):
+        assert np.allclose(got, want.detach().numpy(), rtol=1e-10, atol=1e-12)
+    # without the activation
+    y2, mean2, rstd2 = glue.bn_relu_fwd(x, gamma, beta, 1e-3, False)
+    x2 = torch.tensor(x, requires_grad=True)
+    y2t = torch.nn.functional.batch_norm(x2, None, None, torch.tensor(gamma), torch.tensor(beta), training=True, eps=1e-3)
+    g = rng.standard_normal((n, c))
+    y2t.backward(torch.tensor(g))
+    assert np.allclose(y2, y2t.detach().numpy(), atol=1e-12)
+    assert np.allclose(glue.bn_relu_bwd(x, y2, g, gamma, mean2, rstd2, False)[0], x2.grad.numpy(), atol=1e-11)
