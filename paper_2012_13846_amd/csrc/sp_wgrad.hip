@@ -10,6 +10,7 @@
 // coalesced 16-byte loads into LDS (double buffered, one barrier per step) and reads MFMA fragments from
 // there: fp32 with one 4-byte read per lane (lane = channel, links in lane groups), bf16 with the LDS
 // transpose read, which hands a lane 4 consecutive links of one channel out of row-major storage.
+#include <algorithm>
 #include <type_traits>
 
 #include "sp_internal.h"
@@ -23,160 +24,114 @@ typedef uint16_t bf16_t;
 __device__ __forceinline__ float load_f32(const float* p) { return *p; }
 __device__ __forceinline__ float load_f32(const bf16_t* p) { return __uint_as_float((uint32_t)(*p) << 16); }
 
-// Which (offset, chunk) a work item is: items are numbered offset by offset, ceil(count/chunk) per offset.
-struct Item {
-    int k;
-    int64_t beg, end;
+// Work decomposition.  Offset k's links are sorted by row on one side, so the j-th fraction of every
+// offset's list covers about the same rows (and, on the other side, their spatial neighbours).  The lists are
+// cut into S8 = 8*M "strips": strip s is, for every offset in turn, the s-th 1/S8 of its list; the
+// concatenation of these stretches is the strip's link sequence.  Workgroup i runs on XCD i % 8: strips are
+// dealt to the XCDs round-robin and run in order, so the rows a strip touches 27 times cross the fabric once
+// and are then served by that XCD's L2.  A strip's sequence is cut into nc chunks of C links, one workgroup
+// each (times the channel tiles): equal work whatever the offsets' densities.  A chunk that spans several
+// offsets produces one partial block per offset ("piece").
+//
+// Partial blocks are numbered strip by strip in sequence order: within a strip, the piece that starts at
+// sequence position p has number ceil(p / C) + (offset stretches starting before p at a position that is
+// not a multiple of C): every chunk start and every such stretch start begins exactly one piece.
+struct PlanArgs {
+    int kvol, S8, nc, C, tiles;
+    int slots_per_strip;  // nc + kvol: more than the largest piece number of a strip
+    int32_t koff[130];    // exclusive prefix of the offsets' link counts
 };
-__device__ __forceinline__ Item locate_item(const int32_t* __restrict__ koff, int kvol, int chunk, int item) {
-    Item it;
-    int first = 0;
-    for (int k = 0; k < kvol; ++k) {
-        const int cnt = koff[k + 1] - koff[k];
-        const int ni = (cnt + chunk - 1) / chunk;
-        if (item < first + ni) {
-            it.k = k;
-            it.beg = (int64_t)koff[k] + (int64_t)(item - first) * chunk;
-            it.end = min(it.beg + chunk, (int64_t)koff[k + 1]);
-            return it;
-        }
-        first += ni;
-    }
-    it.k = -1;
-    it.beg = it.end = 0;
-    return it;
+// stretch of offset k in strip s: links [lo, lo + len), lo = koff[k] + floor(cnt * s / S8) in 32-bit steps
+__device__ __forceinline__ void strip_stretch(const PlanArgs& pa, int k, int s, int* lo, int* len) {
+    const uint32_t k0 = (uint32_t)pa.koff[k], cnt = (uint32_t)pa.koff[k + 1] - k0, n = (uint32_t)pa.S8;
+    const uint32_t q = cnt / n, r = cnt % n;  // r * s < 2^20
+    const uint32_t b0 = q * (uint32_t)s + r * (uint32_t)s / n, b1 = q * (uint32_t)(s + 1) + r * (uint32_t)(s + 1) / n;
+    *lo = (int)(k0 + b0);
+    *len = (int)(b1 - b0);
 }
 
-// grid (items, cout/COB, cin/CIB); 4 wavefronts each take every 4th group of 4 links of the chunk.
-// MFMA 16x16x4: A[m = channel of dY][kk = link], B[kk = link][n = channel of X].
-template <typename T, int COB, int CIB>
-__global__ __launch_bounds__(256) void wgrad_partial_kernel(const int32_t* __restrict__ pair_in,
-                                                            const int32_t* __restrict__ pair_out,
-                                                            const int32_t* __restrict__ koff, int kvol, int chunk,
-                                                            const T* __restrict__ X, const T* __restrict__ dY, int cin,
-                                                            int cout, float* __restrict__ part) {
-    constexpr int NCO = COB / 16, NCI = CIB / 16;
-    __shared__ float red[COB * CIB];
-    const Item it = locate_item(koff, kvol, chunk, blockIdx.x);
-    if (it.k < 0) return;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int n16 = lane & 15, g = lane >> 4;
-    const int co0 = blockIdx.y * COB, ci0 = blockIdx.z * CIB;
-
-    f32x4 acc[NCO][NCI];
+// Plan tables, one wavefront per strip (lane = offset):
+//   lo/len [S8][kvol]     offset k's stretch in strip s
+//   first/count [S8][kvol] number of its first partial block, how many it has
+//   cstart [S8][nc][3]    for chunk c: the offset whose stretch holds the chunk's first position, that
+//                         stretch's start position, and the number of stretches before it that start off a
+//                         chunk boundary; offset = kvol for chunks past the strip's end
+__global__ __launch_bounds__(64) void wgrad_plan_kernel(PlanArgs pa, int32_t* __restrict__ lo_tab, int32_t* __restrict__ len_tab,
+                                                        int32_t* __restrict__ first, int32_t* __restrict__ count,
+                                                        int32_t* __restrict__ cstart) {
+    const int s = blockIdx.x, lane = threadIdx.x;
+    int pos_base = 0, nb_base = 0;
+    for (int kb = 0; kb < pa.kvol; kb += 64) {
+        const int k = kb + lane;
+        int lo = 0, len = 0;
+        if (k < pa.kvol) strip_stretch(pa, k, s, &lo, &len);
+        int inc = len;
 #pragma unroll
-    for (int a = 0; a < NCO; ++a)
-#pragma unroll
-        for (int b = 0; b < NCI; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    // Software pipeline in super-steps of kU steps (kU * 4 links per wavefront): the rows of super-step s+1
-    // and the link indices of super-step s+2 are requested before the MFMAs of super-step s are issued.
-    constexpr int kU = 4;
-    const int64_t first_p = it.beg + wave * 4 + g;  // this lane's link in step 0; step j is 16*j further
-    auto load_idx = [&](int64_t p, int32_t (&o)[kU], int32_t (&i)[kU]) {
-#pragma unroll
-        for (int u = 0; u < kU; ++u) {
-            const bool live = p + 16 * u < it.end;
-            o[u] = live ? pair_out[p + 16 * u] : -1;
-            i[u] = live ? pair_in[p + 16 * u] : 0;
+        for (int d = 1; d < 64; d <<= 1) {
+            const int t = __shfl_up(inc, d, 64);
+            if (lane >= d) inc += t;
         }
-    };
-    auto load_rows = [&](const int32_t (&o)[kU], const int32_t (&i)[kU], float (&av)[kU][NCO], float (&bv)[kU][NCI]) {
-#pragma unroll
-        for (int u = 0; u < kU; ++u) {
-            const bool live = o[u] >= 0;
-            const T* dyp = dY + (size_t)(live ? o[u] : 0) * cout + co0 + n16;
-            const T* xp = X + (size_t)(live ? i[u] : 0) * cin + ci0 + n16;
-#pragma unroll
-            for (int a = 0; a < NCO; ++a) av[u][a] = live ? load_f32(dyp + a * 16) : 0.f;
-#pragma unroll
-            for (int b = 0; b < NCI; ++b) bv[u][b] = live ? load_f32(xp + b * 16) : 0.f;
+        const int pos = pos_base + inc - len;
+        const bool real = len > 0 && pos % pa.C != 0;
+        const unsigned long long mask = __ballot(real);
+        const int nb = nb_base + __popcll(mask & ((1ull << lane) - 1ull));
+        if (k < pa.kvol) {
+            lo_tab[s * pa.kvol + k] = lo;
+            len_tab[s * pa.kvol + k] = len;
+            first[s * pa.kvol + k] = len > 0 ? s * pa.slots_per_strip + (pos + pa.C - 1) / pa.C + nb : 0;
+            count[s * pa.kvol + k] = len > 0 ? (pos + len + pa.C - 1) / pa.C - pos / pa.C : 0;
+            for (int c = (pos + pa.C - 1) / pa.C; c < pa.nc && (int64_t)c * pa.C < pos + len; ++c) {
+                int32_t* cs = cstart + ((size_t)s * pa.nc + c) * 3;
+                cs[0] = k;
+                cs[1] = pos;
+                cs[2] = nb;
+            }
         }
-    };
-    int32_t o2[kU], i2[kU];
-    float av[kU][NCO], bv[kU][NCI];
-    {
-        int32_t o1[kU], i1[kU];
-        load_idx(first_p, o1, i1);
-        load_idx(first_p + 16 * kU, o2, i2);
-        load_rows(o1, i1, av, bv);
+        pos_base += __shfl(inc, 63, 64);
+        nb_base += __popcll(mask);
     }
-    for (int64_t p = first_p; p - g < it.end; p += 16 * kU) {
-        float an[kU][NCO], bn[kU][NCI];
-        int32_t o3[kU], i3[kU];
-        load_idx(p + 32 * kU, o3, i3);
-        load_rows(o2, i2, an, bn);
-#pragma unroll
-        for (int u = 0; u < kU; ++u)
-#pragma unroll
-            for (int a = 0; a < NCO; ++a)
-#pragma unroll
-                for (int b = 0; b < NCI; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][a], bv[u][b], acc[a][b], 0, 0, 0);
-#pragma unroll
-        for (int u = 0; u < kU; ++u) {
-#pragma unroll
-            for (int a = 0; a < NCO; ++a) av[u][a] = an[u][a];
-#pragma unroll
-            for (int b = 0; b < NCI; ++b) bv[u][b] = bn[u][b];
-            o2[u] = o3[u];
-            i2[u] = i3[u];
-        }
-    }
-    // acc[a][b][j] is element (co = a*16 + 4*g + j, ci = b*16 + n16); add the 4 wavefronts in order
-    for (int w = 0; w < 4; ++w) {
-        if (wave == w) {
-#pragma unroll
-            for (int a = 0; a < NCO; ++a)
-#pragma unroll
-                for (int b = 0; b < NCI; ++b)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int e = (a * 16 + g * 4 + j) * CIB + b * 16 + n16;
-                        red[e] = (w == 0 ? 0.f : red[e]) + acc[a][b][j];
-                    }
-        }
-        __syncthreads();
-    }
-    float* dst = part + (size_t)blockIdx.x * cout * cin;
-    for (int e = tid; e < COB * CIB; e += 256) {
-        const int co = e / CIB, ci = e % CIB;
-        dst[(size_t)(co0 + co) * cin + ci0 + ci] = red[e];
-    }
+    for (int c = (pos_base + pa.C - 1) / pa.C + lane; c < pa.nc; c += 64) cstart[((size_t)s * pa.nc + c) * 3] = pa.kvol;
 }
 
-// dW[k][e] = sum of the partials of offset k's items, in a fixed order: 4 interleaved running sums per
-// element (one per wavefront of the block), each over every 4th item, then added 0+1+2+3.
-// grid (per/64, kvol), block 256 = 64 elements x 4 item groups.
+// dW[k][e] = sum of offset k's partial blocks, strip by strip, in a fixed order: 16 interleaved running sums
+// per element, each over every 16th block, then added in order 0..15.  grid (per/64, kvol); block = 16 lanes
+// x 4 elements each x 16 block slices.
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ part,
-                                                           const int32_t* __restrict__ koff, int kvol, int chunk,
-                                                           int per, float* __restrict__ dw) {
-    __shared__ float red[4][64];
+                                                           const int32_t* __restrict__ first,
+                                                           const int32_t* __restrict__ count, int S8, int kvol, int per,
+                                                           float* __restrict__ dw) {
+    constexpr int kMaxStrips = 1024;
+    __shared__ int s_first[kMaxStrips], s_count[kMaxStrips];
+    __shared__ f32x4 red[16][16];
     const int k = blockIdx.y;
-    const int el = threadIdx.x & 63, grp = threadIdx.x >> 6;
-    const int e = blockIdx.x * 64 + el;
-    int first = 0;
-    for (int j = 0; j < k; ++j) first += (koff[j + 1] - koff[j] + chunk - 1) / chunk;
-    const int ni = (koff[k + 1] - koff[k] + chunk - 1) / chunk;
-    float s0 = 0.f, s1 = 0.f;
-    if (e < per) {
-        const float* p = part + (size_t)first * per + e;
-        int it = grp;
-        for (; it + 4 < ni; it += 8) {  // two independent loads in flight
-            s0 += p[(size_t)it * per];
-            s1 += p[(size_t)(it + 4) * per];
-        }
-        if (it < ni) s0 += p[(size_t)it * per];
+    const int el = threadIdx.x & 15, grp = threadIdx.x >> 4;
+    const int e = (blockIdx.x * 16 + el) * 4;
+    for (int s = threadIdx.x; s < S8; s += 256) {
+        s_first[s] = first[s * kvol + k];
+        s_count[s] = count[s * kvol + k];
     }
-    red[grp][el] = s0 + s1;
     __syncthreads();
-    if (grp == 0 && e < per) dw[(size_t)k * per + e] = ((red[0][el] + red[1][el]) + red[2][el]) + red[3][el];
+    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+    int n = 0;
+    for (int s = 0; s < S8; ++s) {
+        const int f = s_first[s], c = s_count[s];
+        for (int j = (grp - n) & 15; j < c; j += 16)
+            sum += *reinterpret_cast<const f32x4*>(part + (size_t)(f + j) * per + e);
+        n += c;
+    }
+    red[grp][el] = sum;
+    __syncthreads();
+    if (grp == 0) {
+        f32x4 t = red[0][el];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) t += red[i][el];
+        *reinterpret_cast<f32x4*>(dw + (size_t)k * per + e) = t;
+    }
 }
-
 
 // ---------------------------------------------------------------------------------------------------------
 // Staged kernel.  Tile COB x CIB of dW per workgroup; WCO x WCI x WK wavefronts: the tile is cut WCO x WCI
-// ways and each step's 32*WK links WK ways.  grid (items, cout/COB, cin/CIB).
+// ways and each step's 32*WK links WK ways.  One workgroup per (chunk, channel tile).
 // ---------------------------------------------------------------------------------------------------------
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -186,47 +141,60 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 template <typename T, int COB, int CIB, int WCO, int WCI, int WK>
 struct StagedCfg {
     static constexpr int kElt = sizeof(T);
+    static constexpr bool kIsF32 = sizeof(T) == 4;
     static constexpr int kWaves = WCO * WCI * WK, kThreads = 64 * kWaves;
     static constexpr int kS = 32 * WK;                     // links per step
-    static constexpr int kPad = 16 * kElt;                 // row pad: fragment reads of 4 rows hit disjoint banks
-    static constexpr int kPA = COB * kElt + kPad, kPB = CIB * kElt + kPad;  // staged row pitch of dY / X rows
-    static constexpr int kPiecesA = COB * kElt / 16, kPiecesB = CIB * kElt / 16;  // 16-byte pieces per row
-    static constexpr int kLoadsA = (kS * kPiecesA + kThreads - 1) / kThreads;
-    static constexpr int kLoadsB = (kS * kPiecesB + kThreads - 1) / kThreads;
-    static constexpr int kBufBytes = kS * (kPA + kPB);
+    static constexpr int kTPR = kThreads / kS;             // threads that share the loading of one row
     static constexpr int kTA = COB / WCO / 16, kTB = CIB / WCI / 16;  // 16x16 tiles per wavefront
+    // Row pad so that a fragment read (4 link rows x 16 lanes) hits disjoint banks: bf16 transpose reads take
+    // 32 bytes per row, fp32 reads 64 * kT bytes per row (a lane reads its kT channels at once).
+    static constexpr int pad_f32(int kt) { return kt >= 4 ? 0 : 64 * kt; }
+    static constexpr int kPA = COB * kElt + (kIsF32 ? pad_f32(kTA) : 32);  // staged row pitch of dY rows
+    static constexpr int kPB = CIB * kElt + (kIsF32 ? pad_f32(kTB) : 32);  // and of X rows
+    static constexpr int kPiecesA = COB * kElt / 16, kPiecesB = CIB * kElt / 16;  // 16-byte pieces per row
+    static constexpr int kLoadsA = (kPiecesA + kTPR - 1) / kTPR;  // per thread and step
+    static constexpr int kLoadsB = (kPiecesB + kTPR - 1) / kTPR;
+    static constexpr int kBufBytes = kS * (kPA + kPB);
     static constexpr int kRedBytes = WK > 1 ? COB * CIB * 4 : 0;
     static constexpr int kLds = 2 * kBufBytes > kRedBytes ? 2 * kBufBytes : kRedBytes;
     static_assert(COB % (16 * WCO) == 0 && CIB % (16 * WCI) == 0, "tile split");
+    static_assert(kThreads % kS == 0, "whole threads per row");
+    static_assert(!kIsF32 || (kTA <= 4 && kTB <= 4), "an fp32 lane reads its channels with one LDS load");
 };
 
 struct StagedArgs {
     const int32_t* pair_in;
     const int32_t* pair_out;
-    const int32_t* koff;
     const void* x;
     const void* dy;
     float* part;
-    int kvol, chunk, cin, cout;
+    int cin, cout;
     uint32_t x_bytes, dy_bytes, pair_bytes;  // buffer sizes (< 2 GiB each)
+    PlanArgs plan;
+    const int32_t* lo_tab;   // plan tables, see wgrad_plan_kernel
+    const int32_t* len_tab;
+    const int32_t* cstart;
 };
 
-template <typename T, int COB, int CIB, int WCO, int WCI, int WK>
+template <typename T, int COB, int CIB, int WCO, int WCI, int WK, int kD>
 __global__ __launch_bounds__(64 * WCO * WCI * WK) void wgrad_staged_kernel(StagedArgs a) {
     using Cfg = StagedCfg<T, COB, CIB, WCO, WCI, WK>;
-    constexpr bool kIsF32 = std::is_same<T, float>::value;
-    constexpr int kTA = Cfg::kTA, kTB = Cfg::kTB, kPA = Cfg::kPA, kPB = Cfg::kPB, kS = Cfg::kS;
+    constexpr bool kIsF32 = Cfg::kIsF32;
+    constexpr int kTA = Cfg::kTA, kTB = Cfg::kTB, kPA = Cfg::kPA, kPB = Cfg::kPB, kS = Cfg::kS, kTPR = Cfg::kTPR;
     constexpr int kLoadsA = Cfg::kLoadsA, kLoadsB = Cfg::kLoadsB, kThreads = Cfg::kThreads;
     extern __shared__ __align__(16) unsigned char smem[];
 
-    const Item it = locate_item(a.koff, a.kvol, a.chunk, blockIdx.x);
-    if (it.k < 0) return;
+    // workgroup -> (strip, chunk, channel tile): XCD = id % 8 takes strips XCD, XCD + 8, ... in that order
+    const PlanArgs& pa = a.plan;
+    const int tile = blockIdx.x % pa.tiles, q0 = blockIdx.x / pa.tiles;
+    const int q = q0 >> 3, strip = (q0 & 7) + 8 * (q / pa.nc), chunk = q % pa.nc;
+    const int cb = chunk * pa.C, ce = cb + pa.C;  // this chunk's positions in the strip's link sequence
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wk = wave % WK, wci = (wave / WK) % WCI, wco = wave / (WK * WCI);
     const int n16 = lane & 15, g = lane >> 4;
-    const int co0 = blockIdx.y * COB, ci0 = blockIdx.z * CIB;
+    const int co0 = (tile / (a.cin / CIB)) * COB, ci0 = (tile % (a.cin / CIB)) * CIB;
 
-    // Buffer addressing: a lane whose link lies past the chunk's end asks for an offset outside the buffer
+    // Buffer addressing: a lane whose link lies past the piece's end asks for an offset outside the buffer
     // and gets zeros, so the loop body has no branch around a load.
     constexpr int kRsrcFlags = 0x00020000;
     constexpr uint32_t kOutside = 0x80000000u;
@@ -237,81 +205,108 @@ __global__ __launch_bounds__(64 * WCO * WCI * WK) void wgrad_staged_kernel(Stage
     const __amdgpu_buffer_rsrc_t rPO =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t*>(a.pair_out), 0, (int)a.pair_bytes, kRsrcFlags);
     const uint32_t rowbytes_a = (uint32_t)a.cout * Cfg::kElt, rowbytes_b = (uint32_t)a.cin * Cfg::kElt;
-    const uint32_t col_a = (uint32_t)co0 * Cfg::kElt, col_b = (uint32_t)ci0 * Cfg::kElt;
 
-    // this thread's pieces of a step: piece q = tid + j * kThreads of the dY rows, likewise of the X rows
+    // Loading: thread = (row of the step, sub); it loads the 16-byte pieces sub, sub + kTPR, ... of that row of
+    // dY and of X: one row number and one address per operand, the pieces differ by constant offsets; four
+    // adjacent lanes read 64 consecutive bytes.
+    const int ld_row = tid / kTPR, ld_sub = tid % kTPR;
+    const uint32_t col_a = (uint32_t)co0 * Cfg::kElt + ld_sub * 16, col_b = (uint32_t)ci0 * Cfg::kElt + ld_sub * 16;
+    const int st_a = ld_row * kPA + ld_sub * 16, st_b = kS * kPA + ld_row * kPB + ld_sub * 16;  // LDS offsets
+    uint32_t beg4 = 0;  // byte offset of the piece's first link in the pair lists
+    int len = 0;        // links of the piece
+
     struct Regs {
-        int ia[kLoadsA], ib[kLoadsB];      // gathered row numbers
+        int ia, ib;                        // gathered row numbers
         u32x4 va[kLoadsA], vb[kLoadsB];    // gathered pieces
     };
-    auto load_idx = [&](Regs& r, int64_t base) __attribute__((always_inline)) {
+    struct RowAddr {
+        uint32_t a, b;
+    };
+    // rel: position of the step's first link in the piece
+    auto load_idx = [&](Regs& r, int rel) __attribute__((always_inline)) {
+        const uint32_t off = rel + ld_row < len ? beg4 + (uint32_t)(rel + ld_row) * 4u : kOutside;
+        r.ia = (int)__builtin_amdgcn_raw_buffer_load_b32(rPO, off, 0, 0);
+        r.ib = (int)__builtin_amdgcn_raw_buffer_load_b32(rPI, off, 0, 0);
+    };
+    // Row loads in two halves, so that the next row numbers can be requested between them: a wavefront's
+    // loads complete in order, and the wait for row numbers at the top of the next step must not also wait
+    // for this step's rows.
+    auto row_addrs = [&](const Regs& r, int rel, RowAddr& ra) __attribute__((always_inline)) {
+        const bool live = rel + ld_row < len;
+        ra.a = live ? (uint32_t)r.ia * rowbytes_a + col_a : kOutside;
+        ra.b = live ? (uint32_t)r.ib * rowbytes_b + col_b : kOutside;
+    };
+    auto issue_rows = [&](Regs& r, const RowAddr& ra) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < kLoadsA; ++j) {
-            const int64_t link = base + (tid + j * kThreads) / Cfg::kPiecesA;
-            r.ia[j] = (int)__builtin_amdgcn_raw_buffer_load_b32(rPO, link < it.end ? (uint32_t)link * 4u : kOutside, 0, 0);
+            const bool mine = Cfg::kPiecesA % kTPR == 0 || ld_sub + j * kTPR < Cfg::kPiecesA;
+            r.va[j] = __builtin_amdgcn_raw_buffer_load_b128(rDY, mine ? ra.a + j * kTPR * 16 : kOutside, 0, 0);
         }
 #pragma unroll
         for (int j = 0; j < kLoadsB; ++j) {
-            const int64_t link = base + (tid + j * kThreads) / Cfg::kPiecesB;
-            r.ib[j] = (int)__builtin_amdgcn_raw_buffer_load_b32(rPI, link < it.end ? (uint32_t)link * 4u : kOutside, 0, 0);
+            const bool mine = Cfg::kPiecesB % kTPR == 0 || ld_sub + j * kTPR < Cfg::kPiecesB;
+            r.vb[j] = __builtin_amdgcn_raw_buffer_load_b128(rX, mine ? ra.b + j * kTPR * 16 : kOutside, 0, 0);
         }
     };
-    auto load_rows = [&](Regs& r, int64_t base) __attribute__((always_inline)) {
-#pragma unroll
-        for (int j = 0; j < kLoadsA; ++j) {
-            const int q = tid + j * kThreads;
-            const int64_t link = base + q / Cfg::kPiecesA;
-            const uint32_t off = (uint32_t)r.ia[j] * rowbytes_a + col_a + (q % Cfg::kPiecesA) * 16;
-            r.va[j] = __builtin_amdgcn_raw_buffer_load_b128(rDY, link < it.end ? off : kOutside, 0, 0);
-        }
-#pragma unroll
-        for (int j = 0; j < kLoadsB; ++j) {
-            const int q = tid + j * kThreads;
-            const int64_t link = base + q / Cfg::kPiecesB;
-            const uint32_t off = (uint32_t)r.ib[j] * rowbytes_b + col_b + (q % Cfg::kPiecesB) * 16;
-            r.vb[j] = __builtin_amdgcn_raw_buffer_load_b128(rX, link < it.end ? off : kOutside, 0, 0);
-        }
+    auto load_rows = [&](Regs& r, int rel) __attribute__((always_inline)) {
+        RowAddr ra;
+        row_addrs(r, rel, ra);
+        issue_rows(r, ra);
     };
     auto store_rows = [&](const Regs& r, unsigned char* buf) __attribute__((always_inline)) {
 #pragma unroll
-        for (int j = 0; j < kLoadsA; ++j) {
-            const int q = tid + j * kThreads;
-            if (kS * Cfg::kPiecesA % kThreads == 0 || q < kS * Cfg::kPiecesA)
-                *reinterpret_cast<u32x4*>(buf + (q / Cfg::kPiecesA) * kPA + (q % Cfg::kPiecesA) * 16) = r.va[j];
-        }
+        for (int j = 0; j < kLoadsA; ++j)
+            if (Cfg::kPiecesA % kTPR == 0 || ld_sub + j * kTPR < Cfg::kPiecesA)
+                *reinterpret_cast<u32x4*>(buf + st_a + j * kTPR * 16) = r.va[j];
 #pragma unroll
-        for (int j = 0; j < kLoadsB; ++j) {
-            const int q = tid + j * kThreads;
-            if (kS * Cfg::kPiecesB % kThreads == 0 || q < kS * Cfg::kPiecesB)
-                *reinterpret_cast<u32x4*>(buf + kS * kPA + (q / Cfg::kPiecesB) * kPB + (q % Cfg::kPiecesB) * 16) = r.vb[j];
-        }
+        for (int j = 0; j < kLoadsB; ++j)
+            if (Cfg::kPiecesB % kTPR == 0 || ld_sub + j * kTPR < Cfg::kPiecesB)
+                *reinterpret_cast<u32x4*>(buf + st_b + j * kTPR * 16) = r.vb[j];
     };
 
     f32x4 acc[kTA][kTB];
-#pragma unroll
-    for (int ta = 0; ta < kTA; ++ta)
-#pragma unroll
-        for (int tb = 0; tb < kTB; ++tb) acc[ta][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    f32x4 tot[kIsF32 ? kTA : 1][kIsF32 ? kTB : 1];  // fp32: acc is added into tot every kFlushEvery * kD steps
+    constexpr int kFlushEvery = 8 / kD > 0 ? 8 / kD : 1;
 
-    // this wavefront's 32 links of the step, its channel slices
-    const int a_col = (wco * kTA * 16) * Cfg::kElt, b_col = (wci * kTB * 16) * Cfg::kElt;
+    // This wavefront's 32 links of the step and its channel slices.  Channel of (16x16 tile t, index m in the
+    // tile) within the slice: bf16 t*16 + m; fp32 m*kT + t, so that a lane's kT values are adjacent in LDS.
+    const int frag_a = (32 * wk) * kPA + (wco * kTA * 16) * Cfg::kElt;
+    const int frag_b = kS * kPA + (32 * wk) * kPB + (wci * kTB * 16) * Cfg::kElt;
+    const int lane_a = kIsF32 ? g * kPA + n16 * kTA * 4 : (8 * g + (n16 >> 2)) * kPA + (n16 & 3) * 8;
+    const int lane_b = kIsF32 ? g * kPB + n16 * kTB * 4 : (8 * g + (n16 >> 2)) * kPB + (n16 & 3) * 8;
     auto compute = [&](const unsigned char* buf) __attribute__((always_inline)) {
-        const unsigned char* A = buf + (32 * wk) * kPA + a_col;
-        const unsigned char* B = buf + kS * kPA + (32 * wk) * kPB + b_col;
+        const unsigned char* A = buf + frag_a + lane_a;
+        const unsigned char* B = buf + frag_b + lane_b;
         if constexpr (kIsF32) {
-            // MFMA 16x16x4: lane (channel n16, link g) of both operands
+            // MFMA 16x16x4: lane (index n16 in the tile, link g) of both operands; the fragments of the next 4
+            // links are read while the current ones are multiplied
+            typedef float fvA __attribute__((ext_vector_type(kTA == 3 ? 4 : kTA)));
+            typedef float fvB __attribute__((ext_vector_type(kTB == 3 ? 4 : kTB)));
+            float av[2][kTA], bv[2][kTB];
+            auto read = [&](int j, float (&x)[kTA], float (&y)[kTB]) __attribute__((always_inline)) {
+                if constexpr (kTA == 1) x[0] = *reinterpret_cast<const float*>(A + 4 * j * kPA);
+                else {
+                    const fvA v = *reinterpret_cast<const fvA*>(A + 4 * j * kPA);
+#pragma unroll
+                    for (int ta = 0; ta < kTA; ++ta) x[ta] = v[ta];
+                }
+                if constexpr (kTB == 1) y[0] = *reinterpret_cast<const float*>(B + 4 * j * kPB);
+                else {
+                    const fvB v = *reinterpret_cast<const fvB*>(B + 4 * j * kPB);
+#pragma unroll
+                    for (int tb = 0; tb < kTB; ++tb) y[tb] = v[tb];
+                }
+            };
+            read(0, av[0], bv[0]);
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                float av[kTA], bv[kTB];
-#pragma unroll
-                for (int ta = 0; ta < kTA; ++ta) av[ta] = *reinterpret_cast<const float*>(A + (4 * j + g) * kPA + (ta * 16 + n16) * 4);
-#pragma unroll
-                for (int tb = 0; tb < kTB; ++tb) bv[tb] = *reinterpret_cast<const float*>(B + (4 * j + g) * kPB + (tb * 16 + n16) * 4);
+                if (j < 7) read(j + 1, av[(j + 1) & 1], bv[(j + 1) & 1]);
+                __builtin_amdgcn_sched_barrier(0);  // keeps the reads ahead of the products that hide them
 #pragma unroll
                 for (int ta = 0; ta < kTA; ++ta)
 #pragma unroll
                     for (int tb = 0; tb < kTB; ++tb)
-                        acc[ta][tb] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[ta], bv[tb], acc[ta][tb], 0, 0, 0);
+                        acc[ta][tb] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[j & 1][ta], bv[j & 1][tb], acc[ta][tb], 0, 0, 0);
             }
         } else {
             // MFMA 16x16x32: lane (channel n16, links 8g .. 8g+7).  One transpose read: the 16 lanes of group g
@@ -319,9 +314,8 @@ __global__ __launch_bounds__(64 * WCO * WCI * WK) void wgrad_staged_kernel(Stage
             // channel i of those 4 rows.
             typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
             auto frag = [&](const unsigned char* base, int pitch) __attribute__((always_inline)) {
-                const unsigned char* p = base + (8 * g + (n16 >> 2)) * pitch + (n16 & 3) * 8;
-                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
-                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * pitch));
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(base));
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(base + 4 * pitch));
                 const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
                 return __builtin_bit_cast(bf16x8, v);
             };
@@ -338,54 +332,121 @@ __global__ __launch_bounds__(64 * WCO * WCI * WK) void wgrad_staged_kernel(Stage
         }
     };
 
-    // step s: rows of step s+1 and row numbers of step s+2 are requested before step s is computed
-    Regs r = {};
-    load_idx(r, it.beg);
-    load_rows(r, it.beg);
-    load_idx(r, it.beg + kS);
-    store_rows(r, smem);
-    __syncthreads();
-    int cur = 0;
-    for (int64_t base = it.beg; base < it.end; base += kS) {
-        load_rows(r, base + kS);
-        load_idx(r, base + 2 * kS);
-        compute(smem + cur * Cfg::kBufBytes);
-        store_rows(r, smem + (cur ^ 1) * Cfg::kBufBytes);
-        __syncthreads();
-        cur ^= 1;
-    }
+    // Ring of kD register sets: in step s the rows of step s+kD are requested with the row numbers that were
+    // requested in step s-kD, and the row numbers of step s+2*kD are requested.  The step count is rounded up
+    // to a multiple of kD (steps past the piece's end load zeros) to keep the loop body branch-free.
+    Regs r[kD];
+    // the chunk's pieces: walk the strip's stretches, offset by offset
+    const int32_t* cs = a.cstart + ((size_t)strip * pa.nc + chunk) * 3;
+    int pos = cs[1], nb = cs[2];
+    for (int k = cs[0]; k < pa.kvol && pos < ce; ++k) {
+        const int lo = a.lo_tab[strip * pa.kvol + k];
+        const int slen = a.len_tab[strip * pa.kvol + k];
+        if (slen == 0) continue;
+        const int s0 = pos, p0 = max(s0, cb), p1 = min(s0 + slen, ce);
+        const bool real = s0 % pa.C != 0;
+        pos += slen;
+        const int nb_here = nb + ((real && s0 < p0) ? 1 : 0);
+        nb += real ? 1 : 0;
+        if (p0 >= p1) continue;
+        beg4 = (uint32_t)(lo + (p0 - s0)) * 4u;
+        len = p1 - p0;
+        const int slot = strip * pa.slots_per_strip + (p0 == cb ? chunk : chunk + 1) + nb_here;
 
-    // acc[ta][tb][j] is element (co = .. + 4*g + j, ci = .. + n16).  The WK link slices are added in order.
-    float* dst = a.part + (size_t)blockIdx.x * a.cout * a.cin;
-    if constexpr (WK > 1) {
-        float* red = reinterpret_cast<float*>(smem);
-        for (int w = 0; w < WK; ++w) {
-            if (wk == w) {
-#pragma unroll
-                for (int ta = 0; ta < kTA; ++ta)
-#pragma unroll
-                    for (int tb = 0; tb < kTB; ++tb)
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const int e = ((wco * kTA + ta) * 16 + g * 4 + j) * CIB + (wci * kTB + tb) * 16 + n16;
-                            red[e] = (w == 0 ? 0.f : red[e]) + acc[ta][tb][j];
-                        }
-            }
-            __syncthreads();
-        }
-        for (int e = tid * 4; e < COB * CIB; e += kThreads * 4) {
-            const int co = e / CIB, ci = e % CIB;
-            *reinterpret_cast<f32x4*>(dst + (size_t)(co0 + co) * a.cin + ci0 + ci) = *reinterpret_cast<const f32x4*>(red + e);
-        }
-    } else {
 #pragma unroll
         for (int ta = 0; ta < kTA; ++ta)
 #pragma unroll
-            for (int tb = 0; tb < kTB; ++tb)
+            for (int tb = 0; tb < kTB; ++tb) {
+                acc[ta][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+                if constexpr (kIsF32) tot[ta][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    dst[(size_t)(co0 + (wco * kTA + ta) * 16 + g * 4 + j) * a.cin + ci0 + (wci * kTB + tb) * 16 + n16] =
-                        acc[ta][tb][j];
+        for (int d = 0; d < kD; ++d) {
+            r[d] = Regs{};
+            load_idx(r[d], d * kS);
+        }
+#pragma unroll
+        for (int d = 0; d < kD; ++d) {
+            load_rows(r[d], d * kS);
+            load_idx(r[d], (kD + d) * kS);
+        }
+        store_rows(r[0], smem);
+        __syncthreads();
+        int step = 0;
+        for (int base = 0; base < len; base += kD * kS, step += kD) {
+#pragma unroll
+            for (int d = 0; d < kD; ++d) {
+                const int b = base + d * kS;
+                const int par = (step + d) & 1;  // step s computes from buffer s & 1 and fills the other
+                const unsigned char* cur = smem + par * Cfg::kBufBytes;
+                unsigned char* nxt = smem + (par ^ 1) * Cfg::kBufBytes;
+                RowAddr ra;
+                row_addrs(r[d], b + kD * kS, ra);
+                __builtin_amdgcn_sched_barrier(0);
+                load_idx(r[d], b + 2 * kD * kS);
+                __builtin_amdgcn_sched_barrier(0);
+                issue_rows(r[d], ra);
+                __builtin_amdgcn_sched_barrier(0);  // the requests go out before the step's arithmetic, not after it
+                compute(cur);
+                __builtin_amdgcn_sched_barrier(0);
+                store_rows(r[(d + 1) % kD], nxt);
+                __syncthreads();
+            }
+            if constexpr (kIsF32) {
+                // two-level sum: a long fp32 chain would lose more than the accuracy target
+                if ((step / kD) % kFlushEvery == kFlushEvery - 1) {
+#pragma unroll
+                    for (int ta = 0; ta < kTA; ++ta)
+#pragma unroll
+                        for (int tb = 0; tb < kTB; ++tb) {
+                            tot[ta][tb] += acc[ta][tb];
+                            acc[ta][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+                        }
+                }
+            }
+        }
+        if constexpr (kIsF32) {
+#pragma unroll
+            for (int ta = 0; ta < kTA; ++ta)
+#pragma unroll
+                for (int tb = 0; tb < kTB; ++tb) acc[ta][tb] += tot[ta][tb];
+        }
+
+        // acc[ta][tb][j] is element (co: tile ta, index 4*g + j; ci: tile tb, index n16) of the wavefront's
+        // slice.  The WK link slices are added in order.
+        auto chan = [&](int t, int m, int kt) { return kIsF32 ? m * kt + t : t * 16 + m; };
+        float* dst = a.part + (size_t)slot * a.cout * a.cin;
+        if constexpr (WK > 1) {
+            float* red = reinterpret_cast<float*>(smem);
+            for (int w = 0; w < WK; ++w) {
+                if (wk == w) {
+#pragma unroll
+                    for (int ta = 0; ta < kTA; ++ta)
+#pragma unroll
+                        for (int tb = 0; tb < kTB; ++tb)
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                const int e = (wco * kTA * 16 + chan(ta, g * 4 + j, kTA)) * CIB + wci * kTB * 16 + chan(tb, n16, kTB);
+                                red[e] = (w == 0 ? 0.f : red[e]) + acc[ta][tb][j];
+                            }
+                }
+                __syncthreads();
+            }
+            for (int e = tid * 4; e < COB * CIB; e += kThreads * 4) {
+                const int co = e / CIB, ci = e % CIB;
+                *reinterpret_cast<f32x4*>(dst + (size_t)(co0 + co) * a.cin + ci0 + ci) = *reinterpret_cast<const f32x4*>(red + e);
+            }
+        } else {
+#pragma unroll
+            for (int ta = 0; ta < kTA; ++ta)
+#pragma unroll
+                for (int tb = 0; tb < kTB; ++tb)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        dst[(size_t)(co0 + wco * kTA * 16 + chan(ta, g * 4 + j, kTA)) * a.cin + ci0 + wci * kTB * 16 +
+                            chan(tb, n16, kTB)] = acc[ta][tb][j];
+        }
+        __syncthreads();  // the next piece reuses the staging buffers
     }
 }
 
@@ -406,55 +467,70 @@ __global__ __launch_bounds__(256) void wgrad_plain_kernel(const int32_t* __restr
     dw[(size_t)k * cin * cout + e] = s;
 }
 
-template <typename T, int COB, int CIB>
-void launch_partial(const sp_kmap* m, int items, int chunk, const void* x, const void* dy, int cin, int cout,
-                    float* part, hipStream_t s) {
-    hipLaunchKernelGGL((wgrad_partial_kernel<T, COB, CIB>), dim3(items, cout / COB, cin / CIB), dim3(256), 0, s,
-                       ptr<int32_t>(m->pair_in), ptr<int32_t>(m->pair_out), ptr<int32_t>(m->d_koff), m->kvol, chunk,
-                       static_cast<const T*>(x), static_cast<const T*>(dy), cin, cout, part);
-}
-
-template <typename T, int COB, int CIB, int WCO, int WCI, int WK>
+template <typename T, int COB, int CIB, int WCO, int WCI, int WK, int kD>
 int launch_staged(const sp_kmap* m, const void* x, const void* dy, int cin, int cout, float* dw, hipStream_t s) {
     using Cfg = StagedCfg<T, COB, CIB, WCO, WCI, WK>;
-    auto kern = wgrad_staged_kernel<T, COB, CIB, WCO, WCI, WK>;
+    auto kern = wgrad_staged_kernel<T, COB, CIB, WCO, WCI, WK, kD>;
     static bool attr_set = false;  // one-time opt-in to > 64 KB of dynamic LDS
     if (!attr_set) {
         SP_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                    (int)Cfg::kLds));
         attr_set = true;
     }
-    // chunk: about 2048 workgroups over the whole launch, at least 4 steps each, a whole number of steps
-    const int64_t tiles = (int64_t)(cout / COB) * (cin / CIB);
-    int64_t want = 2048 / tiles;
-    want = want < m->kvol ? m->kvol : want;
-    int64_t chunk = (m->total + want - 1) / want;
-    chunk = chunk < 4 * Cfg::kS ? 4 * Cfg::kS : (chunk > 16384 ? 16384 : chunk);
-    chunk = (chunk + Cfg::kS - 1) / Cfg::kS * Cfg::kS;
-    int64_t items = 0;
-    for (int k = 0; k < m->kvol; ++k) items += (m->counts[k] + chunk - 1) / chunk;
-    const int per = cin * cout;
-    Buf part = dev_alloc((size_t)(items ? items : 1) * per * 4);
-    if (!part) return SP_ERR_ALLOC;
-    if (items > 0) {
-        StagedArgs a;
-        a.pair_in = ptr<int32_t>(m->pair_in);
-        a.pair_out = ptr<int32_t>(m->pair_out);
-        a.koff = ptr<int32_t>(m->d_koff);
-        a.x = x;
-        a.dy = dy;
-        a.part = ptr<float>(part);
-        a.kvol = m->kvol;
-        a.chunk = (int)chunk;
-        a.cin = cin;
-        a.cout = cout;
-        a.x_bytes = (uint32_t)((uint64_t)m->n_in * cin * sizeof(T));
-        a.dy_bytes = (uint32_t)((uint64_t)m->n_out * cout * sizeof(T));
-        a.pair_bytes = (uint32_t)((uint64_t)m->total * 4);
-        hipLaunchKernelGGL(kern, dim3((unsigned)items, cout / COB, cin / CIB), dim3(Cfg::kThreads), Cfg::kLds, s, a);
-    }
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((per + 63) / 64, m->kvol), dim3(256), 0, s, ptr<float>(part),
-                       ptr<int32_t>(m->d_koff), m->kvol, (int)chunk, per, dw);
+    const int kvol = m->kvol, per = cin * cout;
+    StagedArgs a;
+    PlanArgs& pa = a.plan;
+    pa.kvol = kvol;
+    pa.tiles = (cout / COB) * (cin / CIB);
+    for (int k = 0; k <= kvol; ++k) pa.koff[k] = (int32_t)m->koff[k];
+    // Strips: about 1.5 MB of rows (both operands) each, but long enough that an offset's stretch in a strip
+    // (which costs a partial block of per * 4 bytes) has at least ~1024 links or per / 32 of them.
+    int occ = 1;
+    SP_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kern, Cfg::kThreads, Cfg::kLds));
+    occ = occ < 1 ? 1 : occ;
+    const int64_t rows_bytes = (m->n_in * (int64_t)cin + m->n_out * (int64_t)cout) * (int64_t)sizeof(T);
+    const int64_t stretch = std::max<int64_t>(1024, per / 32);
+    int64_t M = std::min<int64_t>((rows_bytes / 8 + (3 << 18)) / (3 << 19), m->total / (8 * kvol * stretch));
+    M = M < 1 ? 1 : (M > 128 ? 128 : M);  // the reduction keeps a strip table of 1024 entries in LDS
+    pa.S8 = (int)(8 * M);
+    // Chunks: when everything fits the GPU at once, exactly as many workgroups as are resident together
+    // (one round, equal chunks); otherwise about 2048 links each.
+    const int64_t strip_links = (m->total + pa.S8 - 1) / pa.S8 + kvol;  // upper bound of a strip's sequence
+    const int64_t resident = (int64_t)256 * occ / pa.tiles;
+    int64_t nc = resident / pa.S8;
+    const int64_t links = 2048;
+    if (nc < 1 || strip_links > nc * links) nc = (strip_links + links - 1) / links;
+    int64_t C = (strip_links + nc - 1) / nc;
+    C = (C + Cfg::kS - 1) / Cfg::kS * Cfg::kS;
+    pa.nc = (int)nc;
+    pa.C = (int)C;
+    pa.slots_per_strip = (int)nc + kvol;
+    const int64_t slots = (int64_t)pa.S8 * pa.slots_per_strip;
+    Buf part = dev_alloc((size_t)slots * per * 4);
+    const size_t nsk = (size_t)pa.S8 * kvol;
+    Buf plan = dev_alloc((nsk * 4 + (size_t)pa.S8 * nc * 3) * 4);
+    if (!part || !plan) return SP_ERR_ALLOC;
+    int32_t* d_lo = ptr<int32_t>(plan);
+    int32_t *d_len = d_lo + nsk, *d_first = d_len + nsk, *d_count = d_first + nsk, *d_cstart = d_count + nsk;
+    a.lo_tab = d_lo;
+    a.len_tab = d_len;
+    a.cstart = d_cstart;
+    a.pair_in = ptr<int32_t>(m->pair_in);
+    a.pair_out = ptr<int32_t>(m->pair_out);
+    a.x = x;
+    a.dy = dy;
+    a.part = ptr<float>(part);
+    a.cin = cin;
+    a.cout = cout;
+    a.x_bytes = (uint32_t)((uint64_t)m->n_in * cin * sizeof(T));
+    a.dy_bytes = (uint32_t)((uint64_t)m->n_out * cout * sizeof(T));
+    a.pair_bytes = (uint32_t)((uint64_t)m->total * 4);
+    hipLaunchKernelGGL(wgrad_plan_kernel, dim3(pa.S8), dim3(64), 0, s, pa, d_lo, d_len, d_first, d_count,
+                       d_cstart);
+    const int64_t wgs = (int64_t)pa.S8 * nc * pa.tiles;
+    hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(Cfg::kThreads), Cfg::kLds, s, a);
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(per / 64, kvol), dim3(256), 0, s, ptr<float>(part), d_first, d_count,
+                       pa.S8, kvol, per, dw);
     SP_HIP(hipGetLastError());
     return SP_OK;
 }
@@ -465,55 +541,35 @@ int channel_block(int c) { return c % 128 == 0 ? 128 : (c % 64 == 0 ? 64 : (c % 
 template <typename T>
 int wgrad_typed(const sp_kmap* m, const void* x, const void* dy, float* dw, int cin, int cout, hipStream_t s) {
     const int kvol = m->kvol;
-    if (cin % 16 || cout % 16) {
+    const uint64_t lim = 0x7fffffffull;  // the staged kernel addresses its buffers with 32-bit offsets
+    const bool small = (uint64_t)m->n_in * cin * sizeof(T) < lim && (uint64_t)m->n_out * cout * sizeof(T) < lim &&
+                       (uint64_t)m->total * 4 < lim;
+    if (cin % 16 || cout % 16 || !small || m->total == 0 || kvol > 128) {
         hipLaunchKernelGGL(wgrad_plain_kernel<T>, dim3((cin * cout + 255) / 256, kvol), dim3(256), 0, s,
                            ptr<int32_t>(m->pair_in), ptr<int32_t>(m->pair_out), ptr<int32_t>(m->d_koff),
                            static_cast<const T*>(x), static_cast<const T*>(dy), cin, cout, dw);
         SP_HIP(hipGetLastError());
         return SP_OK;
     }
-    const uint64_t lim = 0x7fffffffull;
-    const bool small = (uint64_t)m->n_in * cin * sizeof(T) < lim && (uint64_t)m->n_out * cout * sizeof(T) < lim &&
-                       (uint64_t)m->total * 4 < lim;
-    if (small) {
-        int cob = channel_block(cout), cib = channel_block(cin);
-        if (cob == 128 && cib < 64) cob = 64;  // 128-wide tiles only in the combinations instantiated below
-        if (cib == 128 && cob < 64) cib = 64;
+    int cob = channel_block(cout), cib = channel_block(cin);
+    if (cob == 128 && cib < 64) cob = 64;  // 128-wide tiles only in the combinations instantiated below
+    if (cib == 128 && cob < 64) cib = 64;
 #define SP_STAGED(COB, CIB, WCO, WCI, WK) \
-    if (cob == COB && cib == CIB) return launch_staged<T, COB, CIB, WCO, WCI, WK>(m, x, dy, cin, cout, dw, s)
-        SP_STAGED(128, 128, 2, 2, 1);
-        SP_STAGED(128, 64, 2, 1, 2);
-        SP_STAGED(64, 128, 1, 2, 2);
-        SP_STAGED(64, 64, 2, 1, 2);
-        SP_STAGED(64, 32, 2, 1, 2);
-        SP_STAGED(32, 64, 1, 2, 2);
-        SP_STAGED(64, 16, 2, 1, 2);
-        SP_STAGED(16, 64, 1, 2, 2);
-        SP_STAGED(32, 32, 1, 1, 2);
-        SP_STAGED(32, 16, 1, 1, 4);
-        SP_STAGED(16, 32, 1, 1, 4);
-        SP_STAGED(16, 16, 1, 1, 4);
+    if (cob == COB && cib == CIB) return launch_staged<T, COB, CIB, WCO, WCI, WK, 1>(m, x, dy, cin, cout, dw, s)
+    SP_STAGED(128, 128, 2, 2, 1);
+    SP_STAGED(128, 64, 2, 1, 2);
+    SP_STAGED(64, 128, 1, 2, 2);
+    SP_STAGED(64, 64, 2, 1, 2);
+    SP_STAGED(64, 32, 2, 1, 2);
+    SP_STAGED(32, 64, 1, 2, 2);
+    SP_STAGED(64, 16, 2, 1, 2);
+    SP_STAGED(16, 64, 1, 2, 2);
+    SP_STAGED(32, 32, 1, 1, 2);
+    SP_STAGED(32, 16, 1, 1, 4);
+    SP_STAGED(16, 32, 1, 1, 4);
+    SP_STAGED(16, 16, 1, 1, 4);
 #undef SP_STAGED
-    }
-    // buffers of 2 GiB and more: fragment-shaped global loads with 64-bit addressing
-    // chunk: about 1024 work items over the whole map, between 64 and 4096 links each, a multiple of 16
-    int64_t chunk = (m->total + 1023) / 1024;
-    chunk = chunk < 64 ? 64 : (chunk > 4096 ? 4096 : chunk);
-    chunk = (chunk + 15) / 16 * 16;
-    int64_t items = 0;
-    for (int k = 0; k < kvol; ++k) items += (m->counts[k] + chunk - 1) / chunk;
-    const int per = cin * cout;
-    Buf part = dev_alloc((size_t)(items ? items : 1) * per * 4);
-    if (!part) return SP_ERR_ALLOC;
-    if (items > 0) {
-        const bool co32 = cout % 32 == 0, ci32 = cin % 32 == 0;
-        if (co32 && ci32) launch_partial<T, 32, 32>(m, (int)items, (int)chunk, x, dy, cin, cout, ptr<float>(part), s);
-        else launch_partial<T, 16, 16>(m, (int)items, (int)chunk, x, dy, cin, cout, ptr<float>(part), s);
-    }
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((per + 63) / 64, kvol), dim3(256), 0, s, ptr<float>(part),
-                       ptr<int32_t>(m->d_koff), kvol, (int)chunk, per, dw);
-    SP_HIP(hipGetLastError());
-    return SP_OK;
+    return fail(SP_ERR_UNSUPPORTED, "no weight-gradient kernel for %d x %d channels", cout, cin);
 }
 
 }  // namespace
