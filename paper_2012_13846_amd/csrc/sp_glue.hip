@@ -76,7 +76,8 @@ __global__ __launch_bounds__(kThreads) void column_sums_kernel(const T* __restri
     }
 }
 
-// One thread per channel adds the block partials in block order, in double.
+// Adds the block partials in double, in a fixed order: 8 interleaved running sums per channel (block b goes
+// to sum b % 8), then added 0..7.  Block = 32 channels x 8 slices.
 // MODE 0: mean / rstd (the partials are sums of deviations from `shift[ch]`).  MODE 1: dbeta (sum 0) /
 // dgamma (sum 1).
 template <int MODE, typename T>
@@ -85,12 +86,24 @@ __global__ __launch_bounds__(kThreads) void column_sums_final_kernel(const float
                                                                      const T* __restrict__ shift,
                                                                      float* __restrict__ out0,
                                                                      float* __restrict__ out1) {
-    const int ch = blockIdx.x * kThreads + threadIdx.x;
-    if (ch >= c) return;
+    __shared__ double red[2][8][32];
+    const int cx = threadIdx.x & 31, slice = threadIdx.x >> 5;
+    const int ch = blockIdx.x * 32 + cx;
     double s0 = 0.0, s1 = 0.0;
-    for (int64_t b = 0; b < nblk; ++b) {
-        s0 += (double)partial[((size_t)b * 2 + 0) * c + ch];
-        s1 += (double)partial[((size_t)b * 2 + 1) * c + ch];
+    if (ch < c)
+        for (int64_t b = slice; b < nblk; b += 8) {
+            s0 += (double)partial[((size_t)b * 2 + 0) * c + ch];
+            s1 += (double)partial[((size_t)b * 2 + 1) * c + ch];
+        }
+    red[0][slice][cx] = s0;
+    red[1][slice][cx] = s1;
+    __syncthreads();
+    if (slice != 0 || ch >= c) return;
+    s0 = red[0][0][cx];
+    s1 = red[1][0][cx];
+    for (int j = 1; j < 8; ++j) {
+        s0 += red[0][j][cx];
+        s1 += red[1][j][cx];
     }
     if (MODE == 0) {
         const double md = n > 0 ? s0 / (double)n : 0.0;     // mean deviation from the shift
@@ -101,6 +114,191 @@ __global__ __launch_bounds__(kThreads) void column_sums_final_kernel(const float
     } else {
         out0[ch] = (float)s0;
         out1[ch] = (float)s1;
+    }
+}
+
+// ---- 16-byte-vector versions for channel counts that are a multiple of 16 bytes --------------------------------
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+template <typename T>
+struct Vec {
+    static constexpr int kN = 16 / sizeof(T);  // elements per 16 bytes
+    float v[kN];
+};
+__device__ __forceinline__ void unpack(const u32x4& r, Vec<float>& o) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o.v[i] = __uint_as_float(r[i]);
+}
+__device__ __forceinline__ void unpack(const u32x4& r, Vec<bf16_t>& o) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        o.v[2 * i] = __uint_as_float(r[i] << 16);
+        o.v[2 * i + 1] = __uint_as_float(r[i] & 0xffff0000u);
+    }
+}
+__device__ __forceinline__ uint32_t bf16_bits(float v) {
+    const uint32_t u = __float_as_uint(v);
+    return (u & 0x7fffffffu) > 0x7f800000u ? ((u >> 16) | 0x40) : ((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+__device__ __forceinline__ u32x4 pack(const Vec<float>& o) {
+    return u32x4{__float_as_uint(o.v[0]), __float_as_uint(o.v[1]), __float_as_uint(o.v[2]), __float_as_uint(o.v[3])};
+}
+__device__ __forceinline__ u32x4 pack(const Vec<bf16_t>& o) {
+    u32x4 r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i] = bf16_bits(o.v[2 * i]) | (bf16_bits(o.v[2 * i + 1]) << 16);
+    return r;
+}
+template <typename T>
+__device__ __forceinline__ Vec<T> load_vec(const T* p, size_t elem) {
+    Vec<T> o;
+    unpack(*reinterpret_cast<const u32x4*>(p + elem), o);
+    return o;
+}
+
+// Same sums as column_sums_kernel.  Thread = (row lane, 16-byte channel group); tpr = c / kN threads cover a
+// row, 256 / tpr rows are read per pass (tpr need not divide 256: the spare threads idle).  The block's rows
+// are rows [blockIdx.x * rows_per_block, ...).  Row lanes are added in lane order.
+template <typename T, int MODE>
+__global__ __launch_bounds__(kThreads) void column_sums_vec_kernel(const T* __restrict__ x, const T* __restrict__ y,
+                                                                   const T* __restrict__ dy, int64_t n, int c,
+                                                                   int64_t rows_per_block,
+                                                                   const float* __restrict__ mean,
+                                                                   const float* __restrict__ rstd, int relu,
+                                                                   float* __restrict__ partial) {
+    constexpr int kN = Vec<T>::kN;
+    extern __shared__ float red[];  // [2][row lanes][c]
+    const int tpr = c / kN, lanes = kThreads / tpr;
+    const int cg = threadIdx.x % tpr, rl = threadIdx.x / tpr;
+    const int64_t row_beg = (int64_t)blockIdx.x * rows_per_block;
+    const int64_t row_end = row_beg + rows_per_block < n ? row_beg + rows_per_block : n;
+    float s0[kN], s1[kN], m[kN], rs[kN];
+#pragma unroll
+    for (int i = 0; i < kN; ++i) s0[i] = s1[i] = m[i] = rs[i] = 0.f;
+    if (rl < lanes) {
+        if (MODE == 0) {
+            // sums of deviations from the channel's first row (a shift close to the mean keeps
+            // E[d^2] - E[d]^2 free of cancellation; a single row gives variance exactly 0)
+            const Vec<T> f = load_vec(x, (size_t)cg * kN);
+#pragma unroll
+            for (int i = 0; i < kN; ++i) m[i] = f.v[i];
+        } else {
+#pragma unroll
+            for (int i = 0; i < kN; ++i) {
+                m[i] = mean[cg * kN + i];
+                rs[i] = rstd[cg * kN + i];
+            }
+        }
+        for (int64_t r = row_beg + rl; r < row_end; r += lanes) {
+            const size_t e = (size_t)r * c + (size_t)cg * kN;
+            const Vec<T> xv = load_vec(x, e);
+            if (MODE == 0) {
+#pragma unroll
+                for (int i = 0; i < kN; ++i) {
+                    const float v = xv.v[i] - m[i];
+                    s0[i] += v;
+                    s1[i] += v * v;
+                }
+            } else {
+                const Vec<T> gv = load_vec(dy, e);
+                Vec<T> yv = gv;
+                if (relu) yv = load_vec(y, e);
+#pragma unroll
+                for (int i = 0; i < kN; ++i) {
+                    float g = gv.v[i];
+                    if (relu && !(yv.v[i] > 0.f)) g = 0.f;
+                    s0[i] += g;
+                    s1[i] += g * (xv.v[i] - m[i]) * rs[i];
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < kN; ++i) {
+            red[(0 * lanes + rl) * c + cg * kN + i] = s0[i];
+            red[(1 * lanes + rl) * c + cg * kN + i] = s1[i];
+        }
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < 2 * c; e += kThreads) {
+        const int q = e / c, ch = e % c;
+        float t = 0.f;
+        for (int j = 0; j < lanes; ++j) t += red[(q * lanes + j) * c + ch];
+        partial[((size_t)blockIdx.x * 2 + q) * c + ch] = t;
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void bn_apply_vec_kernel(const T* __restrict__ x, T* __restrict__ y,
+                                                                int64_t chunks, int c, const float* __restrict__ gamma,
+                                                                const float* __restrict__ beta,
+                                                                const float* __restrict__ mean,
+                                                                const float* __restrict__ rstd, int relu) {
+    constexpr int kN = Vec<T>::kN;
+    // the grid stride is cut to a multiple of the 16-byte groups per row, so a thread stays on its channels
+    const int tpr = c / kN;
+    const int64_t stride = (int64_t)gridDim.x * kThreads / tpr * tpr;
+    const int64_t i0 = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i0 >= stride) return;
+    const int ch = (int)(i0 % tpr) * kN;
+    float m[kN], k[kN], g[kN], b[kN];
+#pragma unroll
+    for (int j = 0; j < kN; ++j) {
+        m[j] = mean[ch + j];
+        k[j] = rstd[ch + j];
+        g[j] = gamma[ch + j];
+        b[j] = beta[ch + j];
+    }
+    for (int64_t i = i0; i < chunks; i += stride) {
+        const Vec<T> xv = load_vec(x, (size_t)i * kN);
+        Vec<T> o;
+#pragma unroll
+        for (int j = 0; j < kN; ++j) {
+            float v = (xv.v[j] - m[j]) * k[j] * g[j] + b[j];
+            if (relu) v = fmaxf(v, 0.f);
+            o.v[j] = v;
+        }
+        *reinterpret_cast<u32x4*>(y + (size_t)i * kN) = pack(o);
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void bn_bwd_apply_vec_kernel(const T* __restrict__ x, const T* __restrict__ y,
+                                                                    const T* __restrict__ dy, T* __restrict__ dx,
+                                                                    int64_t n, int c, const float* __restrict__ gamma,
+                                                                    const float* __restrict__ mean,
+                                                                    const float* __restrict__ rstd,
+                                                                    const float* __restrict__ dgamma,
+                                                                    const float* __restrict__ dbeta, int relu) {
+    constexpr int kN = Vec<T>::kN;
+    const int64_t chunks = n * c / kN;
+    const float inv_n = 1.f / (float)n;
+    const int tpr = c / kN;
+    const int64_t stride = (int64_t)gridDim.x * kThreads / tpr * tpr;
+    const int64_t i0 = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i0 >= stride) return;
+    const int ch = (int)(i0 % tpr) * kN;
+    float m[kN], k[kN], ga[kN], dg[kN], db[kN];
+#pragma unroll
+    for (int j = 0; j < kN; ++j) {
+        m[j] = mean[ch + j];
+        k[j] = rstd[ch + j];
+        ga[j] = gamma[ch + j];
+        dg[j] = dgamma[ch + j];
+        db[j] = dbeta[ch + j];
+    }
+    for (int64_t i = i0; i < chunks; i += stride) {
+        const size_t e = (size_t)i * kN;
+        const Vec<T> xv = load_vec(x, e), gv = load_vec(dy, e);
+        Vec<T> yv = gv;
+        if (relu) yv = load_vec(y, e);
+        Vec<T> o;
+#pragma unroll
+        for (int j = 0; j < kN; ++j) {
+            float g = gv.v[j];
+            if (relu && !(yv.v[j] > 0.f)) g = 0.f;
+            const float xhat = (xv.v[j] - m[j]) * k[j];
+            o.v[j] = ga[j] * k[j] * (g - (db[j] + xhat * dg[j]) * inv_n);
+        }
+        *reinterpret_cast<u32x4*>(dx + (size_t)i * kN) = pack(o);
     }
 }
 
@@ -286,21 +484,51 @@ inline unsigned stream_blocks(int64_t total) {
     return (unsigned)(b < 1 ? 1 : (b > 65536 ? 65536 : b));
 }
 
+// vector kernels: whole 16-byte groups per row, at most 256 of them, 16-byte aligned base pointers
+template <typename T>
+bool vec_ok(int c, const void* p0, const void* p1, const void* p2, const void* p3) {
+    constexpr int kN = 16 / (int)sizeof(T);
+    const uintptr_t bits = (uintptr_t)p0 | (uintptr_t)p1 | (uintptr_t)p2 | (uintptr_t)p3;
+    return c % kN == 0 && c / kN <= kThreads && (bits & 15) == 0;
+}
+// rows per block of the vector column sums: at most 512 blocks, at least 256 rows each
+inline int64_t vec_rows_per_block(int64_t n) {
+    const int64_t r = (n + 511) / 512;
+    return r < 256 ? 256 : r;
+}
+
 template <typename T>
 int bn_fwd_typed(const void* x, int64_t n, int c, const float* gamma, const float* beta, float eps, int relu, void* y,
                  float* mean, float* rstd, hipStream_t s) {
-    const int64_t nblk = (n + kSlabRows - 1) / kSlabRows;
+    const bool vec = vec_ok<T>(c, x, y, nullptr, nullptr);
+    const int64_t rpb = vec ? vec_rows_per_block(n) : kSlabRows;
+    const int64_t nblk = (n + rpb - 1) / rpb;
     Buf partial = dev_alloc((size_t)(nblk ? nblk : 1) * 2 * c * 4);
     if (!partial) return SP_ERR_ALLOC;
-    if (nblk > 0)
-        hipLaunchKernelGGL((column_sums_kernel<T, 0>), dim3((unsigned)nblk), dim3(kThreads), 0, s,
-                           static_cast<const T*>(x), (const T*)nullptr, (const T*)nullptr, n, c, (const float*)nullptr,
-                           (const float*)nullptr, 0, ptr<float>(partial));
-    hipLaunchKernelGGL((column_sums_final_kernel<0, T>), dim3((c + kThreads - 1) / kThreads), dim3(kThreads), 0, s,
-                       ptr<float>(partial), nblk, n, c, eps, static_cast<const T*>(x), mean, rstd);
-    if (n > 0)
-        hipLaunchKernelGGL(bn_apply_kernel<T>, dim3(stream_blocks(n * c)), dim3(kThreads), 0, s,
-                           static_cast<const T*>(x), static_cast<T*>(y), n * c, c, gamma, beta, mean, rstd, relu);
+    if (nblk > 0) {
+        if (vec) {
+            const int lanes = kThreads / (c / (16 / (int)sizeof(T)));
+            hipLaunchKernelGGL((column_sums_vec_kernel<T, 0>), dim3((unsigned)nblk), dim3(kThreads),
+                               (size_t)2 * lanes * c * 4, s, static_cast<const T*>(x), (const T*)nullptr,
+                               (const T*)nullptr, n, c, rpb, (const float*)nullptr, (const float*)nullptr, 0,
+                               ptr<float>(partial));
+        } else {
+            hipLaunchKernelGGL((column_sums_kernel<T, 0>), dim3((unsigned)nblk), dim3(kThreads), 0, s,
+                               static_cast<const T*>(x), (const T*)nullptr, (const T*)nullptr, n, c,
+                               (const float*)nullptr, (const float*)nullptr, 0, ptr<float>(partial));
+        }
+    }
+    hipLaunchKernelGGL((column_sums_final_kernel<0, T>), dim3((c + 31) / 32), dim3(kThreads), 0, s, ptr<float>(partial),
+                       nblk, n, c, eps, static_cast<const T*>(x), mean, rstd);
+    if (n > 0) {
+        if (vec)
+            hipLaunchKernelGGL(bn_apply_vec_kernel<T>, dim3(stream_blocks(n * c / (16 / (int64_t)sizeof(T)))),
+                               dim3(kThreads), 0, s, static_cast<const T*>(x), static_cast<T*>(y),
+                               n * c / (16 / (int64_t)sizeof(T)), c, gamma, beta, mean, rstd, relu);
+        else
+            hipLaunchKernelGGL(bn_apply_kernel<T>, dim3(stream_blocks(n * c)), dim3(kThreads), 0, s,
+                               static_cast<const T*>(x), static_cast<T*>(y), n * c, c, gamma, beta, mean, rstd, relu);
+    }
     SP_HIP(hipGetLastError());
     return SP_OK;
 }
@@ -308,19 +536,36 @@ int bn_fwd_typed(const void* x, int64_t n, int c, const float* gamma, const floa
 template <typename T>
 int bn_bwd_typed(const void* x, const void* y, const void* dy, int64_t n, int c, const float* gamma, const float* mean,
                  const float* rstd, int relu, void* dx, float* dgamma, float* dbeta, hipStream_t s) {
-    const int64_t nblk = (n + kSlabRows - 1) / kSlabRows;
+    const bool vec = vec_ok<T>(c, x, y, dy, dx);
+    const int64_t rpb = vec ? vec_rows_per_block(n) : kSlabRows;
+    const int64_t nblk = (n + rpb - 1) / rpb;
     Buf partial = dev_alloc((size_t)(nblk ? nblk : 1) * 2 * c * 4);
     if (!partial) return SP_ERR_ALLOC;
-    if (nblk > 0)
-        hipLaunchKernelGGL((column_sums_kernel<T, 1>), dim3((unsigned)nblk), dim3(kThreads), 0, s,
-                           static_cast<const T*>(x), static_cast<const T*>(y), static_cast<const T*>(dy), n, c, mean,
-                           rstd, relu, ptr<float>(partial));
-    hipLaunchKernelGGL((column_sums_final_kernel<1, T>), dim3((c + kThreads - 1) / kThreads), dim3(kThreads), 0, s,
-                       ptr<float>(partial), nblk, n, c, 0.f, (const T*)nullptr, dbeta, dgamma);
-    if (n > 0)
-        hipLaunchKernelGGL(bn_bwd_apply_kernel<T>, dim3(stream_blocks(n * c)), dim3(kThreads), 0, s,
-                           static_cast<const T*>(x), static_cast<const T*>(y), static_cast<const T*>(dy),
-                           static_cast<T*>(dx), n, c, gamma, mean, rstd, dgamma, dbeta, relu);
+    if (nblk > 0) {
+        if (vec) {
+            const int lanes = kThreads / (c / (16 / (int)sizeof(T)));
+            hipLaunchKernelGGL((column_sums_vec_kernel<T, 1>), dim3((unsigned)nblk), dim3(kThreads),
+                               (size_t)2 * lanes * c * 4, s, static_cast<const T*>(x), static_cast<const T*>(y),
+                               static_cast<const T*>(dy), n, c, rpb, mean, rstd, relu, ptr<float>(partial));
+        } else {
+            hipLaunchKernelGGL((column_sums_kernel<T, 1>), dim3((unsigned)nblk), dim3(kThreads), 0, s,
+                               static_cast<const T*>(x), static_cast<const T*>(y), static_cast<const T*>(dy), n, c, mean,
+                               rstd, relu, ptr<float>(partial));
+        }
+    }
+    hipLaunchKernelGGL((column_sums_final_kernel<1, T>), dim3((c + 31) / 32), dim3(kThreads), 0, s, ptr<float>(partial),
+                       nblk, n, c, 0.f, (const T*)nullptr, dbeta, dgamma);
+    if (n > 0) {
+        if (vec)
+            hipLaunchKernelGGL(bn_bwd_apply_vec_kernel<T>, dim3(stream_blocks(n * c / (16 / (int64_t)sizeof(T)))),
+                               dim3(kThreads), 0, s, static_cast<const T*>(x), static_cast<const T*>(y),
+                               static_cast<const T*>(dy), static_cast<T*>(dx), n, c, gamma, mean, rstd, dgamma, dbeta,
+                               relu);
+        else
+            hipLaunchKernelGGL(bn_bwd_apply_kernel<T>, dim3(stream_blocks(n * c)), dim3(kThreads), 0, s,
+                               static_cast<const T*>(x), static_cast<const T*>(y), static_cast<const T*>(dy),
+                               static_cast<T*>(dx), n, c, gamma, mean, rstd, dgamma, dbeta, relu);
+    }
     SP_HIP(hipGetLastError());
     return SP_OK;
 }
