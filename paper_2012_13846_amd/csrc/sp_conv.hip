@@ -661,6 +661,26 @@ int conv_gather(const MapSide& side, int kvol, int64_t total_links, const void* 
                 void* d_g, int cc, int co, sp_dtype dt, hipStream_t s) {
     if (side.n_rows == 0) return SP_OK;
     const size_t elt = dt == SP_F32 ? 4 : 2;
+    // Row-stationary kernel: it multiplies all kvol offsets of every row, the link-list kernels only the links
+    // that exist but pay per link for bookkeeping, weight re-reads and the accumulator update.
+    const uint64_t lim = 0x7fffffffull;
+    double min_fill = 0.25;
+    if (const char* e = getenv("SP_DENSE_FILL")) min_fill = atof(e);
+    if (dense_shape_ok(cc, co, dt) && (double)total_links >= min_fill * (double)side.n_rows * kvol &&
+        (uint64_t)side.n_src * cc * elt < lim && (uint64_t)side.n_rows * kvol * 4 < lim &&
+        (uint64_t)kvol * cc * co * elt < lim) {
+        Buf wt;
+        const void* w = d_w;
+        if (w_transposed) {  // stored matrix is [cout = cc][cin = co]; the kernel wants [co][cc]
+            const int64_t n = (int64_t)kvol * cc * co;
+            wt = dev_alloc((size_t)n * elt);
+            if (!wt) return SP_ERR_ALLOC;
+            hipLaunchKernelGGL(transpose_w_kernel<bf16_t>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
+                               static_cast<const bf16_t*>(d_w), ptr<bf16_t>(wt), kvol, cc, co);
+            w = wt->p;
+        }
+        return conv_gather_dense(side, kvol, d_f, w, d_g, cc, co, s);
+    }
     if (mma_shape_ok(cc, co, dt)) {
         GatherArgs a;
         a.tl_off = ptr<int32_t>(side.tl_off);

@@ -1,0 +1,282 @@
+// Step 3 of the generalized sparse convolution (Eq. 2) for wide bf16 layers on dense-ish maps: a
+// destination-row-stationary kernel whose accumulators never leave the registers.
+//
+// A workgroup owns 256 destination rows and 128 destination channels.  For every kernel offset it reads the
+// rows' neighbour table entries, gathers the neighbours' feature rows (zeros where an offset has no
+// neighbour) and the offset's weight matrix through LDS in slices of 64 contraction channels, and
+// multiplies on the bf16 matrix cores: acc[row][co] += X[nbr_k(row)][:] . W_k[co][:].  Rows without a
+// neighbour multiply zeros, so the kernel pays for all kvol offsets of every row: it is chosen only when a
+// good part of them is there (the host decides from the map's link count), where it wins because bf16 MFMA
+// throughput is 16 times the fp32 one while this form needs no per-link bookkeeping, no scatter and no
+// accumulator traffic.  Each destination row belongs to one workgroup and the offsets are added in index
+// order: no atomics, reproducible, rounded once.
+#include "sp_internal.h"
+
+namespace sp {
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint16_t bf16_t;
+
+__device__ __forceinline__ uint32_t bf16_bits(float f) {  // round to nearest even; NaN stays NaN
+    const uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40;
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+// acc += A * B in place.  Written as an instruction because the compiler, given the builtin and this much
+// register pressure, gives the products fresh registers and copies all 128 accumulators around at the loop's
+// back edge; the tied operand keeps every accumulator in one AGPR quad for the whole kernel.
+__device__ __forceinline__ void mfma_acc(f32x4& acc, const bf16x8& a, const bf16x8& b) {
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+
+struct DenseArgs {
+    const int32_t* nbr;  // [kvol][n_rows] source row or -1
+    const void* f;       // source features [n_src][CC] bf16
+    const void* w;       // weights [kvol][co_total][CC] bf16
+    void* g;             // destination features [n_rows][co_total] bf16
+    int64_t n_rows;
+    int kvol, co_total, flip;
+    uint32_t f_bytes, w_bytes, nbr_bytes;
+};
+
+template <int CC, int COT>
+struct DenseCfg {
+    static constexpr int kTR = 256;                  // destination rows per workgroup
+    static constexpr int kKS = 64;                   // contraction channels per step
+    static constexpr int kPitch = kKS * 2 + 32;      // staged slice row: 128 bytes + 32 (measured: b128 fragment reads of 16 rows
+                                                     // run at the full 256 B/clk with this pad, at 160 B/clk with 16)
+    static constexpr int kXBytes = kTR * kPitch, kWBytes = COT * kPitch, kBuf = kXBytes + kWBytes;
+    static constexpr int kSlices = CC / kKS;
+    static constexpr int kXLoads = kTR * 8 / 256;    // 16-byte pieces per thread and step: rows x 8 pieces / 256 threads
+    static constexpr int kWLoads = COT * 8 / 256;
+    static constexpr int kOutPitch = COT * 2 + 16;   // output staging row (bf16)
+    static constexpr int kLds = 2 * kBuf > kTR * kOutPitch ? 2 * kBuf : kTR * kOutPitch;
+    static constexpr int kMI = kTR / 4 / 16;         // 16-row groups per wavefront (4 wavefronts split the rows)
+    static constexpr int kNI = COT / 16;             // 16-channel tiles per wavefront (each takes all channels)
+    static_assert(CC % kKS == 0, "contraction channels in whole slices");
+};
+
+template <int CC, int COT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void gather_dense_kernel(DenseArgs a) {
+    using Cfg = DenseCfg<CC, COT>;
+    constexpr int kMI = Cfg::kMI, kNI = Cfg::kNI, kPitch = Cfg::kPitch, kSlices = Cfg::kSlices;
+    constexpr int kXLoads = Cfg::kXLoads, kWLoads = Cfg::kWLoads;
+    extern __shared__ __align__(16) unsigned char smem[];
+
+    // Workgroups of one row tile (one per channel slice) get ids that differ by 8: same XCD (id % 8), launched
+    // back to back, so the second one's gathers hit that XCD's L2.
+    const int nslice = a.co_total / COT;
+    const int id = blockIdx.x;
+    const int64_t tile = (int64_t)(id / (8 * nslice)) * 8 + id % 8;
+    const int co0 = ((id / 8) % nslice) * COT;
+    const int64_t row0 = tile * Cfg::kTR;
+    if (row0 >= a.n_rows) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n16 = lane & 15, g = lane >> 4;
+
+    constexpr int kRsrcFlags = 0x00020000;
+    constexpr uint32_t kOutside = 0x80000000u;  // buffers are smaller than 2 GiB: this offset reads as zeros
+    const __amdgpu_buffer_rsrc_t rF = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(a.f), 0, (int)a.f_bytes, kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t rW = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(a.w), 0, (int)a.w_bytes, kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t rN =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t*>(a.nbr), 0, (int)a.nbr_bytes, kRsrcFlags);
+
+    // Loading: 8 adjacent lanes fetch the 8 pieces of one 128-byte slice row; thread t takes piece t % 8 of
+    // the tile rows t / 8 + 32 j and of the weight rows (destination channels) t / 8 + 32 j.
+    const int piece = tid & 7, lrow = tid >> 3;
+    const int st_off = lrow * kPitch + piece * 16;  // + 32 j rows
+    struct Stage {
+        u32x4 x[kXLoads], w[kWLoads];
+    };
+    // Per offset and thread: the byte offsets of its kXLoads source rows (kOutside where the row has no
+    // neighbour: such a load returns zeros) and of its first weight row.  A step's loads then differ from
+    // these only by constants, which ride in the instruction's scalar offset.
+    struct Where {
+        uint32_t x[kXLoads], w;
+    };
+    auto load_nbr = [&](int k, int (&raw)[kXLoads]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < kXLoads; ++j) {
+            const int64_t row = row0 + lrow + 32 * j;
+            const bool live = row < a.n_rows && k < a.kvol;
+            // past the table the load returns 0, which would name row 0: such entries are masked in locate()
+            raw[j] = (int)__builtin_amdgcn_raw_buffer_load_b32(
+                rN, live ? (uint32_t)(((int64_t)k * a.n_rows + row) * 4) : kOutside, 0, 0);
+        }
+    };
+    auto locate = [&](int k, const int (&raw)[kXLoads], Where& wh) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < kXLoads; ++j) {
+            const bool live = row0 + lrow + 32 * j < a.n_rows && k < a.kvol && raw[j] >= 0;
+            wh.x[j] = live ? (uint32_t)raw[j] * (CC * 2) + piece * 16 : kOutside;
+        }
+        const int wk = a.flip ? a.kvol - 1 - k : k;
+        wh.w = k < a.kvol ? ((uint32_t)wk * a.co_total + co0 + lrow) * (CC * 2) + piece * 16 : kOutside;
+    };
+    // load / LDS store number i of a step: i < kXLoads gathered rows, then the weight rows
+    constexpr int kLoads = kXLoads + kWLoads;
+    auto issue_one = [&](Stage& st, int i, int s, const Where& wh) __attribute__((always_inline)) {
+        if (i < kXLoads) st.x[i] = __builtin_amdgcn_raw_buffer_load_b128(rF, wh.x[i], s * 128, 0);
+        else st.w[i - kXLoads] = __builtin_amdgcn_raw_buffer_load_b128(rW, wh.w, (i - kXLoads) * 32 * (CC * 2) + s * 128, 0);
+    };
+    auto store_one = [&](const Stage& st, int i, unsigned char* buf) __attribute__((always_inline)) {
+        if (i < kXLoads) *reinterpret_cast<u32x4*>(buf + st_off + i * 32 * kPitch) = st.x[i];
+        else *reinterpret_cast<u32x4*>(buf + Cfg::kXBytes + st_off + (i - kXLoads) * 32 * kPitch) = st.w[i - kXLoads];
+    };
+    auto issue = [&](Stage& st, int s, const Where& wh) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < kLoads; ++i) issue_one(st, i, s, wh);
+    };
+    auto store = [&](const Stage& st, unsigned char* buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < kLoads; ++i) store_one(st, i, buf);
+    };
+
+    // acc[ni][mi][i]: destination channel co0 + ni*16 + 4*g + i, tile row wave*64 + mi*16 + n16
+    // (weights are the MFMA A operand, the gathered rows the B operand: a lane ends up with 4 adjacent channels
+    // of one row, which pack into one 8-byte store)
+    f32x4 acc[kNI][kMI];
+#pragma unroll
+    for (int ni = 0; ni < kNI; ++ni)
+#pragma unroll
+        for (int mi = 0; mi < kMI; ++mi) acc[ni][mi] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int frag_x = (wave * (Cfg::kTR / 4) + n16) * kPitch + g * 16;   // + mi*16 rows, + 64 bytes for the second k-step
+    const int frag_w = Cfg::kXBytes + n16 * kPitch + g * 16;              // + ni*16 rows
+    // One step = 2 k-steps x kNI channel tiles = 2*kNI groups of kMI MFMAs.  A wavefront issues in order and
+    // an MFMA runs for 16 cycles once issued, so everything else the step has to do is dealt out over the
+    // groups and issued in the shadow of their MFMAs: the LDS fragment reads (two groups ahead of their
+    // use: 3 rotating weight fragments; the second k-step's row fragments during the first k-step), one
+    // global load of step t+2 per group, one LDS store of stage t+1 per group.
+    constexpr int kGroups = 2 * kNI;
+    static_assert(kLoads <= kGroups, "one load and one store per group");
+    auto compute = [&](const unsigned char* buf, auto&& extra) __attribute__((always_inline)) {
+        bf16x8 xf[2][kMI], wf[3];
+        auto read_w = [&](int grp) __attribute__((always_inline)) {
+            return *reinterpret_cast<const bf16x8*>(buf + frag_w + (grp % kNI) * 16 * kPitch + (grp / kNI) * 64);
+        };
+        auto read_x = [&](int ks, int mi) __attribute__((always_inline)) {
+            return *reinterpret_cast<const bf16x8*>(buf + frag_x + mi * 16 * kPitch + ks * 64);
+        };
+#pragma unroll
+        for (int mi = 0; mi < kMI; ++mi) xf[0][mi] = read_x(0, mi);
+        wf[0] = read_w(0);
+        wf[1] = read_w(1);
+#pragma unroll
+        for (int grp = 0; grp < kGroups; ++grp) {
+            if (grp + 2 < kGroups) wf[(grp + 2) % 3] = read_w(grp + 2);
+            if (grp >= 1 && grp <= kMI) xf[1][grp - 1] = read_x(1, grp - 1);
+            extra(grp);
+            __builtin_amdgcn_sched_barrier(0);  // keeps this group's other work ahead of the MFMAs that hide it
+#pragma unroll
+            for (int mi = 0; mi < kMI; ++mi)
+                mfma_acc(acc[grp % kNI][mi], wf[grp % 3], xf[grp / kNI][mi]);
+        }
+    };
+
+    // Steps = (offset, slice), step t = k * kSlices + s.  While step t is multiplied out of LDS buffer t % 2,
+    // the loads of steps t+1 and t+2 are in flight (two register stages: the gathers mostly miss L2, and one
+    // step of arithmetic is shorter than their latency); stage t+1 is then stored to the other buffer.  The
+    // neighbour entries of offset k+1 are requested at the start of offset k.
+    static_assert(kSlices % 2 == 0, "the register stage of a step is s % 2");
+    Where cur, nxt;     // offsets k and k + 1
+    int raw[kXLoads];   // neighbour entries of offset k + 2, in flight
+    Stage st[2];
+    load_nbr(0, raw);
+    locate(0, raw, cur);
+    load_nbr(1, raw);
+    locate(1, raw, nxt);
+    load_nbr(2, raw);
+    issue(st[0], 0, cur);
+    issue(st[1], 1, cur);
+    store(st[0], smem);
+    __syncthreads();
+    for (int k = 0; k < a.kvol; ++k) {
+#pragma unroll
+        for (int s = 0; s < kSlices; ++s) {
+            compute(smem + (s % 2) * Cfg::kBuf, [&](int grp) __attribute__((always_inline)) {
+                if (grp < kLoads) {
+                    if (s + 2 < kSlices) issue_one(st[s % 2], grp, s + 2, cur);
+                    else issue_one(st[s % 2], grp, s + 2 - kSlices, nxt);
+                }
+                if (grp >= kGroups - kLoads)
+                    store_one(st[(s + 1) % 2], grp - (kGroups - kLoads), smem + ((s + 1) % 2) * Cfg::kBuf);
+            });
+            __syncthreads();
+        }
+        cur = nxt;
+        locate(k + 2, raw, nxt);
+        load_nbr(k + 3, raw);
+    }
+
+    // the accumulators are read below by ordinary instructions: the MFMAs were written as opaque instructions,
+    // so the wait states between the last of them and the first read are put in by hand (18 are required)
+    asm volatile("s_nop 15\n s_nop 15" ::: "memory");
+    // round once, stage the tile in LDS, write whole rows
+    unsigned char* out = smem;  // all staging reads are behind the last barrier
+#pragma unroll
+    for (int ni = 0; ni < kNI; ++ni)
+#pragma unroll
+        for (int mi = 0; mi < kMI; ++mi) {
+            const f32x4 v = acc[ni][mi];
+            u32x2 p;
+            p[0] = bf16_bits(v[0]) | (bf16_bits(v[1]) << 16);
+            p[1] = bf16_bits(v[2]) | (bf16_bits(v[3]) << 16);
+            *reinterpret_cast<u32x2*>(out + (wave * (Cfg::kTR / 4) + mi * 16 + n16) * Cfg::kOutPitch + (ni * 16 + 4 * g) * 2) = p;
+        }
+    __syncthreads();
+    constexpr int kRowPieces = COT * 2 / 16;
+    for (int idx = tid; idx < Cfg::kTR * kRowPieces; idx += 256) {
+        const int r = idx / kRowPieces, pc = idx % kRowPieces;
+        const int64_t row = row0 + r;
+        if (row >= a.n_rows) break;
+        *reinterpret_cast<u32x4*>(static_cast<unsigned char*>(a.g) + ((size_t)row * a.co_total + co0) * 2 + pc * 16) =
+            *reinterpret_cast<const u32x4*>(out + r * Cfg::kOutPitch + pc * 16);
+    }
+}
+
+template <int CC, int COT>
+int launch_dense(const DenseArgs& a, hipStream_t s) {
+    using Cfg = DenseCfg<CC, COT>;
+    auto kern = gather_dense_kernel<CC, COT>;
+    static bool attr_set = false;  // one-time opt-in to > 64 KB of dynamic LDS
+    if (!attr_set) {
+        SP_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)Cfg::kLds));
+        attr_set = true;
+    }
+    const int64_t ntiles = (a.n_rows + Cfg::kTR - 1) / Cfg::kTR;
+    const int nslice = a.co_total / COT;
+    const int64_t wgs = (ntiles + 7) / 8 * 8 * nslice;
+    hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(256), Cfg::kLds, s, a);
+    SP_HIP(hipGetLastError());
+    return SP_OK;
+}
+
+}  // namespace
+
+bool dense_shape_ok(int cc, int co, sp_dtype dt) { return dt == SP_BF16 && (cc == 128 || cc == 256) && co % 128 == 0; }
+
+// d_w: [kvol][co][cc] (contraction index fastest).  Buffers must be smaller than 2 GiB.
+int conv_gather_dense(const MapSide& side, int kvol, const void* d_f, const void* d_w, void* d_g, int cc, int co,
+                      hipStream_t s) {
+    DenseArgs a;
+    a.nbr = ptr<int32_t>(side.nbr);
+    a.f = d_f;
+    a.w = d_w;
+    a.g = d_g;
+    a.n_rows = side.n_rows;
+    a.kvol = kvol;
+    a.co_total = co;
+    a.flip = side.flip ? 1 : 0;
+    a.f_bytes = (uint32_t)((uint64_t)side.n_src * cc * 2);
+    a.w_bytes = (uint32_t)((uint64_t)kvol * co * cc * 2);
+    a.nbr_bytes = (uint32_t)((uint64_t)kvol * side.n_rows * 4);
+    return cc == 128 ? launch_dense<128, 128>(a, s) : launch_dense<256, 128>(a, s);
+}
+
+}  // namespace sp
