@@ -47,25 +47,36 @@ struct DenseArgs {
 template <int CC, int COT>
 struct DenseCfg {
     static constexpr int kTR = 256;                  // destination rows per workgroup
-    static constexpr int kKS = 64;                   // contraction channels per step
-    static constexpr int kPitch = kKS * 2 + 32;      // staged slice row: 128 bytes + 32 (measured: b128 fragment reads of 16 rows
-                                                     // run at the full 256 B/clk with this pad, at 160 B/clk with 16)
-    static constexpr int kXBytes = kTR * kPitch, kWBytes = COT * kPitch, kBuf = kXBytes + kWBytes;
+    static constexpr int kKS = 64;                   // contraction channels per step: one staged row is 128 bytes
+    static constexpr int kWaves = 4 * (COT / 128);   // 4 row quarters x COT/128 channel halves
+    static constexpr int kThreads = 64 * kWaves;
+    static constexpr int kXBytes = kTR * 128, kWBytes = COT * 128, kBuf = kXBytes + kWBytes;
     static constexpr int kSlices = CC / kKS;
-    static constexpr int kXLoads = kTR * 8 / 256;    // 16-byte pieces per thread and step: rows x 8 pieces / 256 threads
-    static constexpr int kWLoads = COT * 8 / 256;
+    static constexpr int kRP = kThreads / 8;         // rows loaded per pass: 8 lanes per 128-byte row
+    static constexpr int kXLoads = kTR / kRP;        // 16-byte pieces per thread and step
+    static constexpr int kWLoads = COT / kRP;
+    static constexpr int kWDepth = kWaves > 4 ? 1 : 2;  // register stages of the weight slices (the rows always have 2)
     static constexpr int kOutPitch = COT * 2 + 16;   // output staging row (bf16)
     static constexpr int kLds = 2 * kBuf > kTR * kOutPitch ? 2 * kBuf : kTR * kOutPitch;
-    static constexpr int kMI = kTR / 4 / 16;         // 16-row groups per wavefront (4 wavefronts split the rows)
-    static constexpr int kNI = COT / 16;             // 16-channel tiles per wavefront (each takes all channels)
-    static_assert(CC % kKS == 0, "contraction channels in whole slices");
+    static constexpr int kMI = 4;                    // 16-row groups per wavefront: 64 rows
+    static constexpr int kNI = 8;                    // 16-channel tiles per wavefront: 128 channels
+    static_assert(CC % (2 * kKS) == 0, "an even number of slices: the register stage of a step is s % 2");
+    static_assert(COT == 128 || COT == 256, "channel slice");
 };
 
+// Staged rows are 128 bytes with no pad; the 16-byte piece p of row r sits in slot p ^ ((r >> 1) & 7).  With
+// this swizzle the b128 fragment reads (16 rows x 4 k-groups per wavefront) run at the full LDS rate, like a
+// 32-byte pad would, and the buffers stay small enough for 8 wavefronts' worth of tile.
+__device__ __forceinline__ int swz(int row, int piece) { return (piece ^ ((row >> 1) & 7)) * 16; }
+
+template <int COT>
+constexpr int kDenseThreads = 64 * 4 * (COT / 128);
+
 template <int CC, int COT>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void gather_dense_kernel(DenseArgs a) {
+__global__ __launch_bounds__(kDenseThreads<COT>) void gather_dense_kernel(DenseArgs a) {
     using Cfg = DenseCfg<CC, COT>;
-    constexpr int kMI = Cfg::kMI, kNI = Cfg::kNI, kPitch = Cfg::kPitch, kSlices = Cfg::kSlices;
-    constexpr int kXLoads = Cfg::kXLoads, kWLoads = Cfg::kWLoads;
+    constexpr int kMI = Cfg::kMI, kNI = Cfg::kNI, kSlices = Cfg::kSlices, kRP = Cfg::kRP;
+    constexpr int kXLoads = Cfg::kXLoads, kWLoads = Cfg::kWLoads, kWDepth = Cfg::kWDepth;
     extern __shared__ __align__(16) unsigned char smem[];
 
     // Workgroups of one row tile (one per channel slice) get ids that differ by 8: same XCD (id % 8), launched
@@ -78,6 +89,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     if (row0 >= a.n_rows) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n16 = lane & 15, g = lane >> 4;
+    const int rq = wave & 3, ch = wave >> 2;  // this wavefront: tile rows rq*64 .. +63, slice channels ch*128 .. +127
 
     constexpr int kRsrcFlags = 0x00020000;
     constexpr uint32_t kOutside = 0x80000000u;  // buffers are smaller than 2 GiB: this offset reads as zeros
@@ -87,12 +99,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t*>(a.nbr), 0, (int)a.nbr_bytes, kRsrcFlags);
 
     // Loading: 8 adjacent lanes fetch the 8 pieces of one 128-byte slice row; thread t takes piece t % 8 of
-    // the tile rows t / 8 + 32 j and of the weight rows (destination channels) t / 8 + 32 j.
+    // the tile rows t / 8 + kRP j and of the weight rows (destination channels) t / 8 + kRP j.
     const int piece = tid & 7, lrow = tid >> 3;
-    const int st_off = lrow * kPitch + piece * 16;  // + 32 j rows
-    struct Stage {
-        u32x4 x[kXLoads], w[kWLoads];
-    };
+    const int st_off = lrow * 128 + swz(lrow, piece);  // + kRP j rows: kRP is a multiple of 16, the swizzle stays
     // Per offset and thread: the byte offsets of its kXLoads source rows (kOutside where the row has no
     // neighbour: such a load returns zeros) and of its first weight row.  A step's loads then differ from
     // these only by constants, which ride in the instruction's scalar offset.
@@ -102,7 +111,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     auto load_nbr = [&](int k, int (&raw)[kXLoads]) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < kXLoads; ++j) {
-            const int64_t row = row0 + lrow + 32 * j;
+            const int64_t row = row0 + lrow + kRP * j;
             const bool live = row < a.n_rows && k < a.kvol;
             // past the table the load returns 0, which would name row 0: such entries are masked in locate()
             raw[j] = (int)__builtin_amdgcn_raw_buffer_load_b32(
@@ -112,32 +121,26 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     auto locate = [&](int k, const int (&raw)[kXLoads], Where& wh) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < kXLoads; ++j) {
-            const bool live = row0 + lrow + 32 * j < a.n_rows && k < a.kvol && raw[j] >= 0;
+            const bool live = row0 + lrow + kRP * j < a.n_rows && k < a.kvol && raw[j] >= 0;
             wh.x[j] = live ? (uint32_t)raw[j] * (CC * 2) + piece * 16 : kOutside;
         }
         const int wk = a.flip ? a.kvol - 1 - k : k;
         wh.w = k < a.kvol ? ((uint32_t)wk * a.co_total + co0 + lrow) * (CC * 2) + piece * 16 : kOutside;
     };
-    // load / LDS store number i of a step: i < kXLoads gathered rows, then the weight rows
-    constexpr int kLoads = kXLoads + kWLoads;
-    auto issue_one = [&](Stage& st, int i, int s, const Where& wh) __attribute__((always_inline)) {
-        if (i < kXLoads) st.x[i] = __builtin_amdgcn_raw_buffer_load_b128(rF, wh.x[i], s * 128, 0);
-        else st.w[i - kXLoads] = __builtin_amdgcn_raw_buffer_load_b128(rW, wh.w, (i - kXLoads) * 32 * (CC * 2) + s * 128, 0);
+    auto load_x = [&](u32x4 (&x)[kXLoads], int j, int s, const Where& wh) __attribute__((always_inline)) {
+        x[j] = __builtin_amdgcn_raw_buffer_load_b128(rF, wh.x[j], s * 128, 0);
     };
-    auto store_one = [&](const Stage& st, int i, unsigned char* buf) __attribute__((always_inline)) {
-        if (i < kXLoads) *reinterpret_cast<u32x4*>(buf + st_off + i * 32 * kPitch) = st.x[i];
-        else *reinterpret_cast<u32x4*>(buf + Cfg::kXBytes + st_off + (i - kXLoads) * 32 * kPitch) = st.w[i - kXLoads];
+    auto load_w = [&](u32x4 (&w)[kWLoads], int j, int s, const Where& wh) __attribute__((always_inline)) {
+        w[j] = __builtin_amdgcn_raw_buffer_load_b128(rW, wh.w, j * kRP * (CC * 2) + s * 128, 0);
     };
-    auto issue = [&](Stage& st, int s, const Where& wh) __attribute__((always_inline)) {
-#pragma unroll
-        for (int i = 0; i < kLoads; ++i) issue_one(st, i, s, wh);
+    auto store_x = [&](const u32x4 (&x)[kXLoads], int j, unsigned char* buf) __attribute__((always_inline)) {
+        *reinterpret_cast<u32x4*>(buf + st_off + j * kRP * 128) = x[j];
     };
-    auto store = [&](const Stage& st, unsigned char* buf) __attribute__((always_inline)) {
-#pragma unroll
-        for (int i = 0; i < kLoads; ++i) store_one(st, i, buf);
+    auto store_w = [&](const u32x4 (&w)[kWLoads], int j, unsigned char* buf) __attribute__((always_inline)) {
+        *reinterpret_cast<u32x4*>(buf + Cfg::kXBytes + st_off + j * kRP * 128) = w[j];
     };
 
-    // acc[ni][mi][i]: destination channel co0 + ni*16 + 4*g + i, tile row wave*64 + mi*16 + n16
+    // acc[ni][mi][i]: destination channel co0 + ch*128 + ni*16 + 4*g + i, tile row rq*64 + mi*16 + n16
     // (weights are the MFMA A operand, the gathered rows the B operand: a lane ends up with 4 adjacent channels
     // of one row, which pack into one 8-byte store)
     f32x4 acc[kNI][kMI];
@@ -145,22 +148,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     for (int ni = 0; ni < kNI; ++ni)
 #pragma unroll
         for (int mi = 0; mi < kMI; ++mi) acc[ni][mi] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const int frag_x = (wave * (Cfg::kTR / 4) + n16) * kPitch + g * 16;   // + mi*16 rows, + 64 bytes for the second k-step
-    const int frag_w = Cfg::kXBytes + n16 * kPitch + g * 16;              // + ni*16 rows
+    // fragment of (row n16 of a 16-row group, k-group g) for the two k-steps; + 16-row groups as constants
+    const int frag_x[2] = {(rq * 64 + n16) * 128 + swz(n16, g), (rq * 64 + n16) * 128 + swz(n16, 4 + g)};
+    const int frag_w[2] = {Cfg::kXBytes + (ch * 128 + n16) * 128 + swz(n16, g),
+                           Cfg::kXBytes + (ch * 128 + n16) * 128 + swz(n16, 4 + g)};
     // One step = 2 k-steps x kNI channel tiles = 2*kNI groups of kMI MFMAs.  A wavefront issues in order and
     // an MFMA runs for 16 cycles once issued, so everything else the step has to do is dealt out over the
     // groups and issued in the shadow of their MFMAs: the LDS fragment reads (two groups ahead of their
-    // use: 3 rotating weight fragments; the second k-step's row fragments during the first k-step), one
-    // global load of step t+2 per group, one LDS store of stage t+1 per group.
+    // use: 3 rotating weight fragments; the second k-step's row fragments during the first k-step), the
+    // global loads of later steps and the LDS stores of the next step's stage, one of each per group.
     constexpr int kGroups = 2 * kNI;
-    static_assert(kLoads <= kGroups, "one load and one store per group");
+    static_assert(kXLoads + kWLoads <= kGroups, "one load and one store per group");
     auto compute = [&](const unsigned char* buf, auto&& extra) __attribute__((always_inline)) {
         bf16x8 xf[2][kMI], wf[3];
         auto read_w = [&](int grp) __attribute__((always_inline)) {
-            return *reinterpret_cast<const bf16x8*>(buf + frag_w + (grp % kNI) * 16 * kPitch + (grp / kNI) * 64);
+            return *reinterpret_cast<const bf16x8*>(buf + frag_w[grp / kNI] + (grp % kNI) * 16 * 128);
         };
         auto read_x = [&](int ks, int mi) __attribute__((always_inline)) {
-            return *reinterpret_cast<const bf16x8*>(buf + frag_x + mi * 16 * kPitch + ks * 64);
+            return *reinterpret_cast<const bf16x8*>(buf + frag_x[ks] + mi * 16 * 128);
         };
 #pragma unroll
         for (int mi = 0; mi < kMI; ++mi) xf[0][mi] = read_x(0, mi);
@@ -173,38 +178,55 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             extra(grp);
             __builtin_amdgcn_sched_barrier(0);  // keeps this group's other work ahead of the MFMAs that hide it
 #pragma unroll
-            for (int mi = 0; mi < kMI; ++mi)
-                mfma_acc(acc[grp % kNI][mi], wf[grp % 3], xf[grp / kNI][mi]);
+            for (int mi = 0; mi < kMI; ++mi) mfma_acc(acc[grp % kNI][mi], wf[grp % 3], xf[grp / kNI][mi]);
         }
     };
 
-    // Steps = (offset, slice), step t = k * kSlices + s.  While step t is multiplied out of LDS buffer t % 2,
-    // the loads of steps t+1 and t+2 are in flight (two register stages: the gathers mostly miss L2, and one
-    // step of arithmetic is shorter than their latency); stage t+1 is then stored to the other buffer.  The
-    // neighbour entries of offset k+1 are requested at the start of offset k.
-    static_assert(kSlices % 2 == 0, "the register stage of a step is s % 2");
+    // Steps = (offset, slice), step t = k * kSlices + s, computed out of LDS buffer t % 2.  The gathered rows
+    // have two register stages (they mostly miss L2, and one step of arithmetic is shorter than that latency):
+    // during step t the rows of step t+2 are requested and those of step t+1 are stored to the other buffer.
+    // The weight slices (L2 hits) have kWDepth stages.  The neighbour entries are requested two offsets ahead.
     Where cur, nxt;     // offsets k and k + 1
     int raw[kXLoads];   // neighbour entries of offset k + 2, in flight
-    Stage st[2];
+    u32x4 sx[2][kXLoads], sw[kWDepth][kWLoads];
     load_nbr(0, raw);
     locate(0, raw, cur);
     load_nbr(1, raw);
     locate(1, raw, nxt);
     load_nbr(2, raw);
-    issue(st[0], 0, cur);
-    issue(st[1], 1, cur);
-    store(st[0], smem);
+#pragma unroll
+    for (int j = 0; j < kXLoads; ++j) load_x(sx[0], j, 0, cur);
+#pragma unroll
+    for (int j = 0; j < kWLoads; ++j) load_w(sw[0], j, 0, cur);
+#pragma unroll
+    for (int j = 0; j < kXLoads; ++j) load_x(sx[1], j, 1, cur);
+    if constexpr (kWDepth == 2) {
+#pragma unroll
+        for (int j = 0; j < kWLoads; ++j) load_w(sw[1], j, 1, cur);
+    }
+#pragma unroll
+    for (int j = 0; j < kXLoads; ++j) store_x(sx[0], j, smem);
+#pragma unroll
+    for (int j = 0; j < kWLoads; ++j) store_w(sw[0], j, smem);
     __syncthreads();
     for (int k = 0; k < a.kvol; ++k) {
 #pragma unroll
         for (int s = 0; s < kSlices; ++s) {
             compute(smem + (s % 2) * Cfg::kBuf, [&](int grp) __attribute__((always_inline)) {
-                if (grp < kLoads) {
-                    if (s + 2 < kSlices) issue_one(st[s % 2], grp, s + 2, cur);
-                    else issue_one(st[s % 2], grp, s + 2 - kSlices, nxt);
+                // requests: weight slice of step t + kWDepth, then rows of step t + 2
+                if (grp < kWLoads) {
+                    constexpr int d = kWDepth;
+                    if (s + d < kSlices) load_w(sw[(s + d) % kWDepth], grp, s + d, cur);
+                    else load_w(sw[(s + d) % kWDepth], grp, s + d - kSlices, nxt);
+                } else if (grp < kWLoads + kXLoads) {
+                    if (s + 2 < kSlices) load_x(sx[s % 2], grp - kWLoads, s + 2, cur);
+                    else load_x(sx[s % 2], grp - kWLoads, s + 2 - kSlices, nxt);
                 }
-                if (grp >= kGroups - kLoads)
-                    store_one(st[(s + 1) % 2], grp - (kGroups - kLoads), smem + ((s + 1) % 2) * Cfg::kBuf);
+                // stores of step t + 1's stage: rows first (requested a step ago), weights last
+                const int st = grp - (kGroups - kXLoads - kWLoads);
+                unsigned char* other = smem + ((s + 1) % 2) * Cfg::kBuf;
+                if (st >= 0 && st < kXLoads) store_x(sx[(s + 1) % 2], st, other);
+                else if (st >= kXLoads) store_w(sw[(s + 1) % kWDepth], st - kXLoads, other);
             });
             __syncthreads();
         }
@@ -226,11 +248,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             u32x2 p;
             p[0] = bf16_bits(v[0]) | (bf16_bits(v[1]) << 16);
             p[1] = bf16_bits(v[2]) | (bf16_bits(v[3]) << 16);
-            *reinterpret_cast<u32x2*>(out + (wave * (Cfg::kTR / 4) + mi * 16 + n16) * Cfg::kOutPitch + (ni * 16 + 4 * g) * 2) = p;
+            *reinterpret_cast<u32x2*>(out + (rq * 64 + mi * 16 + n16) * Cfg::kOutPitch + (ch * 128 + ni * 16 + 4 * g) * 2) = p;
         }
     __syncthreads();
     constexpr int kRowPieces = COT * 2 / 16;
-    for (int idx = tid; idx < Cfg::kTR * kRowPieces; idx += 256) {
+    for (int idx = tid; idx < Cfg::kTR * kRowPieces; idx += Cfg::kThreads) {
         const int r = idx / kRowPieces, pc = idx % kRowPieces;
         const int64_t row = row0 + r;
         if (row >= a.n_rows) break;
@@ -252,7 +274,7 @@ int launch_dense(const DenseArgs& a, hipStream_t s) {
     const int64_t ntiles = (a.n_rows + Cfg::kTR - 1) / Cfg::kTR;
     const int nslice = a.co_total / COT;
     const int64_t wgs = (ntiles + 7) / 8 * 8 * nslice;
-    hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(256), Cfg::kLds, s, a);
+    hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(Cfg::kThreads), Cfg::kLds, s, a);
     SP_HIP(hipGetLastError());
     return SP_OK;
 }
@@ -276,7 +298,9 @@ int conv_gather_dense(const MapSide& side, int kvol, const void* d_f, const void
     a.f_bytes = (uint32_t)((uint64_t)side.n_src * cc * 2);
     a.w_bytes = (uint32_t)((uint64_t)kvol * co * cc * 2);
     a.nbr_bytes = (uint32_t)((uint64_t)kvol * side.n_rows * 4);
-    return cc == 128 ? launch_dense<128, 128>(a, s) : launch_dense<256, 128>(a, s);
+    const bool wide = co % 256 == 0 && getenv("SP_DENSE_COT128") == nullptr;
+    if (cc == 128) return wide ? launch_dense<128, 256>(a, s) : launch_dense<128, 128>(a, s);
+    return wide ? launch_dense<256, 256>(a, s) : launch_dense<256, 128>(a, s);
 }
 
 }  // namespace sp

@@ -229,6 +229,22 @@ def test_conv_matches_oracle(sp, case):
     conv_case(sp, raw, ts, K, stride, dil, cin, cout, bf16, seed=1000 + len(name), transposed=transposed)
 
 
+def full_cubes(side, batches):
+    """Every voxel of a side^3 cube per cloud, rows shuffled: interior rows have all 27 neighbours, so the map is
+    dense enough for the row-stationary wide-layer kernel to be chosen."""
+    g = np.arange(side, dtype=np.int32)
+    x, y, z = np.meshgrid(g, g, g, indexing="ij")
+    one = np.stack([x.ravel(), y.ravel(), z.ravel()], 1)
+    rows = np.concatenate([np.concatenate([np.full((len(one), 1), b, np.int32), one], 1) for b in range(batches)])
+    return rows[np.random.default_rng(11).permutation(len(rows))]
+
+
+@pytest.mark.parametrize("cin,cout,side,batches", [(128, 128, 9, 2), (256, 256, 8, 3), (128, 256, 7, 1), (256, 128, 10, 1)])
+def test_wide_bf16_on_dense_maps(sp, cin, cout, side, batches):
+    # rows are not a multiple of the 256-row tile: ragged last tile; forward and both gradients
+    conv_case(sp, full_cubes(side, batches), 1, 3, 1, 1, cin, cout, True, seed=77 + cin + side)
+
+
 def test_identity_weights_reproduce_input_bit_exactly(sp):
     raw = spgen.coords_config(1, 0.2)
     c = sp.sp_coords_build(dev(raw), 1)
