@@ -71,12 +71,142 @@ def cpu_baseline(raw, K, stride, dil, cin, cout, bf16, seed):
             "kmap_mvoxels_per_s": len(c_in) / t_map / 1e6}
 
 
+STACK_CHANNELS = [32, 32, 64, 64, 128, 128, 256, 256, 256]  # input features, then the 8 convs' outputs
+STACK_STRIDES = [1, 1, 1, 2, 1, 2, 1, 1]                     # two stride-2 downsamples
+STACK_CLASSES = 40
+
+
+def run_stack(args, sp, spgen, torch):
+    """Config 3: one training step (forward, loss, backward) of the 8-conv sparse ResNet-style stack on a
+    micro-batch of 4 clouds, bf16 features and weights with fp32 accumulation.  A step is: coordinate hashing,
+    the 5 kernel maps of the hierarchy, 8 x (conv, BN+ReLU), per-cloud average pool, linear, softmax
+    cross-entropy, and every layer's backward (BN, data gradient, weight gradient)."""
+    cfg = 3
+    raw_np = spgen.coords_config(cfg)
+    raw = torch.from_numpy(raw_np).cuda()
+    bf = torch.bfloat16
+    nb = int(raw_np[:, 0].max()) + 1
+    rng = np.random.default_rng(spgen.seed_for(cfg, 0, stream=2))
+    W = [torch.from_numpy(spgen.weights(spgen.seed_for(cfg, l, stream=3), 27, STACK_CHANNELS[l], STACK_CHANNELS[l + 1],
+                                        True)).cuda().to(bf) for l in range(8)]
+    gamma = [torch.ones(c, device="cuda") for c in STACK_CHANNELS[1:]]
+    beta = [torch.zeros(c, device="cuda") for c in STACK_CHANNELS[1:]]
+    w_fc = torch.from_numpy((rng.standard_normal((STACK_CLASSES, 256)) / 16).astype(np.float32)).cuda()
+    b_fc = torch.zeros(STACK_CLASSES, device="cuda")
+    labels = torch.from_numpy(rng.integers(0, STACK_CLASSES, nb).astype(np.int32)).cuda()
+
+    info = {}
+
+    def step(events=None):
+        def mark(i):
+            if events is not None:
+                events[i].record()
+        mark(0)
+        c0 = sp.sp_coords_build(raw, 1)
+        maps, by_key, cur, level, handles = [], {}, c0, 0, [c0]
+        for st in STACK_STRIDES:                      # layers on one level with one stride share their map
+            if (level, st) not in by_key:
+                km, co = sp.sp_kmap_build(cur, 3, st, 1)
+                by_key[(level, st)] = (km, co)
+                handles += [km, co]
+            km, co = by_key[(level, st)]
+            maps.append(km)
+            if st > 1:
+                cur, level = co, level + 1
+        mark(1)
+        if "x0" not in info:                          # input features: fixed after the first step (same coordinates)
+            info["x0"] = torch.from_numpy(spgen.features(spgen.seed_for(cfg, 0, stream=1), c0.n, 32, True)).cuda().to(bf)
+            info["pairs"] = [m.total for m in maps]
+            info["rows"] = [c0.n] + [m.n_out for m in maps]
+        x = info["x0"]
+        saved = []
+        for l in range(8):
+            z = sp.sp_conv_fwd(maps[l], x, W[l])
+            y, mean, rstd = sp.sp_bn_relu_fwd(z, gamma[l], beta[l])
+            saved.append((x, z, y, mean, rstd))
+            x = y
+        coords_last = cur.coords()
+        pooled, counts = sp.sp_pool_avg_fwd(coords_last, x, nb)
+        logits = sp.sp_linear_fwd(pooled, w_fc, b_fc)
+        loss, dlogits = sp.sp_softmax_ce(logits, labels)
+        mark(2)
+        dpooled, dw_fc, db_fc = sp.sp_linear_bwd(pooled, w_fc, dlogits)
+        g = sp.sp_pool_avg_bwd(coords_last, dpooled, counts, x.shape[0], bf)
+        for l in reversed(range(8)):
+            xin, z, y, mean, rstd = saved[l]
+            dz, dgamma, dbeta = sp.sp_bn_relu_bwd(z, y, g, gamma[l], mean, rstd)
+            dw = sp.sp_conv_bwd_weight(maps[l], xin, dz)
+            g = sp.sp_conv_bwd_data(maps[l], dz, W[l])
+        mark(3)
+        info["loss"] = loss
+        for h in handles:
+            h.close()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(ev[i])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    names = ["coords_and_maps", "forward", "backward"]
+    stage_ms = {n: float(np.mean([ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(args.steps)]))
+                for j, n in enumerate(names)}
+    flops_layer = [2.0 * info["pairs"][l] * STACK_CHANNELS[l] * STACK_CHANNELS[l + 1] for l in range(8)]
+    flops_step = 3.0 * sum(flops_layer)
+
+    # dominant kernel: the forward convolution of the widest layer (256 -> 256 on the twice-downsampled level)
+    c0 = sp.sp_coords_build(raw, 1)
+    cur, hs = c0, [c0]
+    for _ in range(2):
+        km, co = sp.sp_kmap_build(cur, 3, 2, 1)
+        hs += [km, co]
+        cur = co
+    km, co = sp.sp_kmap_build(cur, 3, 1, 1)
+    hs += [km, co]
+    x = torch.randn(km.n_in, 256, device="cuda").to(bf)
+    y = torch.empty(km.n_out, 256, device="cuda", dtype=bf)
+    for _ in range(3):
+        sp.sp_conv_fwd(km, x, W[7], out=y)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 20
+    e0.record()
+    for _ in range(reps):
+        sp.sp_conv_fwd(km, x, W[7], out=y)
+    e1.record()
+    torch.cuda.synchronize()
+    conv_s = e0.elapsed_time(e1) / reps * 1e-3
+    fl = 2.0 * km.total * 256 * 256
+    for h in hs:
+        h.close()
+    out = {
+        "metric": "sparse-conv effective TFLOP/s (active MACs) + kernel-map Mvoxels/s, 1 GPU",
+        "value": flops_step / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "clouds": nb, "n_raw": int(raw.shape[0]), "rows_per_level": info["rows"],
+                   "pairs_per_layer": info["pairs"], "channels": STACK_CHANNELS, "strides": STACK_STRIDES,
+                   "step": "coords + 5 kernel maps + 8x(conv, BN+ReLU) + pool + linear + CE + full backward"},
+        "stages": {n: {"ms": round(stage_ms[n], 4)} for n in names},
+        "conv_gflop_per_step": round(flops_step / 1e9, 1),
+        "loss": float(info["loss"].item()),
+        "roofline": {"bound": "mfma", "kernel": "gather_dense_kernel<256,256> (sp_conv_fwd, layer 7/8)",
+                     "achieved": fl / conv_s / 1e12, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
+                     "frac": fl / conv_s / 1e12 / PEAK_BF16_MFMA_TFLOPS, "traffic": None,
+                     "launch_us": round(conv_s * 1e6, 2), "flops_per_launch": fl},
+    }
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg1_k3s1_c32x64_f32", choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default="cfg1_k3s1_c32x64_f32", choices=sorted(WORKLOADS) + ["cfg3_stack_bf16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain device copy of known size (256 MiB read + 256 MiB written per launch): "
@@ -104,6 +234,9 @@ def main():
                           "bytes_written_per_launch": src.numel() * 4, "launches": 10}))
         return
 
+    if args.workload == "cfg3_stack_bf16":
+        run_stack(args, sp, spgen, torch)
+        return
     cfg, K, stride, dil, cin, cout, bf16 = WORKLOADS[args.workload]
     seed = spgen.seed_for(cfg, 0, stream=1)
     raw_np = spgen.coords_config(cfg)

@@ -298,7 +298,7 @@ int conv_gather_dense(const MapSide& side, int kvol, const void* d_f, const void
     a.f_bytes = (uint32_t)((uint64_t)side.n_src * cc * 2);
     a.w_bytes = (uint32_t)((uint64_t)kvol * co * cc * 2);
     a.nbr_bytes = (uint32_t)((uint64_t)kvol * side.n_rows * 4);
-    const bool wide = co % 256 == 0 && getenv("SP_DENSE_COT128") == nullptr;
+    const bool wide = co % 256 == 0;
     if (cc == 128) return wide ? launch_dense<128, 256>(a, s) : launch_dense<128, 128>(a, s);
     return wide ? launch_dense<256, 256>(a, s) : launch_dense<256, 128>(a, s);
 }
