@@ -494,11 +494,11 @@ int launch_staged(const sp_kmap* m, const void* x, const void* dy, int cin, int 
     M = M < 1 ? 1 : (M > 128 ? 128 : M);  // the reduction keeps a strip table of 1024 entries in LDS
     pa.S8 = (int)(8 * M);
     // Chunks: when everything fits the GPU at once, exactly as many workgroups as are resident together
-    // (one round, equal chunks); otherwise about 2048 links each.
+    // (one round, equal chunks); otherwise about 2048 links each (more for wide layers).
     const int64_t strip_links = (m->total + pa.S8 - 1) / pa.S8 + kvol;  // upper bound of a strip's sequence
     const int64_t resident = (int64_t)256 * occ / pa.tiles;
     int64_t nc = resident / pa.S8;
-    const int64_t links = 2048;
+    const int64_t links = std::max<int64_t>(2048, per / 16);  // a chunk's partial block costs per * 8 bytes of traffic
     if (nc < 1 || strip_links > nc * links) nc = (strip_links + links - 1) / links;
     int64_t C = (strip_links + nc - 1) / nc;
     C = (C + Cfg::kS - 1) / Cfg::kS * Cfg::kS;
@@ -554,8 +554,13 @@ int wgrad_typed(const sp_kmap* m, const void* x, const void* dy, float* dw, int 
     int cob = channel_block(cout), cib = channel_block(cin);
     if (cob == 128 && cib < 64) cob = 64;  // 128-wide tiles only in the combinations instantiated below
     if (cib == 128 && cob < 64) cib = 64;
+    // register stages of gathered rows: two for bf16 (a step's arithmetic is short next to the gather latency)
+    constexpr int kD = sizeof(T) == 2 ? 2 : 1;
 #define SP_STAGED(COB, CIB, WCO, WCI, WK) \
-    if (cob == COB && cib == CIB) return launch_staged<T, COB, CIB, WCO, WCI, WK, 1>(m, x, dy, cin, cout, dw, s)
+    if (cob == COB && cib == CIB) return launch_staged<T, COB, CIB, WCO, WCI, WK, kD>(m, x, dy, cin, cout, dw, s)
+    if constexpr (sizeof(T) == 2) {  // bf16: the whole 256 x 256 matrix in one workgroup, every row gathered once
+        if (cout % 256 == 0 && cin % 256 == 0) return launch_staged<T, 256, 256, 2, 4, 1, 1>(m, x, dy, cin, cout, dw, s);
+    }
     SP_STAGED(128, 128, 2, 2, 1);
     SP_STAGED(128, 64, 2, 1, 2);
     SP_STAGED(64, 128, 1, 2, 2);
