@@ -76,22 +76,22 @@ __global__ __launch_bounds__(kThreads) void column_sums_kernel(const T* __restri
     }
 }
 
-// Adds the block partials in double, in a fixed order: 8 interleaved running sums per channel (block b goes
-// to sum b % 8), then added 0..7.  Block = 32 channels x 8 slices.
+// Adds the block partials in double, in a fixed order: 32 interleaved running sums per channel (block b goes
+// to sum b % 32), then added 0..31.  Block = 32 channels x 32 slices.
 // MODE 0: mean / rstd (the partials are sums of deviations from `shift[ch]`).  MODE 1: dbeta (sum 0) /
 // dgamma (sum 1).
 template <int MODE, typename T>
-__global__ __launch_bounds__(kThreads) void column_sums_final_kernel(const float* __restrict__ partial, int64_t nblk,
-                                                                     int64_t n, int c, float eps,
-                                                                     const T* __restrict__ shift,
-                                                                     float* __restrict__ out0,
-                                                                     float* __restrict__ out1) {
-    __shared__ double red[2][8][32];
+__global__ __launch_bounds__(1024) void column_sums_final_kernel(const float* __restrict__ partial, int64_t nblk,
+                                                                 int64_t n, int c, float eps,
+                                                                 const T* __restrict__ shift,
+                                                                 float* __restrict__ out0,
+                                                                 float* __restrict__ out1) {
+    __shared__ double red[2][32][32];
     const int cx = threadIdx.x & 31, slice = threadIdx.x >> 5;
     const int ch = blockIdx.x * 32 + cx;
     double s0 = 0.0, s1 = 0.0;
     if (ch < c)
-        for (int64_t b = slice; b < nblk; b += 8) {
+        for (int64_t b = slice; b < nblk; b += 32) {
             s0 += (double)partial[((size_t)b * 2 + 0) * c + ch];
             s1 += (double)partial[((size_t)b * 2 + 1) * c + ch];
         }
@@ -101,7 +101,7 @@ __global__ __launch_bounds__(kThreads) void column_sums_final_kernel(const float
     if (slice != 0 || ch >= c) return;
     s0 = red[0][0][cx];
     s1 = red[1][0][cx];
-    for (int j = 1; j < 8; ++j) {
+    for (int j = 1; j < 32; ++j) {
         s0 += red[0][j][cx];
         s1 += red[1][j][cx];
     }
@@ -379,18 +379,94 @@ __global__ __launch_bounds__(kThreads) void pool_partial_kernel(const int4* __re
     }
 }
 
+// 16-byte-vector version: thread = (row lane, 16-byte channel group); a thread keeps the running sums of the
+// cloud its rows are currently in and adds them to its own LDS cells [row lane][cloud][channels] when the
+// cloud changes (rows of one cloud are usually contiguous, so that is rare).  Row lanes are added in lane
+// order.  LDS: lanes * nb * c floats, the host checks that it fits.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void pool_partial_vec_kernel(const int4* __restrict__ coords,
+                                                                    const T* __restrict__ x, int64_t n, int c, int nb,
+                                                                    float* __restrict__ partial,
+                                                                    int32_t* __restrict__ cnt_partial) {
+    constexpr int kN = Vec<T>::kN;
+    extern __shared__ float s_acc[];  // [lanes][nb][c] floats, then [lanes][nb] ints
+    const int tpr = c / kN, lanes = kThreads / tpr;
+    const int cg = threadIdx.x % tpr, rl = threadIdx.x / tpr;
+    int* s_cnt = reinterpret_cast<int*>(s_acc + (size_t)lanes * nb * c);
+    for (int i = threadIdx.x; i < lanes * nb * c; i += kThreads) s_acc[i] = 0.f;
+    for (int i = threadIdx.x; i < lanes * nb; i += kThreads) s_cnt[i] = 0;
+    __syncthreads();
+    const int64_t row_beg = (int64_t)blockIdx.x * kSlabRows;
+    const int64_t row_end = row_beg + kSlabRows < n ? row_beg + kSlabRows : n;
+    if (rl < lanes) {
+        float acc[kN];
+#pragma unroll
+        for (int i = 0; i < kN; ++i) acc[i] = 0.f;
+        int cur = -1, cnt = 0;
+        auto flush = [&]() {
+            if (cur >= 0) {
+                float* cell = s_acc + ((size_t)rl * nb + cur) * c + cg * kN;
+#pragma unroll
+                for (int i = 0; i < kN; ++i) {
+                    cell[i] += acc[i];
+                    acc[i] = 0.f;
+                }
+                if (cg == 0) s_cnt[rl * nb + cur] += cnt;
+            }
+            cnt = 0;
+        };
+        for (int64_t r = row_beg + rl; r < row_end; r += lanes) {
+            const int b = coords[r].x;
+            const Vec<T> xv = load_vec(x, (size_t)r * c + (size_t)cg * kN);
+            if ((unsigned)b >= (unsigned)nb) continue;
+            if (b != cur) {
+                flush();
+                cur = b;
+            }
+#pragma unroll
+            for (int i = 0; i < kN; ++i) acc[i] += xv.v[i];
+            ++cnt;
+        }
+        flush();
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < nb * c; i += kThreads) {
+        float t = 0.f;
+        for (int j = 0; j < lanes; ++j) t += s_acc[(size_t)j * nb * c + i];
+        partial[(size_t)blockIdx.x * nb * c + i] = t;
+    }
+    for (int b = threadIdx.x; b < nb; b += kThreads) {
+        int t = 0;
+        for (int j = 0; j < lanes; ++j) t += s_cnt[j * nb + b];
+        cnt_partial[(size_t)blockIdx.x * nb + b] = t;
+    }
+}
+
 __global__ __launch_bounds__(kThreads) void pool_final_kernel(const float* __restrict__ partial,
                                                               const int32_t* __restrict__ cnt_partial, int64_t nblk,
                                                               int c, int nb, float* __restrict__ out,
                                                               float* __restrict__ counts) {
-    const int i = blockIdx.x * kThreads + threadIdx.x;
-    if (i >= nb * c) return;
-    const int b = i / c;
+    // block = 32 (cloud, channel) elements x 8 slices of the row blocks; slices are added in order
+    __shared__ double red[8][32];
+    __shared__ long long redc[8][32];
+    const int ex = threadIdx.x & 31, slice = threadIdx.x >> 5;
+    const int i = blockIdx.x * 32 + ex;
+    const bool live = i < nb * c;
+    const int b = live ? i / c : 0;
     double s = 0.0;
-    int64_t cnt = 0;
-    for (int64_t k = 0; k < nblk; ++k) {
-        s += (double)partial[(size_t)k * nb * c + i];
-        cnt += cnt_partial[(size_t)k * nb + b];
+    long long cnt = 0;
+    if (live)
+        for (int64_t k = slice; k < nblk; k += 8) {
+            s += (double)partial[(size_t)k * nb * c + i];
+            cnt += cnt_partial[(size_t)k * nb + b];
+        }
+    red[slice][ex] = s;
+    redc[slice][ex] = cnt;
+    __syncthreads();
+    if (slice != 0 || !live) return;
+    for (int j = 1; j < 8; ++j) {
+        s += red[j][ex];
+        cnt += redc[j][ex];
     }
     out[i] = cnt > 0 ? (float)(s / (double)cnt) : 0.f;
     if (i % c == 0) counts[b] = (float)cnt;
@@ -419,9 +495,17 @@ __global__ __launch_bounds__(kThreads) void linear_fwd_kernel(const float* __res
     const int i = blockIdx.x * kThreads + threadIdx.x;
     if (i >= nb * m) return;
     const int b = i / m, j = i % m;
-    float s = bias ? bias[j] : 0.f;
-    for (int k = 0; k < c; ++k) s = fmaf(in[(size_t)b * c + k], w[(size_t)j * c + k], s);
-    out[i] = s;
+    // 4 interleaved running sums (k % 4), added 0+1+2+3: four independent load/fma chains instead of one
+    float s[4] = {0.f, 0.f, 0.f, 0.f};
+    const float* x = in + (size_t)b * c;
+    const float* wr = w + (size_t)j * c;
+    int k = 0;
+    for (; k + 4 <= c; k += 4) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) s[u] = fmaf(x[k + u], wr[k + u], s[u]);
+    }
+    for (; k < c; ++k) s[k & 3] = fmaf(x[k], wr[k], s[k & 3]);
+    out[i] = (bias ? bias[j] : 0.f) + (((s[0] + s[1]) + s[2]) + s[3]);
 }
 
 // one launch for the three gradients: [0, nb*c) din, [nb*c, nb*c + m*c) dw, then m entries of dbias
@@ -518,7 +602,7 @@ int bn_fwd_typed(const void* x, int64_t n, int c, const float* gamma, const floa
                                (const float*)nullptr, (const float*)nullptr, 0, ptr<float>(partial));
         }
     }
-    hipLaunchKernelGGL((column_sums_final_kernel<0, T>), dim3((c + 31) / 32), dim3(kThreads), 0, s, ptr<float>(partial),
+    hipLaunchKernelGGL((column_sums_final_kernel<0, T>), dim3((c + 31) / 32), dim3(1024), 0, s, ptr<float>(partial),
                        nblk, n, c, eps, static_cast<const T*>(x), mean, rstd);
     if (n > 0) {
         if (vec)
@@ -553,7 +637,7 @@ int bn_bwd_typed(const void* x, const void* y, const void* dy, int64_t n, int c,
                                rstd, relu, ptr<float>(partial));
         }
     }
-    hipLaunchKernelGGL((column_sums_final_kernel<1, T>), dim3((c + 31) / 32), dim3(kThreads), 0, s, ptr<float>(partial),
+    hipLaunchKernelGGL((column_sums_final_kernel<1, T>), dim3((c + 31) / 32), dim3(1024), 0, s, ptr<float>(partial),
                        nblk, n, c, 0.f, (const T*)nullptr, dbeta, dgamma);
     if (n > 0) {
         if (vec)
@@ -580,12 +664,21 @@ int pool_fwd_typed(const int32_t* coords, const void* x, int64_t n, int c, int n
     Buf partial = dev_alloc((size_t)(nblk ? nblk : 1) * nb * c * 4);
     Buf cnt = dev_alloc((size_t)(nblk ? nblk : 1) * nb * 4);
     if (!partial || !cnt) return SP_ERR_ALLOC;
-    if (nblk > 0)
-        hipLaunchKernelGGL(pool_partial_kernel<T>, dim3((unsigned)nblk), dim3(kThreads), lds, s,
-                           reinterpret_cast<const int4*>(coords), static_cast<const T*>(x), n, c, nb,
-                           ptr<float>(partial), ptr<int32_t>(cnt));
-    hipLaunchKernelGGL(pool_final_kernel, dim3((nb * c + kThreads - 1) / kThreads), dim3(kThreads), 0, s,
-                       ptr<float>(partial), ptr<int32_t>(cnt), nblk, c, nb, out, counts);
+    constexpr int kN = 16 / (int)sizeof(T);
+    const int vlanes = c % kN == 0 && c / kN <= kThreads ? kThreads / (c / kN) : 0;
+    const size_t vlds = (size_t)vlanes * nb * c * 4 + (size_t)vlanes * nb * 4;
+    if (nblk > 0) {
+        if (vlanes > 0 && vlds <= 64 * 1024 && ((uintptr_t)x & 15) == 0)
+            hipLaunchKernelGGL(pool_partial_vec_kernel<T>, dim3((unsigned)nblk), dim3(kThreads), vlds, s,
+                               reinterpret_cast<const int4*>(coords), static_cast<const T*>(x), n, c, nb,
+                               ptr<float>(partial), ptr<int32_t>(cnt));
+        else
+            hipLaunchKernelGGL(pool_partial_kernel<T>, dim3((unsigned)nblk), dim3(kThreads), lds, s,
+                               reinterpret_cast<const int4*>(coords), static_cast<const T*>(x), n, c, nb,
+                               ptr<float>(partial), ptr<int32_t>(cnt));
+    }
+    hipLaunchKernelGGL(pool_final_kernel, dim3((nb * c + 31) / 32), dim3(kThreads), 0, s, ptr<float>(partial),
+                       ptr<int32_t>(cnt), nblk, c, nb, out, counts);
     SP_HIP(hipGetLastError());
     return SP_OK;
 }
