@@ -31,7 +31,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM-side bytes per launch of the forward gather kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each
 # scaled by what the counter reads for a plain copy of known size (see the files under profiles/).
 MEASURED_TRAFFIC_BYTES = {
-    "cfg1_k3s1_c32x64_f32": 92.2e6,   # profiles/step_cfg1_k3s1_c32x64_f32.txt: 66.4 MB read + 25.8 MB written
+    "cfg1_k3s1_c32x64_f32": 92.6e6,   # profiles/step_cfg1_k3s1_c32x64_f32.txt: 66.8 MB read + 25.8 MB written
 }
 
 WORKLOADS = {

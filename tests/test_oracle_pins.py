@@ -401,3 +401,32 @@ def test_glue_layers_match_torch_library_routines():
     y2t.backward(torch.tensor(g))
     assert np.allclose(y2, y2t.detach().numpy(), atol=1e-12)
     assert np.allclose(glue.bn_relu_bwd(x, y2, g, gamma, mean2, rstd2, False)[0], x2.grad.numpy(), atol=1e-11)
+
+
+def test_glue_closed_forms():
+    from oracle import glue
+    # a single row has variance 0: y = beta, mean = the row, rstd = eps^-1/2
+    x = np.array([[1.5, -2.0]])
+    y, mean, rstd = glue.bn_relu_fwd(x, np.array([2.0, 3.0]), np.array([0.5, -1.0]), 1e-5, False)
+    assert np.allclose(mean, x[0]) and np.allclose(rstd, 1e-5 ** -0.5) and np.allclose(y, [[0.5, -1.0]])
+    # two rows +-a: xhat = +-a/sqrt(a^2+eps); ReLU keeps the positive one
+    a = 3.0
+    y, mean, rstd = glue.bn_relu_fwd(np.array([[a], [-a]]), np.array([1.0]), np.array([0.0]), 1e-5, True)
+    assert np.allclose(mean, 0.0) and np.allclose(y[:, 0], [a / np.sqrt(a * a + 1e-5), 0.0])
+    # pooling a per-cloud constant returns it; counts are the cloud sizes; the backward spreads g / count
+    bidx = np.array([0, 0, 0, 2, 2])
+    xs = np.where(bidx[:, None] == 0, 4.0, -1.0) * np.ones((5, 3))
+    pooled, counts = glue.pool_avg_fwd(bidx, xs, 3)
+    assert np.array_equal(counts, [3, 0, 2])
+    assert np.allclose(pooled, [[4, 4, 4], [0, 0, 0], [-1, -1, -1]])
+    g = np.arange(9.0).reshape(3, 3)
+    dx = glue.pool_avg_bwd(bidx, g, counts)
+    assert np.allclose(dx[0], g[0] / 3) and np.allclose(dx[4], g[2] / 2)
+    # uniform logits: loss = log(m); dlogits = (1/m - onehot) / clouds
+    m, B = 7, 4
+    labels = np.array([0, 3, 6, 3])
+    loss, d = glue.softmax_ce(np.zeros((B, m)), labels)
+    assert np.isclose(loss, np.log(m))
+    want = np.full((B, m), 1.0 / m)
+    want[np.arange(B), labels] -= 1.0
+    assert np.allclose(d, want / B)
