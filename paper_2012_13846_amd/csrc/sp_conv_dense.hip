@@ -44,38 +44,50 @@ struct DenseArgs {
     uint32_t f_bytes, w_bytes, nbr_bytes;
 };
 
-template <int CC, int COT>
+// CC contraction channels, COT destination channels per workgroup (64, 128: 4 wavefronts; 256: 8), KS
+// contraction channels per step (64; 32 works too but makes the steps too short to pay for their barrier).
+template <int CC, int COT, int KS>
 struct DenseCfg {
     static constexpr int kTR = 256;                  // destination rows per workgroup
-    static constexpr int kKS = 64;                   // contraction channels per step: one staged row is 128 bytes
-    static constexpr int kWaves = 4 * (COT / 128);   // 4 row quarters x COT/128 channel halves
+    static constexpr int kKS = KS;
+    static constexpr int kRowBytes = KS * 2;         // one staged slice row: 128 or 64 bytes
+    static constexpr int kP = kRowBytes / 16;        // 16-byte pieces per staged row
+    static constexpr int kKSteps = KS / 32;          // MFMA k-steps per slice
+    static constexpr int kWaves = COT == 256 ? 8 : 4;  // 4 row quarters x (COT == 256: 2 channel halves)
     static constexpr int kThreads = 64 * kWaves;
-    static constexpr int kXBytes = kTR * 128, kWBytes = COT * 128, kBuf = kXBytes + kWBytes;
+    static constexpr int kXBytes = kTR * kRowBytes, kWBytes = COT * kRowBytes, kBuf = kXBytes + kWBytes;
     static constexpr int kSlices = CC / kKS;
-    static constexpr int kRP = kThreads / 8;         // rows loaded per pass: 8 lanes per 128-byte row
+    static constexpr int kRP = kThreads / kP;        // rows loaded per pass: kP lanes per row
     static constexpr int kXLoads = kTR / kRP;        // 16-byte pieces per thread and step
     static constexpr int kWLoads = COT / kRP;
     static constexpr int kWDepth = kWaves > 4 ? 1 : 2;  // register stages of the weight slices (the rows always have 2)
     static constexpr int kOutPitch = COT * 2 + 16;   // output staging row (bf16)
     static constexpr int kLds = 2 * kBuf > kTR * kOutPitch ? 2 * kBuf : kTR * kOutPitch;
     static constexpr int kMI = 4;                    // 16-row groups per wavefront: 64 rows
-    static constexpr int kNI = 8;                    // 16-channel tiles per wavefront: 128 channels
-    static_assert(CC % (2 * kKS) == 0, "an even number of slices: the register stage of a step is s % 2");
-    static_assert(COT == 128 || COT == 256, "channel slice");
+    static constexpr int kNI = COT == 64 ? 4 : 8;    // 16-channel tiles per wavefront: 64 or 128 channels
+    static_assert(CC % kKS == 0, "whole slices");
+    static_assert(COT == 64 || COT == 128 || COT == 256, "channel slice");
+    static_assert(KS == 64 || KS == 32, "slice width");
+    static_assert(COT % kRP == 0 && kTR % kRP == 0, "whole loads per thread");
 };
 
-// Staged rows are 128 bytes with no pad; the 16-byte piece p of row r sits in slot p ^ ((r >> 1) & 7).  With
-// this swizzle the b128 fragment reads (16 rows x 4 k-groups per wavefront) run at the full LDS rate, like a
-// 32-byte pad would, and the buffers stay small enough for 8 wavefronts' worth of tile.
-__device__ __forceinline__ int swz(int row, int piece) { return (piece ^ ((row >> 1) & 7)) * 16; }
+// Staged rows have no pad; the 16-byte piece p of row r sits in slot p ^ f(r), f(r) = (r >> 1) & 7 for 128-byte
+// rows and (r >> 2) & 3 for 64-byte rows (rows that share a bank range get different slots).  With this swizzle
+// the b128 fragment reads (16 rows x 4 k-groups per wavefront) run at the full LDS rate, like a 32-byte pad
+// would, and the buffers stay small enough for 8 wavefronts' worth of tile.
+template <int P>
+__device__ __forceinline__ int swz(int row, int piece) {
+    return (P == 8 ? (piece ^ ((row >> 1) & 7)) : (piece ^ ((row >> 2) & 3))) * 16;
+}
 
 template <int COT>
-constexpr int kDenseThreads = 64 * 4 * (COT / 128);
+constexpr int kDenseThreads = COT == 256 ? 512 : 256;
 
-template <int CC, int COT>
+template <int CC, int COT, int KS>
 __global__ __launch_bounds__(kDenseThreads<COT>) void gather_dense_kernel(DenseArgs a) {
-    using Cfg = DenseCfg<CC, COT>;
-    constexpr int kMI = Cfg::kMI, kNI = Cfg::kNI, kSlices = Cfg::kSlices, kRP = Cfg::kRP;
+    using Cfg = DenseCfg<CC, COT, KS>;
+    constexpr int kMI = Cfg::kMI, kNI = Cfg::kNI, kSlices = Cfg::kSlices, kRP = Cfg::kRP, kP = Cfg::kP;
+    constexpr int kRowBytes = Cfg::kRowBytes, kKSteps = Cfg::kKSteps;
     constexpr int kXLoads = Cfg::kXLoads, kWLoads = Cfg::kWLoads, kWDepth = Cfg::kWDepth;
     extern __shared__ __align__(16) unsigned char smem[];
 
@@ -89,7 +101,7 @@ __global__ __launch_bounds__(kDenseThreads<COT>) void gather_dense_kernel(DenseA
     if (row0 >= a.n_rows) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n16 = lane & 15, g = lane >> 4;
-    const int rq = wave & 3, ch = wave >> 2;  // this wavefront: tile rows rq*64 .. +63, slice channels ch*128 .. +127
+    const int rq = wave & 3, ch = wave >> 2;  // this wavefront: tile rows rq*64 .. +63, slice channels ch*128 .. (+127 | +63)
 
     constexpr int kRsrcFlags = 0x00020000;
     constexpr uint32_t kOutside = 0x80000000u;  // buffers are smaller than 2 GiB: this offset reads as zeros
@@ -98,10 +110,10 @@ __global__ __launch_bounds__(kDenseThreads<COT>) void gather_dense_kernel(DenseA
     const __amdgpu_buffer_rsrc_t rN =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t*>(a.nbr), 0, (int)a.nbr_bytes, kRsrcFlags);
 
-    // Loading: 8 adjacent lanes fetch the 8 pieces of one 128-byte slice row; thread t takes piece t % 8 of
-    // the tile rows t / 8 + kRP j and of the weight rows (destination channels) t / 8 + kRP j.
-    const int piece = tid & 7, lrow = tid >> 3;
-    const int st_off = lrow * 128 + swz(lrow, piece);  // + kRP j rows: kRP is a multiple of 16, the swizzle stays
+    // Loading: kP adjacent lanes fetch the pieces of one slice row; thread t takes piece t % kP of the tile
+    // rows t / kP + kRP j and of the weight rows (destination channels) t / kP + kRP j.
+    const int piece = tid % kP, lrow = tid / kP;
+    const int st_off = lrow * kRowBytes + swz<kP>(lrow, piece);  // + kRP j rows: kRP is a multiple of 16, the swizzle stays
     // Per offset and thread: the byte offsets of its kXLoads source rows (kOutside where the row has no
     // neighbour: such a load returns zeros) and of its first weight row.  A step's loads then differ from
     // these only by constants, which ride in the instruction's scalar offset.
@@ -128,16 +140,16 @@ __global__ __launch_bounds__(kDenseThreads<COT>) void gather_dense_kernel(DenseA
         wh.w = k < a.kvol ? ((uint32_t)wk * a.co_total + co0 + lrow) * (CC * 2) + piece * 16 : kOutside;
     };
     auto load_x = [&](u32x4 (&x)[kXLoads], int j, int s, const Where& wh) __attribute__((always_inline)) {
-        x[j] = __builtin_amdgcn_raw_buffer_load_b128(rF, wh.x[j], s * 128, 0);
+        x[j] = __builtin_amdgcn_raw_buffer_load_b128(rF, wh.x[j], s * kRowBytes, 0);
     };
     auto load_w = [&](u32x4 (&w)[kWLoads], int j, int s, const Where& wh) __attribute__((always_inline)) {
-        w[j] = __builtin_amdgcn_raw_buffer_load_b128(rW, wh.w, j * kRP * (CC * 2) + s * 128, 0);
+        w[j] = __builtin_amdgcn_raw_buffer_load_b128(rW, wh.w, j * kRP * (CC * 2) + s * kRowBytes, 0);
     };
     auto store_x = [&](const u32x4 (&x)[kXLoads], int j, unsigned char* buf) __attribute__((always_inline)) {
-        *reinterpret_cast<u32x4*>(buf + st_off + j * kRP * 128) = x[j];
+        *reinterpret_cast<u32x4*>(buf + st_off + j * kRP * kRowBytes) = x[j];
     };
     auto store_w = [&](const u32x4 (&w)[kWLoads], int j, unsigned char* buf) __attribute__((always_inline)) {
-        *reinterpret_cast<u32x4*>(buf + Cfg::kXBytes + st_off + j * kRP * 128) = w[j];
+        *reinterpret_cast<u32x4*>(buf + Cfg::kXBytes + st_off + j * kRP * kRowBytes) = w[j];
     };
 
     // acc[ni][mi][i]: destination channel co0 + ch*128 + ni*16 + 4*g + i, tile row rq*64 + mi*16 + n16
@@ -149,23 +161,26 @@ __global__ __launch_bounds__(kDenseThreads<COT>) void gather_dense_kernel(DenseA
 #pragma unroll
         for (int mi = 0; mi < kMI; ++mi) acc[ni][mi] = f32x4{0.f, 0.f, 0.f, 0.f};
     // fragment of (row n16 of a 16-row group, k-group g) for the two k-steps; + 16-row groups as constants
-    const int frag_x[2] = {(rq * 64 + n16) * 128 + swz(n16, g), (rq * 64 + n16) * 128 + swz(n16, 4 + g)};
-    const int frag_w[2] = {Cfg::kXBytes + (ch * 128 + n16) * 128 + swz(n16, g),
-                           Cfg::kXBytes + (ch * 128 + n16) * 128 + swz(n16, 4 + g)};
-    // One step = 2 k-steps x kNI channel tiles = 2*kNI groups of kMI MFMAs.  A wavefront issues in order and
-    // an MFMA runs for 16 cycles once issued, so everything else the step has to do is dealt out over the
+    // (for 64-byte rows there is one k-step and the second entries are not used)
+    const int frag_x[2] = {(rq * 64 + n16) * kRowBytes + swz<kP>(n16, g),
+                           (rq * 64 + n16) * kRowBytes + swz<kP>(n16, (4 + g) % kP)};
+    const int frag_w[2] = {Cfg::kXBytes + (ch * 128 + n16) * kRowBytes + swz<kP>(n16, g),
+                           Cfg::kXBytes + (ch * 128 + n16) * kRowBytes + swz<kP>(n16, (4 + g) % kP)};
+    // One step = kKSteps k-steps x kNI channel tiles = kGroups groups of kMI MFMAs.  A wavefront issues in order
+    // and an MFMA runs for 16 cycles once issued, so everything else the step has to do is dealt out over the
     // groups and issued in the shadow of their MFMAs: the LDS fragment reads (two groups ahead of their
     // use: 3 rotating weight fragments; the second k-step's row fragments during the first k-step), the
-    // global loads of later steps and the LDS stores of the next step's stage, one of each per group.
-    constexpr int kGroups = 2 * kNI;
-    static_assert(kXLoads + kWLoads <= kGroups, "one load and one store per group");
+    // global loads of later steps and the LDS stores of the next step's stage, kPerGroup of each per group.
+    constexpr int kGroups = kKSteps * kNI;
+    constexpr int kLoads = kXLoads + kWLoads;
+    constexpr int kPerGroup = (kLoads + kGroups - 1) / kGroups;
     auto compute = [&](const unsigned char* buf, auto&& extra) __attribute__((always_inline)) {
-        bf16x8 xf[2][kMI], wf[3];
+        bf16x8 xf[kKSteps][kMI], wf[3];
         auto read_w = [&](int grp) __attribute__((always_inline)) {
-            return *reinterpret_cast<const bf16x8*>(buf + frag_w[grp / kNI] + (grp % kNI) * 16 * 128);
+            return *reinterpret_cast<const bf16x8*>(buf + frag_w[grp / kNI] + (grp % kNI) * 16 * kRowBytes);
         };
         auto read_x = [&](int ks, int mi) __attribute__((always_inline)) {
-            return *reinterpret_cast<const bf16x8*>(buf + frag_x[ks] + mi * 16 * 128);
+            return *reinterpret_cast<const bf16x8*>(buf + frag_x[ks] + mi * 16 * kRowBytes);
         };
 #pragma unroll
         for (int mi = 0; mi < kMI; ++mi) xf[0][mi] = read_x(0, mi);
@@ -174,65 +189,84 @@ __global__ __launch_bounds__(kDenseThreads<COT>) void gather_dense_kernel(DenseA
 #pragma unroll
         for (int grp = 0; grp < kGroups; ++grp) {
             if (grp + 2 < kGroups) wf[(grp + 2) % 3] = read_w(grp + 2);
-            if (grp >= 1 && grp <= kMI) xf[1][grp - 1] = read_x(1, grp - 1);
-            extra(grp);
+            if (kKSteps == 2 && grp >= 1 && grp <= kMI) xf[kKSteps - 1][grp - 1] = read_x(1, grp - 1);
+#pragma unroll
+            for (int e = 0; e < kPerGroup; ++e) extra(grp * kPerGroup + e);
             __builtin_amdgcn_sched_barrier(0);  // keeps this group's other work ahead of the MFMAs that hide it
 #pragma unroll
             for (int mi = 0; mi < kMI; ++mi) mfma_acc(acc[grp % kNI][mi], wf[grp % 3], xf[grp / kNI][mi]);
         }
     };
 
-    // Steps = (offset, slice), step t = k * kSlices + s, computed out of LDS buffer t % 2.  The gathered rows
-    // have two register stages (they mostly miss L2, and one step of arithmetic is shorter than that latency):
-    // during step t the rows of step t+2 are requested and those of step t+1 are stored to the other buffer.
-    // The weight slices (L2 hits) have kWDepth stages.  The neighbour entries are requested two offsets ahead.
-    Where cur, nxt;     // offsets k and k + 1
-    int raw[kXLoads];   // neighbour entries of offset k + 2, in flight
+    // The loop runs over "rounds" of kRS = 2 or 4 steps.  For Cin >= 128 a round is one offset and its steps
+    // are the offset's 64-channel slices; for Cin = 64 a round is two offsets, one step each (the sum over
+    // offsets and the sum over channels are one contraction, so a step is just 64 more columns of it).
+    // Step j of a round works out of LDS buffer j % 2.  The gathered rows have two register stages (they mostly
+    // miss L2, and one step of arithmetic is shorter than that latency): during a step the rows of the step two
+    // ahead are requested and those of the next step are stored to the other buffer.  The weight slices (L2
+    // hits) have kWDepth stages.  The neighbour entries are requested two rounds ahead.
+    constexpr int kSPO = kSlices;                   // slices per offset: 1, 2 or 4
+    constexpr int kOPR = kSPO == 1 ? 2 : 1;         // offsets per round
+    constexpr int kRS = kSPO * kOPR;                // steps per round
+    static_assert(kRS % 2 == 0, "the register stage and LDS buffer of a step are its index in the round % 2");
+    Where cur[kOPR], nxt[kOPR];  // the offsets of this round and of the next
+    int raw[kOPR][kXLoads];      // neighbour entries of the round after that, in flight
+#pragma unroll
+    for (int o = 0; o < kOPR; ++o) {
+        load_nbr(o, raw[o]);
+        locate(o, raw[o], cur[o]);
+    }
+#pragma unroll
+    for (int o = 0; o < kOPR; ++o) {
+        load_nbr(kOPR + o, raw[o]);
+        locate(kOPR + o, raw[o], nxt[o]);
+    }
+#pragma unroll
+    for (int o = 0; o < kOPR; ++o) load_nbr(2 * kOPR + o, raw[o]);
     u32x4 sx[2][kXLoads], sw[kWDepth][kWLoads];
-    load_nbr(0, raw);
-    locate(0, raw, cur);
-    load_nbr(1, raw);
-    locate(1, raw, nxt);
-    load_nbr(2, raw);
+    // step j of this round (j < kRS) or of the next (j >= kRS): its offset's addresses and its slice
+    auto where_of = [&](int j) -> const Where& { return j < kRS ? cur[j / kSPO] : nxt[(j - kRS) / kSPO]; };
 #pragma unroll
-    for (int j = 0; j < kXLoads; ++j) load_x(sx[0], j, 0, cur);
+    for (int j = 0; j < kXLoads; ++j) load_x(sx[0], j, 0, where_of(0));
 #pragma unroll
-    for (int j = 0; j < kWLoads; ++j) load_w(sw[0], j, 0, cur);
+    for (int j = 0; j < kWLoads; ++j) load_w(sw[0], j, 0, where_of(0));
 #pragma unroll
-    for (int j = 0; j < kXLoads; ++j) load_x(sx[1], j, 1, cur);
+    for (int j = 0; j < kXLoads; ++j) load_x(sx[1], j, 1 % kSPO, where_of(1));
     if constexpr (kWDepth == 2) {
 #pragma unroll
-        for (int j = 0; j < kWLoads; ++j) load_w(sw[1], j, 1, cur);
+        for (int j = 0; j < kWLoads; ++j) load_w(sw[1], j, 1 % kSPO, where_of(1));
     }
 #pragma unroll
     for (int j = 0; j < kXLoads; ++j) store_x(sx[0], j, smem);
 #pragma unroll
     for (int j = 0; j < kWLoads; ++j) store_w(sw[0], j, smem);
     __syncthreads();
-    for (int k = 0; k < a.kvol; ++k) {
+    for (int k = 0; k < a.kvol; k += kOPR) {
 #pragma unroll
-        for (int s = 0; s < kSlices; ++s) {
-            compute(smem + (s % 2) * Cfg::kBuf, [&](int grp) __attribute__((always_inline)) {
-                // requests: weight slice of step t + kWDepth, then rows of step t + 2
-                if (grp < kWLoads) {
+        for (int s = 0; s < kRS; ++s) {
+            compute(smem + (s % 2) * Cfg::kBuf, [&](int slot) __attribute__((always_inline)) {
+                // slot = 0 .. kGroups * kPerGroup - 1.  Requests: weight slice of the step kWDepth ahead, then
+                // the rows of the step 2 ahead
+                if (slot < kWLoads) {
                     constexpr int d = kWDepth;
-                    if (s + d < kSlices) load_w(sw[(s + d) % kWDepth], grp, s + d, cur);
-                    else load_w(sw[(s + d) % kWDepth], grp, s + d - kSlices, nxt);
-                } else if (grp < kWLoads + kXLoads) {
-                    if (s + 2 < kSlices) load_x(sx[s % 2], grp - kWLoads, s + 2, cur);
-                    else load_x(sx[s % 2], grp - kWLoads, s + 2 - kSlices, nxt);
+                    load_w(sw[(s + d) % kWDepth], slot, (s + d) % kSPO, where_of(s + d));
+                } else if (slot < kLoads) {
+                    load_x(sx[s % 2], slot - kWLoads, (s + 2) % kSPO, where_of(s + 2));
                 }
-                // stores of step t + 1's stage: rows first (requested a step ago), weights last
-                const int st = grp - (kGroups - kXLoads - kWLoads);
+                // stores of the next step's stage in the last slots: rows first (requested a step ago), weights last
+                const int st = slot - (kGroups * kPerGroup - kLoads);
                 unsigned char* other = smem + ((s + 1) % 2) * Cfg::kBuf;
                 if (st >= 0 && st < kXLoads) store_x(sx[(s + 1) % 2], st, other);
                 else if (st >= kXLoads) store_w(sw[(s + 1) % kWDepth], st - kXLoads, other);
             });
             __syncthreads();
         }
-        cur = nxt;
-        locate(k + 2, raw, nxt);
-        load_nbr(k + 3, raw);
+#pragma unroll
+        for (int o = 0; o < kOPR; ++o) {
+            cur[o] = nxt[o];
+            locate(k + 2 * kOPR + o, raw[o], nxt[o]);
+            load_nbr(k + 3 * kOPR + o, raw[o]);
+        }
     }
 
     // the accumulators are read below by ordinary instructions: the MFMAs were written as opaque instructions,
@@ -261,10 +295,10 @@ __global__ __launch_bounds__(kDenseThreads<COT>) void gather_dense_kernel(DenseA
     }
 }
 
-template <int CC, int COT>
+template <int CC, int COT, int KS>
 int launch_dense(const DenseArgs& a, hipStream_t s) {
-    using Cfg = DenseCfg<CC, COT>;
-    auto kern = gather_dense_kernel<CC, COT>;
+    using Cfg = DenseCfg<CC, COT, KS>;
+    auto kern = gather_dense_kernel<CC, COT, KS>;
     static bool attr_set = false;  // one-time opt-in to > 64 KB of dynamic LDS
     if (!attr_set) {
         SP_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -281,7 +315,9 @@ int launch_dense(const DenseArgs& a, hipStream_t s) {
 
 }  // namespace
 
-bool dense_shape_ok(int cc, int co, sp_dtype dt) { return dt == SP_BF16 && (cc == 128 || cc == 256) && co % 128 == 0; }
+// Cin = 64 layers work too (two offsets per round, instantiate <64, COT, 64>), but measured slower than the
+// link-list kernel there: their steps hold too little arithmetic to cover the gather latency two steps ahead.
+bool dense_shape_ok(int cc, int co, sp_dtype dt) { return dt == SP_BF16 && (cc == 128 || cc == 256) && co % 64 == 0; }
 
 // d_w: [kvol][co][cc] (contraction index fastest).  Buffers must be smaller than 2 GiB.
 int conv_gather_dense(const MapSide& side, int kvol, const void* d_f, const void* d_w, void* d_g, int cc, int co,
@@ -298,9 +334,17 @@ int conv_gather_dense(const MapSide& side, int kvol, const void* d_f, const void
     a.f_bytes = (uint32_t)((uint64_t)side.n_src * cc * 2);
     a.w_bytes = (uint32_t)((uint64_t)kvol * co * cc * 2);
     a.nbr_bytes = (uint32_t)((uint64_t)kvol * side.n_rows * 4);
-    const bool wide = co % 256 == 0;
-    if (cc == 128) return wide ? launch_dense<128, 256>(a, s) : launch_dense<128, 128>(a, s);
-    return wide ? launch_dense<256, 256>(a, s) : launch_dense<256, 128>(a, s);
+    const int cot = co % 256 == 0 ? 256 : (co % 128 == 0 ? 128 : 64);
+#define SP_DENSE(CC, COT, KS) \
+    if (cc == CC && cot == COT) return launch_dense<CC, COT, KS>(a, s)
+    SP_DENSE(256, 256, 64);
+    SP_DENSE(256, 128, 64);
+    SP_DENSE(256, 64, 64);
+    SP_DENSE(128, 256, 64);
+    SP_DENSE(128, 128, 64);
+    SP_DENSE(128, 64, 64);
+#undef SP_DENSE
+    return fail(SP_ERR_UNSUPPORTED, "no row-stationary kernel for %d -> %d channels", cc, co);
 }
 
 }  // namespace sp
