@@ -666,7 +666,8 @@ int conv_gather(const MapSide& side, int kvol, int64_t total_links, const void* 
     // 128- and 256-channel layers, it is the faster one from about 1 link in 20 row-offsets upwards.
     const uint64_t lim = 0x7fffffffull;
     const double min_fill = 0.06;
-    if (dense_shape_ok(cc, co, dt) && (double)total_links >= min_fill * (double)side.n_rows * kvol &&
+    // (A side with position classes skips the offsets its tiles cannot have: its cost follows the links.)
+    if (dense_shape_ok(cc, co, dt) && (side.tile_mask || (double)total_links >= min_fill * (double)side.n_rows * kvol) &&
         (uint64_t)side.n_src * cc * elt < lim && (uint64_t)side.n_rows * kvol * 4 < lim &&
         (uint64_t)kvol * cc * co * elt < lim) {
         Buf wt;

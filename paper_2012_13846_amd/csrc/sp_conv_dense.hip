@@ -42,6 +42,8 @@ struct DenseArgs {
     int64_t n_rows;
     int kvol, co_total, flip;
     uint32_t f_bytes, w_bytes, nbr_bytes;
+    const int32_t* perm;        // null, or the order in which the destination rows are taken (tile = 256 entries)
+    const uint32_t* tile_mask;  // null, or per tile 4 words: the offsets that link any of its rows
 };
 
 // CC contraction channels, COT destination channels per workgroup (64, 128: 4 wavefronts; 256: 8), KS
@@ -97,7 +99,7 @@ __global__ __launch_bounds__(kDenseThreads<COT>) void gather_dense_kernel(DenseA
     const int id = blockIdx.x;
     const int64_t tile = (int64_t)(id / (8 * nslice)) * 8 + id % 8;
     const int co0 = ((id / 8) % nslice) * COT;
-    const int64_t row0 = tile * Cfg::kTR;
+    const int64_t row0 = tile * Cfg::kTR;  // first entry of the tile (in perm order if there is one)
     if (row0 >= a.n_rows) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n16 = lane & 15, g = lane >> 4;
@@ -120,20 +122,26 @@ __global__ __launch_bounds__(kDenseThreads<COT>) void gather_dense_kernel(DenseA
     struct Where {
         uint32_t x[kXLoads], w;
     };
+    // destination rows this thread gathers for: entry row0 + lrow + kRP j of the tile, -1 past the end
+    int my_row[kXLoads];
+#pragma unroll
+    for (int j = 0; j < kXLoads; ++j) {
+        const int64_t e = row0 + lrow + kRP * j;
+        my_row[j] = e < a.n_rows ? (a.perm ? a.perm[e] : (int)e) : -1;
+    }
     auto load_nbr = [&](int k, int (&raw)[kXLoads]) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < kXLoads; ++j) {
-            const int64_t row = row0 + lrow + kRP * j;
-            const bool live = row < a.n_rows && k < a.kvol;
+            const bool live = my_row[j] >= 0 && k < a.kvol;
             // past the table the load returns 0, which would name row 0: such entries are masked in locate()
             raw[j] = (int)__builtin_amdgcn_raw_buffer_load_b32(
-                rN, live ? (uint32_t)(((int64_t)k * a.n_rows + row) * 4) : kOutside, 0, 0);
+                rN, live ? (uint32_t)(((int64_t)k * a.n_rows + my_row[j]) * 4) : kOutside, 0, 0);
         }
     };
     auto locate = [&](int k, const int (&raw)[kXLoads], Where& wh) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < kXLoads; ++j) {
-            const bool live = row0 + lrow + kRP * j < a.n_rows && k < a.kvol && raw[j] >= 0;
+            const bool live = my_row[j] >= 0 && k < a.kvol && raw[j] >= 0;
             wh.x[j] = live ? (uint32_t)raw[j] * (CC * 2) + piece * 16 : kOutside;
         }
         const int wk = a.flip ? a.kvol - 1 - k : k;
@@ -209,20 +217,48 @@ __global__ __launch_bounds__(kDenseThreads<COT>) void gather_dense_kernel(DenseA
     constexpr int kOPR = kSPO == 1 ? 2 : 1;         // offsets per round
     constexpr int kRS = kSPO * kOPR;                // steps per round
     static_assert(kRS % 2 == 0, "the register stage and LDS buffer of a step are its index in the round % 2");
+    // The offsets to visit, ascending: all of them, or those of the tile's mask.  next_offset() hands them out
+    // one by one and then kvol (for which every load reads zeros) for ever.
+    uint32_t todo[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int lo = 32 * i, n = a.kvol - lo;
+        uint32_t all = n >= 32 ? 0xffffffffu : (n > 0 ? (1u << n) - 1u : 0u);
+        if (a.tile_mask) all &= a.tile_mask[tile * 4 + i];
+        todo[i] = __builtin_amdgcn_readfirstlane(all);
+    }
+    auto next_offset = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (todo[i]) {
+                const int b = __builtin_ctz(todo[i]);
+                todo[i] &= todo[i] - 1;
+                return 32 * i + b;
+            }
+        return a.kvol;
+    };
     Where cur[kOPR], nxt[kOPR];  // the offsets of this round and of the next
+    int k_cur[kOPR];             // this round's offsets (kvol: none left)
     int raw[kOPR][kXLoads];      // neighbour entries of the round after that, in flight
+    int k_raw[kOPR];
 #pragma unroll
     for (int o = 0; o < kOPR; ++o) {
-        load_nbr(o, raw[o]);
-        locate(o, raw[o], cur[o]);
+        k_cur[o] = next_offset();
+        load_nbr(k_cur[o], raw[o]);
+        locate(k_cur[o], raw[o], cur[o]);
+    }
+    int k_nxt[kOPR];
+#pragma unroll
+    for (int o = 0; o < kOPR; ++o) {
+        k_nxt[o] = next_offset();
+        load_nbr(k_nxt[o], raw[o]);
+        locate(k_nxt[o], raw[o], nxt[o]);
     }
 #pragma unroll
     for (int o = 0; o < kOPR; ++o) {
-        load_nbr(kOPR + o, raw[o]);
-        locate(kOPR + o, raw[o], nxt[o]);
+        k_raw[o] = next_offset();
+        load_nbr(k_raw[o], raw[o]);
     }
-#pragma unroll
-    for (int o = 0; o < kOPR; ++o) load_nbr(2 * kOPR + o, raw[o]);
     u32x4 sx[2][kXLoads], sw[kWDepth][kWLoads];
     // step j of this round (j < kRS) or of the next (j >= kRS): its offset's addresses and its slice
     auto where_of = [&](int j) -> const Where& { return j < kRS ? cur[j / kSPO] : nxt[(j - kRS) / kSPO]; };
@@ -241,7 +277,7 @@ __global__ __launch_bounds__(kDenseThreads<COT>) void gather_dense_kernel(DenseA
 #pragma unroll
     for (int j = 0; j < kWLoads; ++j) store_w(sw[0], j, smem);
     __syncthreads();
-    for (int k = 0; k < a.kvol; k += kOPR) {
+    while (k_cur[0] < a.kvol) {
 #pragma unroll
         for (int s = 0; s < kRS; ++s) {
             compute(smem + (s % 2) * Cfg::kBuf, [&](int slot) __attribute__((always_inline)) {
@@ -264,8 +300,11 @@ __global__ __launch_bounds__(kDenseThreads<COT>) void gather_dense_kernel(DenseA
 #pragma unroll
         for (int o = 0; o < kOPR; ++o) {
             cur[o] = nxt[o];
-            locate(k + 2 * kOPR + o, raw[o], nxt[o]);
-            load_nbr(k + 3 * kOPR + o, raw[o]);
+            k_cur[o] = k_nxt[o];
+            k_nxt[o] = k_raw[o];
+            locate(k_nxt[o], raw[o], nxt[o]);
+            k_raw[o] = next_offset();
+            load_nbr(k_raw[o], raw[o]);
         }
     }
 
@@ -288,8 +327,8 @@ __global__ __launch_bounds__(kDenseThreads<COT>) void gather_dense_kernel(DenseA
     constexpr int kRowPieces = COT * 2 / 16;
     for (int idx = tid; idx < Cfg::kTR * kRowPieces; idx += Cfg::kThreads) {
         const int r = idx / kRowPieces, pc = idx % kRowPieces;
-        const int64_t row = row0 + r;
-        if (row >= a.n_rows) break;
+        if (row0 + r >= a.n_rows) break;
+        const int64_t row = a.perm ? a.perm[row0 + r] : row0 + r;
         *reinterpret_cast<u32x4*>(static_cast<unsigned char*>(a.g) + ((size_t)row * a.co_total + co0) * 2 + pc * 16) =
             *reinterpret_cast<const u32x4*>(out + r * Cfg::kOutPitch + pc * 16);
     }
@@ -334,6 +373,8 @@ int conv_gather_dense(const MapSide& side, int kvol, const void* d_f, const void
     a.f_bytes = (uint32_t)((uint64_t)side.n_src * cc * 2);
     a.w_bytes = (uint32_t)((uint64_t)kvol * co * cc * 2);
     a.nbr_bytes = (uint32_t)((uint64_t)kvol * side.n_rows * 4);
+    a.perm = ptr<int32_t>(side.perm);
+    a.tile_mask = ptr<uint32_t>(side.tile_mask);
     const int cot = co % 256 == 0 ? 256 : (co % 128 == 0 ? 128 : 64);
 #define SP_DENSE(CC, COT, KS) \
     if (cc == CC && cot == COT) return launch_dense<CC, COT, KS>(a, s)

@@ -100,6 +100,12 @@ struct MapSide {
     Buf tl_src;   // int32 [total]
     Buf tl_row;   // uint16 [total]
     bool flip = false;  // weight offset index = kvol-1-k (side derived by the stride-1 symmetry)
+    // Input side of a strided map only: which offsets can link an input row depends on the row's position inside
+    // its coarse cell (stride 2, K = 3: 1 to 8 of the 27).  `perm` lists the rows sorted by that position class
+    // and `tile_mask` holds, per 256 entries of perm, the offsets that link at least one of them (4 words, bit k
+    // of word k/32), so that a row-stationary kernel walking perm skips the other offsets of a tile.
+    Buf perm;       // int32 [n_rows] or null
+    Buf tile_mask;  // uint32 [ceil(n_rows/256)][4] or null
 };
 
 }  // namespace sp

@@ -118,7 +118,91 @@ __global__ __launch_bounds__(kThreads) void emit_kernel(const int32_t* __restric
     }
 }
 
+// Position class of an input row inside its coarse cell: ((x/ts) mod s, (y/ts) mod s, (z/ts) mod s) as one number.
+__device__ __forceinline__ int cell_class(const int4& c, int ts, int stride) {
+    auto r = [&](int v) { const int q = v / ts % stride; return q < 0 ? q + stride : q; };  // coordinates are multiples of ts
+    return (r(c.y) * stride + r(c.z)) * stride + r(c.w);
+}
+
+// cnt[cls * ntiles + tile] = rows of the tile in class cls (tiles of 256 rows in row order)
+__global__ __launch_bounds__(kThreads) void class_count_kernel(const int4* __restrict__ coords, int64_t n, int ts,
+                                                               int stride, int nclass, int32_t* __restrict__ cnt) {
+    __shared__ int s_cnt[32][kSubTiles];
+    const int64_t r = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int cls = r < n ? cell_class(coords[r], ts, stride) : -1;
+    const int w = threadIdx.x >> 6;
+    for (int c = 0; c < nclass; ++c) {
+        const unsigned long long m = __ballot(cls == c);
+        if ((threadIdx.x & 63) == 0) s_cnt[c][w] = __popcll(m);
+    }
+    __syncthreads();
+    if (threadIdx.x < nclass)
+        cnt[(int64_t)threadIdx.x * gridDim.x + blockIdx.x] =
+            s_cnt[threadIdx.x][0] + s_cnt[threadIdx.x][1] + s_cnt[threadIdx.x][2] + s_cnt[threadIdx.x][3];
+}
+
+// perm[off[cls * ntiles + tile] + rank of the row among the tile's rows of its class] = row
+__global__ __launch_bounds__(kThreads) void class_emit_kernel(const int4* __restrict__ coords, int64_t n, int ts,
+                                                              int stride, int nclass, const int32_t* __restrict__ off,
+                                                              int32_t* __restrict__ perm) {
+    __shared__ int s_cnt[32][kSubTiles];
+    const int64_t r = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int cls = r < n ? cell_class(coords[r], ts, stride) : -1;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int rank = 0;
+    for (int c = 0; c < nclass; ++c) {
+        const unsigned long long m = __ballot(cls == c);
+        if (lane == 0) s_cnt[c][w] = __popcll(m);
+        if (cls == c) rank = __popcll(m & ((1ull << lane) - 1ull));
+    }
+    __syncthreads();
+    if (cls >= 0) {
+        for (int j = 0; j < w; ++j) rank += s_cnt[cls][j];
+        perm[off[(int64_t)cls * gridDim.x + blockIdx.x] + rank] = (int32_t)r;
+    }
+}
+
+// mask[tile][k / 32] bit k % 32 = some row of perm[tile*256 .. +255] has a link at offset k
+__global__ __launch_bounds__(kThreads) void tile_mask_kernel(const int32_t* __restrict__ nbr, int64_t n, int kvol,
+                                                             const int32_t* __restrict__ perm,
+                                                             uint32_t* __restrict__ mask) {
+    __shared__ uint32_t s_mask[4];
+    if (threadIdx.x < 4) s_mask[threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int64_t row = i < n ? perm[i] : -1;
+    for (int k = 0; k < kvol; ++k) {
+        const bool has = row >= 0 && nbr[(int64_t)k * n + row] >= 0;
+        if (__ballot(has) != 0 && (threadIdx.x & 63) == 0) atomicOr(&s_mask[k >> 5], 1u << (k & 31));
+    }
+    __syncthreads();
+    if (threadIdx.x < 4) mask[(int64_t)blockIdx.x * 4 + threadIdx.x] = s_mask[threadIdx.x];
+}
+
 inline unsigned blocks256(int64_t n) { return (unsigned)((n + 255) / 256); }
+
+// Rows of a strided map's input side sorted by position class, and the per-tile offset masks.
+int build_classes(MapSide& side, const sp_coords* c, int stride, int kvol, hipStream_t s) {
+    const int nclass = stride * stride * stride;
+    const int64_t n = side.n_rows, ntiles = (n + kTileRows - 1) / kTileRows;
+    if (nclass > 32 || n == 0) return SP_OK;  // larger strides: no class order, the kernels take all offsets
+    Buf cnt = dev_alloc((size_t)(nclass * ntiles + 1) * 4);
+    side.perm = dev_alloc((size_t)n * 4);
+    side.tile_mask = dev_alloc((size_t)ntiles * 16);
+    if (!cnt || !side.perm || !side.tile_mask) return SP_ERR_ALLOC;
+    hipLaunchKernelGGL(class_count_kernel, dim3((unsigned)ntiles), dim3(kThreads), 0, s, ptr<int4>(c->coords), n, c->ts,
+                       stride, nclass, ptr<int32_t>(cnt));
+    ScanJob job;
+    job.data = ptr<int32_t>(cnt);
+    job.n = nclass * ntiles;
+    SP_TRY(exclusive_scan_jobs(&job, 1, s));
+    hipLaunchKernelGGL(class_emit_kernel, dim3((unsigned)ntiles), dim3(kThreads), 0, s, ptr<int4>(c->coords), n, c->ts,
+                       stride, nclass, ptr<int32_t>(cnt), ptr<int32_t>(side.perm));
+    hipLaunchKernelGGL(tile_mask_kernel, dim3((unsigned)ntiles), dim3(kThreads), 0, s, ptr<int32_t>(side.nbr), n, kvol,
+                       ptr<int32_t>(side.perm), ptr<uint32_t>(side.tile_mask));
+    SP_HIP(hipGetLastError());
+    return SP_OK;
+}
 
 // Turns sub-tile counts (already in side.tl_off) into offsets and fills the tile lists.
 int finish_side(MapSide& side, int kvol, int64_t total, const int32_t* d_blk_off, int32_t* d_pair_in,
@@ -260,6 +344,7 @@ int sp_kmap_build(const sp_coords_t* in, int32_t kernel_size, int32_t stride, in
         job.total = ptr<int32_t>(si.tl_off) + n_sub_in;
         SP_TRY(exclusive_scan_jobs(&job, 1, s));
         SP_TRY(finish_side(si, kvol, m->total, nullptr, nullptr, nullptr, s));
+        if (stride > 1) SP_TRY(build_classes(si, cin, stride, kvol, s));
     }
     if (out_coords) {
         m->c_out->ref.fetch_add(1);

@@ -245,6 +245,14 @@ def test_wide_bf16_on_dense_maps(sp, cin, cout, side, batches):
     conv_case(sp, full_cubes(side, batches), 1, 3, 1, 1, cin, cout, True, seed=77 + cin + side)
 
 
+@pytest.mark.parametrize("K,cin,cout,transposed,side", [(3, 128, 256, False, 9), (2, 64, 128, False, 10),
+                                                        (2, 256, 128, True, 8), (3, 256, 64, True, 7)])
+def test_wide_bf16_strided_maps_with_position_classes(sp, K, cin, cout, transposed, side):
+    # stride 2: the input side of the map is walked in position-class order with per-tile offset masks
+    # (data gradient of the strided conv; forward of the transposed one)
+    conv_case(sp, full_cubes(side, 2), 1, K, 2, 1, cin, cout, True, seed=99 + K + cin, transposed=transposed)
+
+
 def test_identity_weights_reproduce_input_bit_exactly(sp):
     raw = spgen.coords_config(1, 0.2)
     c = sp.sp_coords_build(dev(raw), 1)
