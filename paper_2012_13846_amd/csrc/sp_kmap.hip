@@ -118,6 +118,8 @@ __global__ __launch_bounds__(kThreads) void emit_kernel(const int32_t* __restric
     }
 }
 
+inline unsigned blocks256(int64_t n) { return (unsigned)((n + 255) / 256); }
+
 // Position class of an input row inside its coarse cell: ((x/ts) mod s, (y/ts) mod s, (z/ts) mod s) as one number.
 __device__ __forceinline__ int cell_class(const int4& c, int ts, int stride) {
     auto r = [&](int v) { const int q = v / ts % stride; return q < 0 ? q + stride : q; };  // coordinates are multiples of ts
@@ -162,27 +164,34 @@ __global__ __launch_bounds__(kThreads) void class_emit_kernel(const int4* __rest
     }
 }
 
-// mask[tile][k / 32] bit k % 32 = some row of perm[tile*256 .. +255] has a link at offset k
-__global__ __launch_bounds__(kThreads) void tile_mask_kernel(const int32_t* __restrict__ nbr, int64_t n, int kvol,
-                                                             const int32_t* __restrict__ perm,
-                                                             uint32_t* __restrict__ mask) {
-    __shared__ uint32_t s_mask[4];
-    if (threadIdx.x < 4) s_mask[threadIdx.x] = 0;
-    __syncthreads();
-    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    const int64_t row = i < n ? perm[i] : -1;
-    for (int k = 0; k < kvol; ++k) {
-        const bool has = row >= 0 && nbr[(int64_t)k * n + row] >= 0;
-        if (__ballot(has) != 0 && (threadIdx.x & 63) == 0) atomicOr(&s_mask[k >> 5], 1u << (k & 31));
+// mask[tile][k / 32] bit k % 32 = offset k can link a row of one of the position classes present in
+// perm[tile*256 .. +255].  Offset (ax, ay, az) links an input at class r to an output only if, per axis, the
+// offset's displacement is congruent to r modulo the stride (output coordinates are multiples of the stride).
+// One thread per tile; the classes' stretches of perm start at off[cls * ntiles].
+__global__ __launch_bounds__(kThreads) void tile_mask_kernel(const int32_t* __restrict__ off, int64_t n, int64_t ntiles,
+                                                             int K, int stride, uint32_t* __restrict__ mask) {
+    const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (t >= ntiles) return;
+    const int nclass = stride * stride * stride, centre = (K & 1) ? (K - 1) / 2 : 0;
+    const int64_t lo = t * kTileRows, hi = lo + kTileRows < n ? lo + kTileRows : n;
+    uint32_t m[4] = {0u, 0u, 0u, 0u};
+    for (int c = 0; c < nclass; ++c) {
+        const int64_t beg = off[(int64_t)c * ntiles], end = c + 1 < nclass ? off[(int64_t)(c + 1) * ntiles] : n;
+        if (beg >= hi || end <= lo) continue;
+        const int r[3] = {c / (stride * stride), c / stride % stride, c % stride};
+        for (int k = 0; k < K * K * K; ++k) {
+            const int d[3] = {k / (K * K) - centre, k / K % K - centre, k % K - centre};
+            bool ok = true;
+            for (int ax = 0; ax < 3; ++ax) ok = ok && ((d[ax] % stride + stride) % stride == r[ax]);
+            if (ok) m[k >> 5] |= 1u << (k & 31);
+        }
     }
-    __syncthreads();
-    if (threadIdx.x < 4) mask[(int64_t)blockIdx.x * 4 + threadIdx.x] = s_mask[threadIdx.x];
+    for (int i = 0; i < 4; ++i) mask[t * 4 + i] = m[i];
 }
 
-inline unsigned blocks256(int64_t n) { return (unsigned)((n + 255) / 256); }
 
 // Rows of a strided map's input side sorted by position class, and the per-tile offset masks.
-int build_classes(MapSide& side, const sp_coords* c, int stride, int kvol, hipStream_t s) {
+int build_classes(MapSide& side, const sp_coords* c, int stride, int K, hipStream_t s) {
     const int nclass = stride * stride * stride;
     const int64_t n = side.n_rows, ntiles = (n + kTileRows - 1) / kTileRows;
     if (nclass > 32 || n == 0) return SP_OK;  // larger strides: no class order, the kernels take all offsets
@@ -198,8 +207,8 @@ int build_classes(MapSide& side, const sp_coords* c, int stride, int kvol, hipSt
     SP_TRY(exclusive_scan_jobs(&job, 1, s));
     hipLaunchKernelGGL(class_emit_kernel, dim3((unsigned)ntiles), dim3(kThreads), 0, s, ptr<int4>(c->coords), n, c->ts,
                        stride, nclass, ptr<int32_t>(cnt), ptr<int32_t>(side.perm));
-    hipLaunchKernelGGL(tile_mask_kernel, dim3((unsigned)ntiles), dim3(kThreads), 0, s, ptr<int32_t>(side.nbr), n, kvol,
-                       ptr<int32_t>(side.perm), ptr<uint32_t>(side.tile_mask));
+    hipLaunchKernelGGL(tile_mask_kernel, dim3(blocks256(ntiles)), dim3(kThreads), 0, s, ptr<int32_t>(cnt), n, ntiles, K,
+                       stride, ptr<uint32_t>(side.tile_mask));
     SP_HIP(hipGetLastError());
     return SP_OK;
 }
@@ -344,7 +353,7 @@ int sp_kmap_build(const sp_coords_t* in, int32_t kernel_size, int32_t stride, in
         job.total = ptr<int32_t>(si.tl_off) + n_sub_in;
         SP_TRY(exclusive_scan_jobs(&job, 1, s));
         SP_TRY(finish_side(si, kvol, m->total, nullptr, nullptr, nullptr, s));
-        if (stride > 1) SP_TRY(build_classes(si, cin, stride, kvol, s));
+        if (stride > 1) SP_TRY(build_classes(si, cin, stride, kernel_size, s));
     }
     if (out_coords) {
         m->c_out->ref.fetch_add(1);
