@@ -48,6 +48,11 @@ CASES = [
     ("cfg3_k3s2_bf16_64x128", 3, 3, 2, 1, 64, 128, True, False),
     ("cfg4_k3_bf16_64x64", 4, 3, 1, 1, 64, 64, True, False),
     ("cfg4_k3d2_bf16_64x64", 4, 3, 1, 2, 64, 64, True, False),
+    # wide layers of the config-3 stack at full row count: the row-stationary kernel (stride 1), and the
+    # position-class order with offset masks (stride 2: data gradient, and forward of the transposed map)
+    ("cfg3_k3_bf16_128x128", 3, 3, 1, 1, 128, 128, True, False),
+    ("cfg3_k3s2_bf16_128x256", 3, 3, 2, 1, 128, 256, True, False),
+    ("cfg3_k3s2_up_bf16_256x128", 3, 3, 2, 1, 256, 128, True, True),
 ]
 
 
