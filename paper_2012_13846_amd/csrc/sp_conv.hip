@@ -662,10 +662,11 @@ int conv_gather(const MapSide& side, int kvol, int64_t total_links, const void* 
     if (side.n_rows == 0) return SP_OK;
     const size_t elt = dt == SP_F32 ? 4 : 2;
     // Row-stationary kernel: it multiplies all kvol offsets of every row, the link-list kernels only the links
-    // that exist but pay per link for bookkeeping, weight re-reads and the accumulator update.  Measured on
-    // 128- and 256-channel layers, it is the faster one from about 1 link in 20 row-offsets upwards.
+    // that exist but pay per link for bookkeeping, weight re-reads and the accumulator update.  Measured, it is
+    // the faster one from about 1 link in 20 row-offsets upwards on 128- and 256-channel inputs, from 1 in 3
+    // on 64-channel inputs.
     const uint64_t lim = 0x7fffffffull;
-    const double min_fill = 0.06;
+    const double min_fill = dense_min_fill(cc);
     // (A side with position classes skips the offsets its tiles cannot have: its cost follows the links.)
     if (dense_shape_ok(cc, co, dt) && (side.tile_mask || (double)total_links >= min_fill * (double)side.n_rows * kvol) &&
         (uint64_t)side.n_src * cc * elt < lim && (uint64_t)side.n_rows * kvol * 4 < lim &&

@@ -354,9 +354,13 @@ int launch_dense(const DenseArgs& a, hipStream_t s) {
 
 }  // namespace
 
-// Cin = 64 layers work too (two offsets per round, instantiate <64, COT, 64>), but measured slower than the
-// link-list kernel there: their steps hold too little arithmetic to cover the gather latency two steps ahead.
-bool dense_shape_ok(int cc, int co, sp_dtype dt) { return dt == SP_BF16 && (cc == 128 || cc == 256) && co % 64 == 0; }
+// Cin = 64: two offsets per round.  Its steps hold little arithmetic next to the gather latency, so it only
+// beats the link-list kernel on well-filled maps (see dense_min_fill).
+bool dense_shape_ok(int cc, int co, sp_dtype dt) {
+    return dt == SP_BF16 && (cc == 64 || cc == 128 || cc == 256) && co % 64 == 0;
+}
+// smallest links / (rows * kvol) from which the row-stationary kernel is the faster one (measured)
+double dense_min_fill(int cc) { return cc == 64 ? 0.40 : 0.06; }
 
 // d_w: [kvol][co][cc] (contraction index fastest).  Buffers must be smaller than 2 GiB.
 int conv_gather_dense(const MapSide& side, int kvol, const void* d_f, const void* d_w, void* d_g, int cc, int co,
@@ -384,6 +388,9 @@ int conv_gather_dense(const MapSide& side, int kvol, const void* d_f, const void
     SP_DENSE(128, 256, 64);
     SP_DENSE(128, 128, 64);
     SP_DENSE(128, 64, 64);
+    SP_DENSE(64, 256, 64);
+    SP_DENSE(64, 128, 64);
+    SP_DENSE(64, 64, 64);
 #undef SP_DENSE
     return fail(SP_ERR_UNSUPPORTED, "no row-stationary kernel for %d -> %d channels", cc, co);
 }

@@ -129,6 +129,7 @@ int conv_gather(const MapSide& side, int kvol, int64_t total_links, const void* 
                 void* d_g, int cc, int co, sp_dtype dt, hipStream_t s);
 // wide bf16 layers on maps where most offsets of a row have a neighbour (sp_conv_dense.hip); d_w is [kvol][co][cc]
 bool dense_shape_ok(int cc, int co, sp_dtype dt);
+double dense_min_fill(int cc);
 int conv_gather_dense(const MapSide& side, int kvol, const void* d_f, const void* d_w, void* d_g, int cc, int co,
                       hipStream_t s);
 int conv_wgrad(const sp_kmap* m, const void* d_x, const void* d_dy, float* d_dw, int cin, int cout, sp_dtype dt,
