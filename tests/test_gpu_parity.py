@@ -239,7 +239,8 @@ def full_cubes(side, batches):
     return rows[np.random.default_rng(11).permutation(len(rows))]
 
 
-@pytest.mark.parametrize("cin,cout,side,batches", [(128, 128, 9, 2), (256, 256, 8, 3), (128, 256, 7, 1), (256, 128, 10, 1)])
+@pytest.mark.parametrize("cin,cout,side,batches", [(128, 128, 9, 2), (256, 256, 8, 3), (128, 256, 7, 1), (256, 128, 10, 1),
+                                                  (64, 64, 9, 2), (64, 128, 8, 1), (128, 64, 8, 2)])
 def test_wide_bf16_on_dense_maps(sp, cin, cout, side, batches):
     # rows are not a multiple of the 256-row tile: ragged last tile; forward and both gradients
     conv_case(sp, full_cubes(side, batches), 1, 3, 1, 1, cin, cout, True, seed=77 + cin + side)
