@@ -4,6 +4,7 @@
 // per-cloud global average pooling, a linear layer and the mean softmax cross-entropy, each with its
 // backward pass.  All are streaming / reduction kernels over [N][C] row-major features; reductions are
 // two-level (per-block partial sums in fp32, combined in fp64 in a fixed order): no atomics, reproducible.
+#include <algorithm>
 #include <type_traits>
 
 #include "sp_internal.h"
@@ -386,7 +387,7 @@ __global__ __launch_bounds__(kThreads) void pool_partial_kernel(const int4* __re
 template <typename T>
 __global__ __launch_bounds__(kThreads) void pool_partial_vec_kernel(const int4* __restrict__ coords,
                                                                     const T* __restrict__ x, int64_t n, int c, int nb,
-                                                                    float* __restrict__ partial,
+                                                                    int slab, float* __restrict__ partial,
                                                                     int32_t* __restrict__ cnt_partial) {
     constexpr int kN = Vec<T>::kN;
     extern __shared__ float s_acc[];  // [lanes][nb][c] floats, then [lanes][nb] ints
@@ -396,8 +397,8 @@ __global__ __launch_bounds__(kThreads) void pool_partial_vec_kernel(const int4* 
     for (int i = threadIdx.x; i < lanes * nb * c; i += kThreads) s_acc[i] = 0.f;
     for (int i = threadIdx.x; i < lanes * nb; i += kThreads) s_cnt[i] = 0;
     __syncthreads();
-    const int64_t row_beg = (int64_t)blockIdx.x * kSlabRows;
-    const int64_t row_end = row_beg + kSlabRows < n ? row_beg + kSlabRows : n;
+    const int64_t row_beg = (int64_t)blockIdx.x * slab;
+    const int64_t row_end = row_beg + slab < n ? row_beg + slab : n;
     if (rl < lanes) {
         float acc[kN];
 #pragma unroll
@@ -660,17 +661,22 @@ int pool_fwd_typed(const int32_t* coords, const void* x, int64_t n, int c, int n
     const int cb = channel_block(c), ry = kThreads / cb;
     const size_t lds = (size_t)ry * nb * cb * 4 + (size_t)ry * nb * 4;
     if (lds > 64 * 1024) return fail(SP_ERR_UNSUPPORTED, "too many clouds for the pooling kernel (%d)", nb);
-    const int64_t nblk = (n + kSlabRows - 1) / kSlabRows;
-    Buf partial = dev_alloc((size_t)(nblk ? nblk : 1) * nb * c * 4);
-    Buf cnt = dev_alloc((size_t)(nblk ? nblk : 1) * nb * 4);
-    if (!partial || !cnt) return SP_ERR_ALLOC;
     constexpr int kN = 16 / (int)sizeof(T);
     const int vlanes = c % kN == 0 && c / kN <= kThreads ? kThreads / (c / kN) : 0;
     const size_t vlds = (size_t)vlanes * nb * c * 4 + (size_t)vlanes * nb * 4;
+    const bool vec = vlanes > 0 && vlds <= 64 * 1024 && ((uintptr_t)x & 15) == 0;
+    // rows per block: the vector kernel is latency bound per block, so it takes smaller slabs (more blocks),
+    // but no more than 1024 blocks for the final sums to add up
+    int64_t slab = kSlabRows;
+    if (vec) slab = std::max<int64_t>(128, (n + 1023) / 1024);
+    const int64_t nblk = (n + slab - 1) / slab;
+    Buf partial = dev_alloc((size_t)(nblk ? nblk : 1) * nb * c * 4);
+    Buf cnt = dev_alloc((size_t)(nblk ? nblk : 1) * nb * 4);
+    if (!partial || !cnt) return SP_ERR_ALLOC;
     if (nblk > 0) {
-        if (vlanes > 0 && vlds <= 64 * 1024 && ((uintptr_t)x & 15) == 0)
+        if (vec)
             hipLaunchKernelGGL(pool_partial_vec_kernel<T>, dim3((unsigned)nblk), dim3(kThreads), vlds, s,
-                               reinterpret_cast<const int4*>(coords), static_cast<const T*>(x), n, c, nb,
+                               reinterpret_cast<const int4*>(coords), static_cast<const T*>(x), n, c, nb, (int)slab,
                                ptr<float>(partial), ptr<int32_t>(cnt));
         else
             hipLaunchKernelGGL(pool_partial_kernel<T>, dim3((unsigned)nblk), dim3(kThreads), lds, s,
