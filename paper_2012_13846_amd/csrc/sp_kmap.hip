@@ -170,25 +170,33 @@ __global__ __launch_bounds__(kThreads) void class_emit_kernel(const int4* __rest
 // One thread per tile; the classes' stretches of perm start at off[cls * ntiles].
 __global__ __launch_bounds__(kThreads) void tile_mask_kernel(const int32_t* __restrict__ off, int64_t n, int64_t ntiles,
                                                              int K, int stride, uint32_t* __restrict__ mask) {
-    const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (t >= ntiles) return;
+    __shared__ uint32_t s_cm[32][4];   // offsets possible for each class
+    __shared__ int64_t s_beg[33];      // the classes' stretches of perm
     const int nclass = stride * stride * stride, centre = (K & 1) ? (K - 1) / 2 : 0;
-    const int64_t lo = t * kTileRows, hi = lo + kTileRows < n ? lo + kTileRows : n;
-    uint32_t m[4] = {0u, 0u, 0u, 0u};
-    for (int c = 0; c < nclass; ++c) {
-        const int64_t beg = off[(int64_t)c * ntiles], end = c + 1 < nclass ? off[(int64_t)(c + 1) * ntiles] : n;
-        if (beg >= hi || end <= lo) continue;
+    if (threadIdx.x < nclass) {
+        const int c = threadIdx.x;
         const int r[3] = {c / (stride * stride), c / stride % stride, c % stride};
+        uint32_t m[4] = {0u, 0u, 0u, 0u};
         for (int k = 0; k < K * K * K; ++k) {
             const int d[3] = {k / (K * K) - centre, k / K % K - centre, k % K - centre};
             bool ok = true;
             for (int ax = 0; ax < 3; ++ax) ok = ok && ((d[ax] % stride + stride) % stride == r[ax]);
             if (ok) m[k >> 5] |= 1u << (k & 31);
         }
+        for (int i = 0; i < 4; ++i) s_cm[c][i] = m[i];
+        s_beg[c] = off[(int64_t)c * ntiles];
+        if (c == nclass - 1) s_beg[nclass] = n;
     }
+    __syncthreads();
+    const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (t >= ntiles) return;
+    const int64_t lo = t * kTileRows, hi = lo + kTileRows < n ? lo + kTileRows : n;
+    uint32_t m[4] = {0u, 0u, 0u, 0u};
+    for (int c = 0; c < nclass; ++c)
+        if (s_beg[c] < hi && s_beg[c + 1] > lo)
+            for (int i = 0; i < 4; ++i) m[i] |= s_cm[c][i];
     for (int i = 0; i < 4; ++i) mask[t * 4 + i] = m[i];
 }
-
 
 // Rows of a strided map's input side sorted by position class, and the per-tile offset masks.
 int build_classes(MapSide& side, const sp_coords* c, int stride, int K, hipStream_t s) {
