@@ -21,7 +21,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint16_t bf16_t;
 
-__device__ __forceinline__ uint32_t bf16_bits(float f) {  // round to nearest even; NaN stays NaN
+__device__ __forceinline__ uint32_t bf16_bits(float f) {  // nearest-even rounding; NaN stays NaN
     const uint32_t u = __float_as_uint(f);
     if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40;
     return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
@@ -206,17 +206,17 @@ __global__ __launch_bounds__(kDenseThreads<COT>) void gather_dense_kernel(DenseA
         }
     };
 
-    // The loop runs over "rounds" of kRS = 2 or 4 steps.  For Cin >= 128 a round is one offset and its steps
-    // are the offset's 64-channel slices; for Cin = 64 a round is two offsets, one step each (the sum over
+    // The loop runs over "turns" of kRS = 2 or 4 steps.  For Cin >= 128 a turn is one offset and its steps
+    // are the offset's 64-channel slices; for Cin = 64 a turn is two offsets, one step each (the sum over
     // offsets and the sum over channels are one contraction, so a step is just 64 more columns of it).
-    // Step j of a round works out of LDS buffer j % 2.  The gathered rows have two register stages (they mostly
+    // Step j of a turn works out of LDS buffer j % 2.  The gathered rows have two register stages (they mostly
     // miss L2, and one step of arithmetic is shorter than that latency): during a step the rows of the step two
     // ahead are requested and those of the next step are stored to the other buffer.  The weight slices (L2
-    // hits) have kWDepth stages.  The neighbour entries are requested two rounds ahead.
+    // hits) have kWDepth stages.  The neighbour entries are requested two turns ahead.
     constexpr int kSPO = kSlices;                   // slices per offset: 1, 2 or 4
-    constexpr int kOPR = kSPO == 1 ? 2 : 1;         // offsets per round
-    constexpr int kRS = kSPO * kOPR;                // steps per round
-    static_assert(kRS % 2 == 0, "the register stage and LDS buffer of a step are its index in the round % 2");
+    constexpr int kOPR = kSPO == 1 ? 2 : 1;         // offsets per turn
+    constexpr int kRS = kSPO * kOPR;                // steps per turn
+    static_assert(kRS % 2 == 0, "the register stage and LDS buffer of a step are its index in the turn % 2");
     // The offsets to visit, ascending: all of them, or those of the tile's mask.  next_offset() hands them out
     // one by one and then kvol (for which every load reads zeros) for ever.
     uint32_t todo[4];
@@ -237,9 +237,9 @@ __global__ __launch_bounds__(kDenseThreads<COT>) void gather_dense_kernel(DenseA
             }
         return a.kvol;
     };
-    Where cur[kOPR], nxt[kOPR];  // the offsets of this round and of the next
-    int k_cur[kOPR];             // this round's offsets (kvol: none left)
-    int raw[kOPR][kXLoads];      // neighbour entries of the round after that, in flight
+    Where cur[kOPR], nxt[kOPR];  // the offsets of this turn and of the next
+    int k_cur[kOPR];             // this turn's offsets (kvol: none left)
+    int raw[kOPR][kXLoads];      // neighbour entries of the turn after that, in flight
     int k_raw[kOPR];
 #pragma unroll
     for (int o = 0; o < kOPR; ++o) {
@@ -260,7 +260,7 @@ __global__ __launch_bounds__(kDenseThreads<COT>) void gather_dense_kernel(DenseA
         load_nbr(k_raw[o], raw[o]);
     }
     u32x4 sx[2][kXLoads], sw[kWDepth][kWLoads];
-    // step j of this round (j < kRS) or of the next (j >= kRS): its offset's addresses and its slice
+    // step j of this turn (j < kRS) or of the next (j >= kRS): its offset's addresses and its slice
     auto where_of = [&](int j) -> const Where& { return j < kRS ? cur[j / kSPO] : nxt[(j - kRS) / kSPO]; };
 #pragma unroll
     for (int j = 0; j < kXLoads; ++j) load_x(sx[0], j, 0, where_of(0));
@@ -311,7 +311,7 @@ __global__ __launch_bounds__(kDenseThreads<COT>) void gather_dense_kernel(DenseA
     // the accumulators are read below by ordinary instructions: the MFMAs were written as opaque instructions,
     // so the wait states between the last of them and the first read are put in by hand (18 are required)
     asm volatile("s_nop 15\n s_nop 15" ::: "memory");
-    // round once, stage the tile in LDS, write whole rows
+    // one rounding to bf16, stage the tile in LDS, write whole rows
     unsigned char* out = smem;  // all staging reads are behind the last barrier
 #pragma unroll
     for (int ni = 0; ni < kNI; ++ni)
@@ -354,7 +354,7 @@ int launch_dense(const DenseArgs& a, hipStream_t s) {
 
 }  // namespace
 
-// Cin = 64: two offsets per round.  Its steps hold little arithmetic next to the gather latency, so it only
+// Cin = 64: two offsets per turn.  Its steps hold little arithmetic next to the gather latency, so it only
 // beats the link-list kernel on well-filled maps (see dense_min_fill).
 bool dense_shape_ok(int cc, int co, sp_dtype dt) {
     return dt == SP_BF16 && (cc == 64 || cc == 128 || cc == 256) && co % 64 == 0;
