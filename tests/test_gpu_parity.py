@@ -254,6 +254,23 @@ def test_wide_bf16_strided_maps_with_position_classes(sp, K, cin, cout, transpos
     conv_case(sp, full_cubes(side, 2), 1, K, 2, 1, cin, cout, True, seed=99 + K + cin, transposed=transposed)
 
 
+@pytest.mark.parametrize("K,stride,cin,cout,side,batches", [
+    (1, 1, 128, 128, 6, 1),      # one offset
+    (5, 1, 128, 64, 6, 1),       # 125 offsets: four mask words
+    (3, 3, 128, 128, 9, 1),      # stride 3: 27 position classes
+    (3, 4, 128, 64, 8, 1),       # stride 4: more classes than the class order handles, plain row order
+    (2, 1, 256, 128, 5, 2),      # even kernel at stride 1: two separate map sides
+])
+def test_wide_bf16_corner_shapes(sp, K, stride, cin, cout, side, batches):
+    conv_case(sp, full_cubes(side, batches), 1, K, stride, 1, cin, cout, True, seed=31 + K * 7 + stride)
+
+
+def test_wide_bf16_tiny_inputs(sp):
+    one = np.array([[0, 3, -2, 5]], np.int32)
+    conv_case(sp, one, 1, 3, 1, 1, 128, 128, True, seed=5)
+    conv_case(sp, random_coords(12, 257, 5, batches=1), 1, 3, 1, 1, 256, 256, True, seed=6)
+
+
 def test_identity_weights_reproduce_input_bit_exactly(sp):
     raw = spgen.coords_config(1, 0.2)
     c = sp.sp_coords_build(dev(raw), 1)
