@@ -18,6 +18,11 @@ __global__ __launch_bounds__(256) void fill_i32_kernel(int32_t* __restrict__ p, 
 // one thread are independent, so their memory latencies overlap, and the row's coordinates are read once.
 // Writes nbr_out[k][o]; scatters nbr_in[k][i] = o when nbr_in is given; counts live links per 64-row
 // half sub-tile (sub_counts[((tile*4 + wave)*kvol + k)*2 + half]) and per tile (blk_counts[k*ntiles + tile]).
+// identity_k >= 0 (stride 1, odd K; input and output rows are the same set): the centre offset is the
+// identity, and link (i, o) at offset k is link (o, i) at offset kvol-1-k, so only the offsets below the
+// centre are searched and each hit is also written to the mirrored entry nbr_out[kvol-1-k][i] = o.  The
+// entries above the centre that stay without a hit were set to -1 beforehand, and the counts come from a
+// separate pass over the table (count_kernel): sub_counts is null here.
 template <int K>
 __global__ __launch_bounds__(kThreads) void probe_kernel(const int4* __restrict__ c_out, int64_t n_out,
                                                          const HashSlot* __restrict__ tab, uint32_t cap, int step,
@@ -45,14 +50,18 @@ __global__ __launch_bounds__(kThreads) void probe_kernel(const int4* __restrict_
 #pragma unroll
         for (int az = 0; az < K; ++az) {
             if (k0 + az == identity_k) v[az] = (int32_t)o;
-            else if (ok[az]) v[az] = hash_find(tab, cap, key[az]);
+            else if (ok[az] && (identity_k < 0 || k0 + az < identity_k)) v[az] = hash_find(tab, cap, key[az]);
         }
 #pragma unroll
         for (int az = 0; az < K; ++az) {
+            if (identity_k >= 0 && k0 + az > identity_k) continue;  // written by the mirrored offset's hits
             nbr_out[(int64_t)(k0 + az) * n_out + o] = v[az];
             if (nbr_in && v[az] >= 0) nbr_in[(int64_t)(k0 + az) * n_in + v[az]] = (int32_t)o;
+            if (identity_k >= 0 && k0 + az < identity_k && v[az] >= 0)
+                nbr_out[(int64_t)(kvol - 1 - (k0 + az)) * n_out + v[az]] = (int32_t)o;
         }
     }
+    if (!sub_counts) return;  // uniform: the counts of a mirrored table are taken by count_kernel
     const int w = threadIdx.x >> 6;
 #pragma unroll
     for (int az = 0; az < K; ++az) {
@@ -73,7 +82,9 @@ __global__ __launch_bounds__(kThreads) void probe_kernel(const int4* __restrict_
 
 // Same counting from an existing table (the scattered input-side table of a strided map).
 __global__ __launch_bounds__(kThreads) void count_kernel(const int32_t* __restrict__ nbr, int64_t n_rows,
-                                                         int32_t* __restrict__ sub_counts) {
+                                                         int32_t* __restrict__ sub_counts,
+                                                         int32_t* __restrict__ blk_counts) {
+    __shared__ int s_cnt[kSubTiles];
     const int k = blockIdx.y, kvol = gridDim.y;
     const int64_t r = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     const int32_t v = r < n_rows ? nbr[(int64_t)k * n_rows + r] : -1;
@@ -82,7 +93,11 @@ __global__ __launch_bounds__(kThreads) void count_kernel(const int32_t* __restri
         int32_t* dst = sub_counts + (((int64_t)blockIdx.x * kSubTiles + (threadIdx.x >> 6)) * kvol + k) * kHalves;
         dst[0] = __popc((unsigned)live);
         dst[1] = __popc((unsigned)(live >> 32));
+        s_cnt[threadIdx.x >> 6] = __popcll(live);
     }
+    if (!blk_counts) return;  // uniform
+    __syncthreads();
+    if (threadIdx.x == 0) blk_counts[(int64_t)k * gridDim.x + blockIdx.x] = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
 }
 
 // Compaction: every live (row, k) writes its entry at offset + (number of live lanes below it).
@@ -302,13 +317,21 @@ int sp_kmap_build(const sp_coords_t* in, int32_t kernel_size, int32_t stride, in
     }
     int32_t* d_koff = ptr<int32_t>(small);
     if (nt_out > 0) {
-        const dim3 grid((unsigned)nt_out, (unsigned)(kernel_size * kernel_size));
         const int identity_k = symmetric ? (kvol - 1) / 2 : -1;
+        // mirrored table: only the (ax, ay) pairs that hold an offset up to the centre are launched, and the
+        // entries above the centre start as "no link"
+        const int pairs_xy = symmetric ? identity_k / kernel_size + 1 : kernel_size * kernel_size;
+        const dim3 grid((unsigned)nt_out, (unsigned)pairs_xy);
+        if (symmetric && kvol > 1)
+            hipLaunchKernelGGL(fill_i32_kernel, dim3(blocks256(n_out * (int64_t)(kvol - 1 - identity_k))), dim3(256), 0, s,
+                               ptr<int32_t>(so.nbr) + (int64_t)(identity_k + 1) * n_out,
+                               n_out * (int64_t)(kvol - 1 - identity_k), -1);
         int32_t* nbr_in_arg = symmetric ? (int32_t*)nullptr : ptr<int32_t>(si.nbr);
+        int32_t* sub_arg = symmetric ? (int32_t*)nullptr : ptr<int32_t>(so.tl_off);
 #define SP_LAUNCH_PROBE(KS)                                                                                     \
     hipLaunchKernelGGL(probe_kernel<KS>, grid, dim3(kThreads), 0, s, ptr<int4>(m->c_out->coords), n_out,          \
                        ptr<HashSlot>(in->tab.slots), in->tab.cap, step, identity_k, ptr<int32_t>(so.nbr), nbr_in_arg, \
-                       n_in, ptr<int32_t>(so.tl_off), ptr<int32_t>(blk))
+                       n_in, sub_arg, ptr<int32_t>(blk))
         switch (kernel_size) {
             case 1: SP_LAUNCH_PROBE(1); break;
             case 2: SP_LAUNCH_PROBE(2); break;
@@ -317,6 +340,9 @@ int sp_kmap_build(const sp_coords_t* in, int32_t kernel_size, int32_t stride, in
             default: SP_LAUNCH_PROBE(5); break;
         }
 #undef SP_LAUNCH_PROBE
+        if (symmetric)
+            hipLaunchKernelGGL(count_kernel, dim3((unsigned)nt_out, kvol), dim3(kThreads), 0, s, ptr<int32_t>(so.nbr),
+                               n_out, ptr<int32_t>(so.tl_off), ptr<int32_t>(blk));
     }
     SP_HIP(hipGetLastError());
     // both scans in one launch pair: sub-tile-major list offsets, and offset-major pair-list offsets whose
@@ -353,7 +379,7 @@ int sp_kmap_build(const sp_coords_t* in, int32_t kernel_size, int32_t stride, in
     } else {
         if (nt_in > 0)
             hipLaunchKernelGGL(count_kernel, dim3((unsigned)nt_in, kvol), dim3(kThreads), 0, s, ptr<int32_t>(si.nbr),
-                               n_in, ptr<int32_t>(si.tl_off));
+                               n_in, ptr<int32_t>(si.tl_off), (int32_t*)nullptr);
         const int64_t n_sub_in = nt_in * kvol * kSubTiles * kHalves;
         ScanJob job;
         job.data = ptr<int32_t>(si.tl_off);
