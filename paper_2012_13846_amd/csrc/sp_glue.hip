@@ -189,9 +189,10 @@ __global__ __launch_bounds__(kThreads) void column_sums_vec_kernel(const T* __re
                 rs[i] = rstd[cg * kN + i];
             }
         }
-        for (int64_t r = row_beg + rl; r < row_end; r += lanes) {
-            const size_t e = (size_t)r * c + (size_t)cg * kN;
-            const Vec<T> xv = load_vec(x, e);
+        auto raw = [&](const T* p, size_t e) { return *reinterpret_cast<const u32x4*>(p + e); };
+        auto add_row = [&](const u32x4& rx, const u32x4& rg, const u32x4& ry) __attribute__((always_inline)) {
+            Vec<T> xv, gv, yv;
+            unpack(rx, xv);
             if (MODE == 0) {
 #pragma unroll
                 for (int i = 0; i < kN; ++i) {
@@ -200,9 +201,8 @@ __global__ __launch_bounds__(kThreads) void column_sums_vec_kernel(const T* __re
                     s1[i] += v * v;
                 }
             } else {
-                const Vec<T> gv = load_vec(dy, e);
-                Vec<T> yv = gv;
-                if (relu) yv = load_vec(y, e);
+                unpack(rg, gv);
+                unpack(ry, yv);
 #pragma unroll
                 for (int i = 0; i < kN; ++i) {
                     float g = gv.v[i];
@@ -211,6 +211,31 @@ __global__ __launch_bounds__(kThreads) void column_sums_vec_kernel(const T* __re
                     s1[i] += g * (xv.v[i] - m[i]) * rs[i];
                 }
             }
+        };
+        // 4 rows' loads are requested before the first is used (the rows are still added in row order)
+        int64_t r = row_beg + rl;
+        for (; r + 3 * (int64_t)lanes < row_end; r += 4 * lanes) {
+            u32x4 rx[4], rg[4], ry[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const size_t e = (size_t)(r + u * lanes) * c + (size_t)cg * kN;
+                rx[u] = raw(x, e);
+                if (MODE == 1) {
+                    rg[u] = raw(dy, e);
+                    ry[u] = relu ? raw(y, e) : rg[u];
+                } else {
+                    rg[u] = ry[u] = rx[u];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) add_row(rx[u], rg[u], ry[u]);
+        }
+        for (; r < row_end; r += lanes) {
+            const size_t e = (size_t)r * c + (size_t)cg * kN;
+            const u32x4 rx = raw(x, e);
+            const u32x4 rg = MODE == 1 ? raw(dy, e) : rx;
+            const u32x4 ry = MODE == 1 && relu ? raw(y, e) : rg;
+            add_row(rx, rg, ry);
         }
 #pragma unroll
         for (int i = 0; i < kN; ++i) {
