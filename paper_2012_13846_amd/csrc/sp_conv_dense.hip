@@ -206,9 +206,9 @@ __global__ __launch_bounds__(kDenseThreads<COT>, (KS == 32 ? 2 : 1)) void gather
         }
     };
 
-    // The loop runs over "turns" of kRS = 2 or 4 steps.  For Cin >= 128 a turn is one offset and its steps
-    // are the offset's 64-channel slices; for Cin = 64 a turn is two offsets, one step each (the sum over
-    // offsets and the sum over channels are one contraction, so a step is just 64 more columns of it).
+    // The loop runs over "turns" of kRS = 2, 4 or 8 steps.  Normally a turn is one offset and its steps are
+    // the offset's slices; when an offset is a single slice, a turn is two offsets, one step each (the sum
+    // over offsets and the sum over channels are one contraction, so a step is just more columns of it).
     // Step j of a turn works out of LDS buffer j % 2.  The gathered rows have two register stages (they mostly
     // miss L2, and one step of arithmetic is shorter than that latency): during a step the rows of the step two
     // ahead are requested and those of the next step are stored to the other buffer.  The weight slices (L2
@@ -354,13 +354,13 @@ int launch_dense(const DenseArgs& a, hipStream_t s) {
 
 }  // namespace
 
-// Cin = 64: two offsets per turn.  Its steps hold little arithmetic next to the gather latency, so it only
-// beats the link-list kernel on well-filled maps (see dense_min_fill).
+// Cin = 64: its steps hold little arithmetic next to the gather latency, so it only beats the link-list
+// kernel on well-filled maps (see dense_min_fill).
 bool dense_shape_ok(int cc, int co, sp_dtype dt) {
     return dt == SP_BF16 && (cc == 64 || cc == 128 || cc == 256) && co % 64 == 0;
 }
 // smallest links / (rows * kvol) from which the row-stationary kernel is the faster one (measured)
-double dense_min_fill(int cc) { return cc == 64 ? 0.40 : 0.06; }
+double dense_min_fill(int cc) { return cc == 64 ? 0.28 : 0.06; }
 
 // d_w: [kvol][co][cc] (contraction index fastest).  Buffers must be smaller than 2 GiB.
 int conv_gather_dense(const MapSide& side, int kvol, const void* d_f, const void* d_w, void* d_g, int cc, int co,
@@ -391,8 +391,8 @@ int conv_gather_dense(const MapSide& side, int kvol, const void* d_f, const void
     SP_DENSE(128, 128, 32);
     SP_DENSE(128, 64, 32);
     SP_DENSE(64, 256, 64);
-    SP_DENSE(64, 128, 64);
-    SP_DENSE(64, 64, 64);
+    SP_DENSE(64, 128, 32);
+    SP_DENSE(64, 64, 32);
 #undef SP_DENSE
     return fail(SP_ERR_UNSUPPORTED, "no row-stationary kernel for %d -> %d channels", cc, co);
 }
