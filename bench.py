@@ -308,7 +308,11 @@ def main():
     fwd_s = e0.elapsed_time(e1) / reps * 1e-3
     km.close(), co.close(), c.close()
     traffic = MEASURED_TRAFFIC_BYTES.get(args.workload)
-    roofline = {"bound": "mfma", "kernel": "gather_wave_kernel (sp_conv_fwd)",
+    # which of the library's gather kernels sp_conv_fwd picks for this shape (same rule as csrc/sp_conv.hip)
+    fill = pairs / float(n_out * K ** 3)
+    dense = bf16 and cin in (64, 128, 256) and cout % 64 == 0 and stride == 1 and fill >= (0.28 if cin == 64 else 0.06)
+    kernel_name = "gather_dense_kernel" if dense else "gather_wave_kernel"
+    roofline = {"bound": "mfma", "kernel": kernel_name + " (sp_conv_fwd)",
                 "achieved": flops_conv / fwd_s / 1e12, "peak": peak, "unit": "TFLOP/s",
                 "frac": flops_conv / fwd_s / 1e12 / peak, "traffic": traffic,
                 "launch_us": round(fwd_s * 1e6, 2), "flops_per_launch": flops_conv}
