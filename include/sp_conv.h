@@ -58,7 +58,8 @@ typedef struct sp_kmap sp_kmap_t;     /* kernel map of one (coords, kernel, stri
  * Hashes d_raw [n_raw][4] into an open-addressing table, merges duplicate rows and numbers the
  * distinct rows in first-occurrence order (unique row r = r-th distinct coordinate met walking the
  * rows in order).  tensor_stride (>= 1) is recorded, coordinates are expected on that lattice.
- * Synchronises `stream` once (the count N comes back to the host).  n_raw may be 0.
+ * Blocks until the count N has come back to the host (everything but the filling of the inverse array, which
+ * may still be in flight on `stream` when the call returns, is complete by then).  n_raw may be 0.
  * *out receives a new handle (caller destroys).  d_raw is not referenced after the call returns. */
 int sp_coords_build(const int32_t* d_raw, int64_t n_raw, int32_t tensor_stride, void* stream, sp_coords_t** out);
 

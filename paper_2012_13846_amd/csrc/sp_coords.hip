@@ -194,11 +194,15 @@ int coords_build_impl(const int32_t* d_src, int64_t n_src, int32_t floor_step, i
         }
         hipLaunchKernelGGL(emit_first_kernel, dim3((unsigned)nb), dim3(kThreads), 0, s, src, n_src, floor_step, tab,
                            ptr<int32_t>(slot_of), ptr<int32_t>(block_counts), scanned, ptr<int4>(c->coords), d_small);
-        hipLaunchKernelGGL(inverse_kernel, dim3(blocks_for(n_src, kThreads)), dim3(kThreads), 0, s, tab,
-                           ptr<int32_t>(slot_of), n_src, ptr<int32_t>(c->inverse));
         SP_HIP(hipGetLastError());
     }
-    SP_TRY(read_back(host_small, d_small, 8, s));
+    // the host only waits for N; the inverse array is filled behind the read-back, while the host wakes up
+    SP_TRY(read_back(host_small, d_small, 8, s, [&]() {
+        if (n_src > 0)
+            hipLaunchKernelGGL(inverse_kernel, dim3(blocks_for(n_src, kThreads)), dim3(kThreads), 0, s, tab,
+                               ptr<int32_t>(slot_of), n_src, ptr<int32_t>(c->inverse));
+    }));
+    SP_HIP(hipGetLastError());
     if (host_small[1] & 1)
         return fail(SP_ERR_RANGE, "a coordinate is outside 0 <= b < 65536, -32768 <= x,y,z < 32768");
     if (host_small[1] & 2) return fail(SP_ERR_TABLE_FULL, "hash table overflow");

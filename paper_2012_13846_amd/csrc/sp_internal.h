@@ -7,6 +7,7 @@
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
+#include <functional>
 #include <memory>
 #include <vector>
 
@@ -47,7 +48,11 @@ int pool_trim();
 int64_t pool_bytes();
 
 // Pinned host staging area for small read-backs (one per process, guarded by a mutex inside).
-int read_back(void* h_dst, const void* d_src, size_t bytes, hipStream_t s);  // async copy + stream sync
+// Blocks until `bytes` at d_src, as of everything enqueued on s so far, are in h_dst.  `then_enqueue`, if given,
+// is called once the read-back itself is enqueued and before the host starts waiting: work that the caller
+// wants on the stream but whose result the host does not need runs while the host wakes up.
+int read_back(void* h_dst, const void* d_src, size_t bytes, hipStream_t s,
+              const std::function<void()>& then_enqueue = nullptr);
 
 // ---- hash table ---------------------------------------------------------------------------------------------
 struct HashTab {

@@ -165,8 +165,9 @@ __global__ __launch_bounds__(256) void mailbox_kernel(const uint32_t* __restrict
 }
 }  // namespace
 
-int read_back(void* h_dst, const void* d_src, size_t bytes, hipStream_t s) {
+int read_back(void* h_dst, const void* d_src, size_t bytes, hipStream_t s, const std::function<void()>& then_enqueue) {
     if (bytes == 0) {
+        if (then_enqueue) then_enqueue();
         SP_HIP(hipStreamSynchronize(s));
         return SP_OK;
     }
@@ -193,6 +194,7 @@ int read_back(void* h_dst, const void* d_src, size_t bytes, hipStream_t s) {
             hipLaunchKernelGGL(mailbox_kernel, dim3(1), dim3(256), 0, s, static_cast<const uint32_t*>(d_src),
                                (int)(bytes / 4), mb.d, seq);
             SP_HIP(hipGetLastError());
+            if (then_enqueue) then_enqueue();
             volatile uint32_t* flag = mb.h + kMailWords;
             // poll; every ~50 us of silence ask the runtime whether the stream has failed or finished
             for (uint64_t spins = 0;; ++spins) {
@@ -225,6 +227,7 @@ int read_back(void* h_dst, const void* d_src, size_t bytes, hipStream_t s) {
         st.bytes = want;
     }
     SP_HIP(hipMemcpyAsync(st.h, d_src, bytes, hipMemcpyDeviceToHost, s));
+    if (then_enqueue) then_enqueue();
     SP_HIP(hipStreamSynchronize(s));
     memcpy(h_dst, st.h, bytes);
     return SP_OK;
