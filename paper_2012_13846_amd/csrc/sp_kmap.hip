@@ -1,6 +1,8 @@
 // Kernel maps (Sec. III-B step 2): for every kernel offset the (input row, output row) pairs it links,
 // found by probing the input coordinate set's hash table, then compacted with wavefront ballots and
 // prefix sums into (a) offset-major pair lists and (b) tile-major lists for the gather-GEMM kernels.
+#include <algorithm>
+
 #include "sp_hash.h"
 #include "sp_internal.h"
 
@@ -237,6 +239,7 @@ int build_classes(MapSide& side, const sp_coords* c, int stride, int K, hipStrea
 }
 
 // Turns sub-tile counts (already in side.tl_off) into offsets and fills the tile lists.
+// `total`: the number of links, or any upper bound of it (the lists are then allocated larger than needed).
 int finish_side(MapSide& side, int kvol, int64_t total, const int32_t* d_blk_off, int32_t* d_pair_in,
                 int32_t* d_pair_out, hipStream_t s) {
     const int64_t ntiles = (side.n_rows + kTileRows - 1) / kTileRows;
@@ -360,19 +363,30 @@ int sp_kmap_build(const sp_coords_t* in, int32_t kernel_size, int32_t stride, in
         jobs[1].koff_n = kvol;
         SP_TRY(exclusive_scan_jobs(jobs, 2, s));
     }
+    // The host needs the pair counts (for its own bookkeeping and the callers'), the device does not: unless
+    // the lists would be huge, they are allocated for the most links there can be and the compaction is
+    // enqueued behind the read-back, so the GPU does not idle while the host wakes up and launches.
+    const int64_t most = std::min(n_out, n_in) * kvol;
+    const bool early = most * 14 <= ((int64_t)512 << 20);
+    int early_rc = SP_OK;
+    auto emit_out_side = [&](int64_t total) {
+        m->pair_in = dev_alloc((size_t)(total ? total : 1) * 4);
+        m->pair_out = dev_alloc((size_t)(total ? total : 1) * 4);
+        if (!m->pair_in || !m->pair_out) return (int)SP_ERR_ALLOC;
+        return finish_side(so, kvol, total, ptr<int32_t>(blk), ptr<int32_t>(m->pair_in), ptr<int32_t>(m->pair_out), s);
+    };
     std::vector<int32_t> h_koff(kvol + 1);
-    SP_TRY(read_back(h_koff.data(), d_koff, (size_t)(kvol + 1) * 4, s));
+    SP_TRY(read_back(h_koff.data(), d_koff, (size_t)(kvol + 1) * 4, s, [&]() {
+        if (early) early_rc = emit_out_side(most);
+    }));
+    SP_TRY(early_rc);
     m->koff.resize(kvol + 1);
     m->counts.resize(kvol);
     for (int k = 0; k <= kvol; ++k) m->koff[k] = h_koff[k];
     for (int k = 0; k < kvol; ++k) m->counts[k] = m->koff[k + 1] - m->koff[k];
     m->total = m->koff[kvol];
     m->d_koff = small;
-
-    m->pair_in = dev_alloc((size_t)(m->total ? m->total : 1) * 4);
-    m->pair_out = dev_alloc((size_t)(m->total ? m->total : 1) * 4);
-    if (!m->pair_in || !m->pair_out) return SP_ERR_ALLOC;
-    SP_TRY(finish_side(so, kvol, m->total, ptr<int32_t>(blk), ptr<int32_t>(m->pair_in), ptr<int32_t>(m->pair_out), s));
+    if (!early) SP_TRY(emit_out_side(m->total));
     if (symmetric) {
         si = so;  // same lists; the link (i, o) at offset k is the link (o, i) at offset kvol-1-k
         si.flip = true;
