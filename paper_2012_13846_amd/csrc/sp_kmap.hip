@@ -375,9 +375,26 @@ int sp_kmap_build(const sp_coords_t* in, int32_t kernel_size, int32_t stride, in
         if (!m->pair_in || !m->pair_out) return (int)SP_ERR_ALLOC;
         return finish_side(so, kvol, total, ptr<int32_t>(blk), ptr<int32_t>(m->pair_in), ptr<int32_t>(m->pair_out), s);
     };
+    // the input side of a map without the stride-1 symmetry: its own counts, list offsets, lists and classes
+    auto emit_in_side = [&](int64_t total) {
+        if (nt_in > 0)
+            hipLaunchKernelGGL(count_kernel, dim3((unsigned)nt_in, kvol), dim3(kThreads), 0, s, ptr<int32_t>(si.nbr),
+                               n_in, ptr<int32_t>(si.tl_off), (int32_t*)nullptr);
+        const int64_t n_sub_in = nt_in * kvol * kSubTiles * kHalves;
+        ScanJob job;
+        job.data = ptr<int32_t>(si.tl_off);
+        job.n = n_sub_in;
+        job.total = ptr<int32_t>(si.tl_off) + n_sub_in;
+        SP_TRY(exclusive_scan_jobs(&job, 1, s));
+        SP_TRY(finish_side(si, kvol, total, nullptr, nullptr, nullptr, s));
+        if (stride > 1) SP_TRY(build_classes(si, cin, stride, kernel_size, s));
+        return (int)SP_OK;
+    };
     std::vector<int32_t> h_koff(kvol + 1);
     SP_TRY(read_back(h_koff.data(), d_koff, (size_t)(kvol + 1) * 4, s, [&]() {
-        if (early) early_rc = emit_out_side(most);
+        if (!early) return;
+        early_rc = emit_out_side(most);
+        if (early_rc == SP_OK && !symmetric) early_rc = emit_in_side(most);
     }));
     SP_TRY(early_rc);
     m->koff.resize(kvol + 1);
@@ -390,18 +407,8 @@ int sp_kmap_build(const sp_coords_t* in, int32_t kernel_size, int32_t stride, in
     if (symmetric) {
         si = so;  // same lists; the link (i, o) at offset k is the link (o, i) at offset kvol-1-k
         si.flip = true;
-    } else {
-        if (nt_in > 0)
-            hipLaunchKernelGGL(count_kernel, dim3((unsigned)nt_in, kvol), dim3(kThreads), 0, s, ptr<int32_t>(si.nbr),
-                               n_in, ptr<int32_t>(si.tl_off), (int32_t*)nullptr);
-        const int64_t n_sub_in = nt_in * kvol * kSubTiles * kHalves;
-        ScanJob job;
-        job.data = ptr<int32_t>(si.tl_off);
-        job.n = n_sub_in;
-        job.total = ptr<int32_t>(si.tl_off) + n_sub_in;
-        SP_TRY(exclusive_scan_jobs(&job, 1, s));
-        SP_TRY(finish_side(si, kvol, m->total, nullptr, nullptr, nullptr, s));
-        if (stride > 1) SP_TRY(build_classes(si, cin, stride, kernel_size, s));
+    } else if (!early) {
+        SP_TRY(emit_in_side(m->total));
     }
     if (out_coords) {
         m->c_out->ref.fetch_add(1);
