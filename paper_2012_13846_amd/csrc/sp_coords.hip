@@ -75,16 +75,21 @@ __device__ __forceinline__ bool is_first(const HashSlot* __restrict__ tab, const
     return s >= 0 && tab[s].first == (int32_t)i;
 }
 
-// Block b counts the first occurrences among rows [b*1024, b*1024+1024).
+// Block b counts the first occurrences among rows [b*1024, b*1024+1024) and keeps them as one bit per row
+// (first_mask[row / 64]), so that the numbering pass does not have to look every row up in the table again.
 __global__ __launch_bounds__(kThreads) void count_first_kernel(const HashSlot* __restrict__ tab,
                                                                const int32_t* __restrict__ slot_of, int64_t n,
-                                                               int32_t* __restrict__ block_counts) {
+                                                               int32_t* __restrict__ block_counts,
+                                                               unsigned long long* __restrict__ first_mask) {
     __shared__ int s_cnt[kThreads / 64];
     const int64_t base = (int64_t)blockIdx.x * kBlockRows;
     int c = 0;
 #pragma unroll
-    for (int j = 0; j < kRowsPerThread; ++j)
-        c += __popcll(__ballot(is_first(tab, slot_of, base + j * kThreads + threadIdx.x, n)));
+    for (int j = 0; j < kRowsPerThread; ++j) {
+        const unsigned long long m = __ballot(is_first(tab, slot_of, base + j * kThreads + threadIdx.x, n));
+        if ((threadIdx.x & 63) == 0) first_mask[(base + j * kThreads + threadIdx.x) >> 6] = m;
+        c += __popcll(m);
+    }
     if ((threadIdx.x & 63) == 0) s_cnt[threadIdx.x >> 6] = c;
     __syncthreads();
     if (threadIdx.x == 0) block_counts[blockIdx.x] = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
@@ -97,6 +102,7 @@ __global__ __launch_bounds__(kThreads) void emit_first_kernel(const int4* __rest
                                                               int32_t floor_step, HashSlot* __restrict__ tab,
                                                               const int32_t* __restrict__ slot_of,
                                                               const int32_t* __restrict__ block_counts, int scanned,
+                                                              const unsigned long long* __restrict__ first_mask,
                                                               int4* __restrict__ coords, int32_t* __restrict__ total) {
     __shared__ int s_red[kThreads / 64];
     __shared__ int s_row[kRowsPerThread][kThreads / 64];
@@ -119,8 +125,8 @@ __global__ __launch_bounds__(kThreads) void emit_first_kernel(const int4* __rest
     int pos[kRowsPerThread];
 #pragma unroll
     for (int j = 0; j < kRowsPerThread; ++j) {
-        f[j] = is_first(tab, slot_of, base + j * kThreads + threadIdx.x, n);
-        const unsigned long long m = __ballot(f[j]);
+        const unsigned long long m = first_mask[(base + j * kThreads + threadIdx.x) >> 6];
+        f[j] = (m >> lane) & 1ull;
         pos[j] = __popcll(m & ((1ull << lane) - 1ull));
         if (lane == 0) s_row[j][w] = __popcll(m);
     }
@@ -171,8 +177,9 @@ int coords_build_impl(const int32_t* d_src, int64_t n_src, int32_t floor_step, i
     Buf slot_of = dev_alloc((size_t)(n_src ? n_src : 1) * 4);
     const int64_t nb = (n_src + kBlockRows - 1) / kBlockRows;
     Buf block_counts = dev_alloc((size_t)(nb ? nb : 1) * 4);
+    Buf first_mask = dev_alloc((size_t)(nb ? nb : 1) * (kBlockRows / 64) * 8);
     Buf small = dev_alloc(8);  // [0] total, [1] error bits
-    if (!c->tab.slots || !c->coords || !c->inverse || !slot_of || !block_counts || !small) return SP_ERR_ALLOC;
+    if (!c->tab.slots || !c->coords || !c->inverse || !slot_of || !block_counts || !first_mask || !small) return SP_ERR_ALLOC;
     HashSlot* tab = ptr<HashSlot>(c->tab.slots);
     int32_t* d_small = ptr<int32_t>(small);
 
@@ -183,7 +190,7 @@ int coords_build_impl(const int32_t* d_src, int64_t n_src, int32_t floor_step, i
         hipLaunchKernelGGL(insert_kernel, dim3(blocks_for(n_src, kThreads)), dim3(kThreads), 0, s, src, n_src,
                            floor_step, tab, cap, ptr<int32_t>(slot_of), d_small + 1);
         hipLaunchKernelGGL(count_first_kernel, dim3((unsigned)nb), dim3(kThreads), 0, s, tab, ptr<int32_t>(slot_of),
-                           n_src, ptr<int32_t>(block_counts));
+                           n_src, ptr<int32_t>(block_counts), ptr<unsigned long long>(first_mask));
         int scanned = 0;
         if (nb > 4096) {  // too many blocks for every block to add up its predecessors: scan the counts first
             ScanJob job;
@@ -193,7 +200,8 @@ int coords_build_impl(const int32_t* d_src, int64_t n_src, int32_t floor_step, i
             scanned = 1;
         }
         hipLaunchKernelGGL(emit_first_kernel, dim3((unsigned)nb), dim3(kThreads), 0, s, src, n_src, floor_step, tab,
-                           ptr<int32_t>(slot_of), ptr<int32_t>(block_counts), scanned, ptr<int4>(c->coords), d_small);
+                           ptr<int32_t>(slot_of), ptr<int32_t>(block_counts), scanned,
+                           ptr<unsigned long long>(first_mask), ptr<int4>(c->coords), d_small);
         SP_HIP(hipGetLastError());
     }
     // the host only waits for N; the inverse array is filled behind the read-back, while the host wakes up
