@@ -47,7 +47,7 @@ __global__ __launch_bounds__(kThreads) void fill_table_kernel(HashSlot* __restri
 
 // Every source row inserts its key; slot.first becomes the smallest source row carrying that key.
 __global__ __launch_bounds__(kThreads) void insert_kernel(const int4* __restrict__ src, int64_t n, int32_t floor_step,
-                                                          HashSlot* __restrict__ tab, uint32_t cap,
+                                                          HashSlot* __restrict__ tab, uint32_t cap, int zshift,
                                                           int32_t* __restrict__ slot_of, int32_t* __restrict__ err) {
     const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (i >= n) return;
@@ -58,7 +58,7 @@ __global__ __launch_bounds__(kThreads) void insert_kernel(const int4* __restrict
         slot_of[i] = -1;
         return;
     }
-    const int64_t slot = hash_insert(tab, cap, key);
+    const int64_t slot = hash_insert(tab, cap, zshift, key);
     if (slot < 0) {
         atomicOr(err, 2);
         slot_of[i] = -1;
@@ -171,6 +171,7 @@ int coords_build_impl(const int32_t* d_src, int64_t n_src, int32_t floor_step, i
     uint32_t cap = 1024;
     while ((int64_t)cap < 2 * n_src) cap <<= 1;
     c->tab.cap = cap;
+    for (int t = tensor_stride; t > 1; t >>= 1) ++c->tab.zshift;
     c->tab.slots = dev_alloc((size_t)cap * sizeof(HashSlot));
     c->coords = dev_alloc((size_t)(n_src ? n_src : 1) * 16);
     c->inverse = dev_alloc((size_t)(n_src ? n_src : 1) * 4);
@@ -188,7 +189,7 @@ int coords_build_impl(const int32_t* d_src, int64_t n_src, int32_t floor_step, i
     if (n_src > 0) {
         const int4* src = reinterpret_cast<const int4*>(d_src);
         hipLaunchKernelGGL(insert_kernel, dim3(blocks_for(n_src, kThreads)), dim3(kThreads), 0, s, src, n_src,
-                           floor_step, tab, cap, ptr<int32_t>(slot_of), d_small + 1);
+                           floor_step, tab, cap, c->tab.zshift, ptr<int32_t>(slot_of), d_small + 1);
         hipLaunchKernelGGL(count_first_kernel, dim3((unsigned)nb), dim3(kThreads), 0, s, tab, ptr<int32_t>(slot_of),
                            n_src, ptr<int32_t>(block_counts), ptr<unsigned long long>(first_mask));
         int scanned = 0;

@@ -1,7 +1,14 @@
 // Device-side open-addressing hash table on 64-bit packed coordinates (the GPU hashmap of Sec. III-B,
 // used for the insertions and searches of step 2).  One slot is 16 bytes {key, first, row}, so a search
-// resolves key and row with a single 16-byte access, and the 8 slots after the home slot share its
-// 128-byte line: with linear probing at load factor <= 0.5 a probe sequence almost always stays inside it.
+// resolves key and row with a single 16-byte access.
+//
+// The table is made of buckets of 4 slots (64 bytes).  Four coordinates that are neighbours along z (same b,
+// x, y, same z / (4 * lattice step)) hash to the same bucket and have the slot given by their position in
+// that group of four as home slot; collisions are resolved by plain linear probing over all slots, so the
+// table fills evenly even when the coordinates use one position only (a plane of constant z).  The kernel-map search
+// asks for a voxel's neighbours along z in one thread, so its 2-3 searches usually fall into one 64-byte line
+// instead of 2-3 random ones: these searches are bound by the rate of random line fetches.
+// zshift = floor(log2(lattice step)): which two bits of z number the four group members.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -37,10 +44,17 @@ __device__ __forceinline__ uint32_t hash_key(uint64_t k) {
     return (uint32_t)k;
 }
 
+// home bucket and slot position of a key (cap slots = cap / 4 buckets, cap a power of two >= 4)
+__device__ __forceinline__ void hash_home(uint64_t key, uint32_t cap, int zshift, uint32_t* bucket, uint32_t* pos) {
+    *pos = (uint32_t)(key >> zshift) & 3u;
+    *bucket = hash_key(key & ~(3ull << zshift)) & (cap / 4 - 1);
+}
+
 // Insert-or-find.  Returns the slot of `key`, or -1 if the table is full (never at load factor <= 0.5).
-__device__ __forceinline__ int64_t hash_insert(HashSlot* __restrict__ tab, uint32_t cap, uint64_t key) {
-    const uint32_t mask = cap - 1;
-    uint32_t slot = hash_key(key) & mask;
+__device__ __forceinline__ int64_t hash_insert(HashSlot* __restrict__ tab, uint32_t cap, int zshift, uint64_t key) {
+    uint32_t bucket, pos;
+    hash_home(key, cap, zshift, &bucket, &pos);
+    uint32_t slot = bucket * 4 + pos;
     for (uint32_t probe = 0; probe < cap; ++probe) {
         unsigned long long cur = tab[slot].key;
         if (cur == key) return slot;
@@ -48,21 +62,22 @@ __device__ __forceinline__ int64_t hash_insert(HashSlot* __restrict__ tab, uint3
             unsigned long long prev = atomicCAS(&tab[slot].key, (unsigned long long)kEmptyKey, (unsigned long long)key);
             if (prev == kEmptyKey || prev == key) return slot;
         }
-        slot = (slot + 1) & mask;
+        slot = (slot + 1) & (cap - 1);
     }
     return -1;
 }
 
 // Row number stored for `key`, or -1 when absent.  One 16-byte load per probed slot.
-__device__ __forceinline__ int32_t hash_find(const HashSlot* __restrict__ tab, uint32_t cap, uint64_t key) {
-    const uint32_t mask = cap - 1;
-    uint32_t slot = hash_key(key) & mask;
+__device__ __forceinline__ int32_t hash_find(const HashSlot* __restrict__ tab, uint32_t cap, int zshift, uint64_t key) {
+    uint32_t bucket, pos;
+    hash_home(key, cap, zshift, &bucket, &pos);
+    uint32_t slot = bucket * 4 + pos;
     for (uint32_t probe = 0; probe < cap; ++probe) {
         const uint4 raw = *reinterpret_cast<const uint4*>(&tab[slot]);
         const unsigned long long cur = ((unsigned long long)raw.y << 32) | raw.x;
         if (cur == key) return (int32_t)raw.w;
         if (cur == kEmptyKey) return -1;
-        slot = (slot + 1) & mask;
+        slot = (slot + 1) & (cap - 1);
     }
     return -1;
 }

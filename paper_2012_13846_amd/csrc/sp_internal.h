@@ -58,6 +58,7 @@ int read_back(void* h_dst, const void* d_src, size_t bytes, hipStream_t s,
 struct HashTab {
     Buf slots;         // HashSlot [cap] (sp_hash.h): 16 bytes {key, first source row, row number}
     uint32_t cap = 0;  // power of two, >= 2 * entries
+    int zshift = 0;    // floor(log2(tensor stride)): see sp_hash.h
 };
 
 // ---- device-wide exclusive scans of int32 (sp_scan.hip) --------------------------------------------------------

@@ -27,7 +27,7 @@ __global__ __launch_bounds__(256) void fill_i32_kernel(int32_t* __restrict__ p, 
 // separate pass over the table (count_kernel): sub_counts is null here.
 template <int K>
 __global__ __launch_bounds__(kThreads) void probe_kernel(const int4* __restrict__ c_out, int64_t n_out,
-                                                         const HashSlot* __restrict__ tab, uint32_t cap, int step,
+                                                         const HashSlot* __restrict__ tab, uint32_t cap, int zshift, int step,
                                                          int identity_k, int32_t* __restrict__ nbr_out,
                                                          int32_t* __restrict__ nbr_in, int64_t n_in,
                                                          int32_t* __restrict__ sub_counts,
@@ -52,7 +52,7 @@ __global__ __launch_bounds__(kThreads) void probe_kernel(const int4* __restrict_
 #pragma unroll
         for (int az = 0; az < K; ++az) {
             if (k0 + az == identity_k) v[az] = (int32_t)o;
-            else if (ok[az] && (identity_k < 0 || k0 + az < identity_k)) v[az] = hash_find(tab, cap, key[az]);
+            else if (ok[az] && (identity_k < 0 || k0 + az < identity_k)) v[az] = hash_find(tab, cap, zshift, key[az]);
         }
 #pragma unroll
         for (int az = 0; az < K; ++az) {
@@ -333,7 +333,7 @@ int sp_kmap_build(const sp_coords_t* in, int32_t kernel_size, int32_t stride, in
         int32_t* sub_arg = symmetric ? (int32_t*)nullptr : ptr<int32_t>(so.tl_off);
 #define SP_LAUNCH_PROBE(KS)                                                                                     \
     hipLaunchKernelGGL(probe_kernel<KS>, grid, dim3(kThreads), 0, s, ptr<int4>(m->c_out->coords), n_out,          \
-                       ptr<HashSlot>(in->tab.slots), in->tab.cap, step, identity_k, ptr<int32_t>(so.nbr), nbr_in_arg, \
+                       ptr<HashSlot>(in->tab.slots), in->tab.cap, in->tab.zshift, step, identity_k, ptr<int32_t>(so.nbr), nbr_in_arg, \
                        n_in, sub_arg, ptr<int32_t>(blk))
         switch (kernel_size) {
             case 1: SP_LAUNCH_PROBE(1); break;
