@@ -49,10 +49,46 @@ __global__ __launch_bounds__(kThreads) void probe_kernel(const int4* __restrict_
         for (int az = 0; az < K; ++az)
             ok[az] = pack_key(c.x, c.y + (ax - centre) * step, c.z + (ay - centre) * step, c.w + (az - centre) * step,
                               &key[az]);
+        // The K searches advance in lockstep: every turn issues the next slot's load of all searches still
+        // running and only then looks at the answers, so their memory latencies overlap (run one after the
+        // other, each search costs as many round trips as the longest probe sequence among the 64 lanes).
+        uint32_t slot[K];
+        bool run[K];
+        bool any = false;
 #pragma unroll
         for (int az = 0; az < K; ++az) {
-            if (k0 + az == identity_k) v[az] = (int32_t)o;
-            else if (ok[az] && (identity_k < 0 || k0 + az < identity_k)) v[az] = hash_find(tab, cap, zshift, key[az]);
+            run[az] = false;
+            slot[az] = 0;
+            if (k0 + az == identity_k) {
+                v[az] = (int32_t)o;
+            } else if (ok[az] && (identity_k < 0 || k0 + az < identity_k)) {
+                uint32_t bucket, pos;
+                hash_home(key[az], cap, zshift, &bucket, &pos);
+                slot[az] = bucket * 4 + pos;
+                run[az] = true;
+                any = true;
+            }
+        }
+        for (uint32_t turn = 0; any && turn < cap; ++turn) {
+            uint4 raw[K];
+#pragma unroll
+            for (int az = 0; az < K; ++az)
+                if (run[az]) raw[az] = *reinterpret_cast<const uint4*>(&tab[slot[az]]);
+            any = false;
+#pragma unroll
+            for (int az = 0; az < K; ++az) {
+                if (!run[az]) continue;
+                const unsigned long long cur = ((unsigned long long)raw[az].y << 32) | raw[az].x;
+                if (cur == key[az]) {
+                    v[az] = (int32_t)raw[az].w;
+                    run[az] = false;
+                } else if (cur == kEmptyKey) {
+                    run[az] = false;
+                } else {
+                    slot[az] = (slot[az] + 1) & (cap - 1);
+                    any = true;
+                }
+            }
         }
 #pragma unroll
         for (int az = 0; az < K; ++az) {
