@@ -48,7 +48,7 @@ __global__ __launch_bounds__(kThreads) void fill_table_kernel(HashSlot* __restri
 // Every source row inserts its key; slot.first becomes the smallest source row carrying that key.
 __global__ __launch_bounds__(kThreads) void insert_kernel(const int4* __restrict__ src, int64_t n, int32_t floor_step,
                                                           HashSlot* __restrict__ tab, uint32_t cap, int zshift,
-                                                          int32_t* __restrict__ slot_of, int32_t* __restrict__ err) {
+                                                          int32_t* __restrict__ slot_of, int32_t* __restrict__ err, int always) {
     const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (i >= n) return;
     const int4 c = load_row(src, i, floor_step);
@@ -58,13 +58,17 @@ __global__ __launch_bounds__(kThreads) void insert_kernel(const int4* __restrict
         slot_of[i] = -1;
         return;
     }
-    const int64_t slot = hash_insert(tab, cap, zshift, key);
+    bool fresh;
+    const int64_t slot = hash_insert(tab, cap, zshift, key, &fresh);
     if (slot < 0) {
         atomicOr(err, 2);
         slot_of[i] = -1;
         return;
     }
-    atomicMin(&tab[slot].first, (int32_t)i);
+    // A duplicate that sees a smaller row already recorded has nothing to add (the value only ever decreases).
+    // Looking first costs a round trip and saves an atomic: measured 5 us slower on 157 k rows, 50 us faster
+    // on 4.1 M rows (where the atomics' throughput binds), so the host asks for it from 1 M rows (always = 0).
+    if (always || fresh || __builtin_nontemporal_load(&tab[slot].first) > (int32_t)i) atomicMin(&tab[slot].first, (int32_t)i);
     slot_of[i] = (int32_t)slot;
 }
 
@@ -189,7 +193,7 @@ int coords_build_impl(const int32_t* d_src, int64_t n_src, int32_t floor_step, i
     if (n_src > 0) {
         const int4* src = reinterpret_cast<const int4*>(d_src);
         hipLaunchKernelGGL(insert_kernel, dim3(blocks_for(n_src, kThreads)), dim3(kThreads), 0, s, src, n_src,
-                           floor_step, tab, cap, c->tab.zshift, ptr<int32_t>(slot_of), d_small + 1);
+                           floor_step, tab, cap, c->tab.zshift, ptr<int32_t>(slot_of), d_small + 1, n_src < (1 << 20) ? 1 : 0);
         hipLaunchKernelGGL(count_first_kernel, dim3((unsigned)nb), dim3(kThreads), 0, s, tab, ptr<int32_t>(slot_of),
                            n_src, ptr<int32_t>(block_counts), ptr<unsigned long long>(first_mask));
         int scanned = 0;

@@ -51,15 +51,19 @@ __device__ __forceinline__ void hash_home(uint64_t key, uint32_t cap, int zshift
 }
 
 // Insert-or-find.  Returns the slot of `key`, or -1 if the table is full (never at load factor <= 0.5).
-__device__ __forceinline__ int64_t hash_insert(HashSlot* __restrict__ tab, uint32_t cap, int zshift, uint64_t key) {
+// *fresh: this call put the key in (otherwise it was there, or arrived from another thread meanwhile).
+__device__ __forceinline__ int64_t hash_insert(HashSlot* __restrict__ tab, uint32_t cap, int zshift, uint64_t key,
+                                               bool* fresh) {
     uint32_t bucket, pos;
     hash_home(key, cap, zshift, &bucket, &pos);
     uint32_t slot = bucket * 4 + pos;
+    *fresh = false;
     for (uint32_t probe = 0; probe < cap; ++probe) {
         unsigned long long cur = tab[slot].key;
         if (cur == key) return slot;
         if (cur == kEmptyKey) {
             unsigned long long prev = atomicCAS(&tab[slot].key, (unsigned long long)kEmptyKey, (unsigned long long)key);
+            *fresh = prev == kEmptyKey;
             if (prev == kEmptyKey || prev == key) return slot;
         }
         slot = (slot + 1) & (cap - 1);
