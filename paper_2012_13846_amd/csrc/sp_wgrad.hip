@@ -485,9 +485,12 @@ int launch_staged(const sp_kmap* m, const void* x, const void* dy, int cin, int 
     for (int k = 0; k <= kvol; ++k) pa.koff[k] = (int32_t)m->koff[k];
     // Strips: about 1.5 MB of rows (both operands) each, but long enough that an offset's stretch in a strip
     // (which costs a partial block of per * 4 bytes) has at least ~1024 links or per / 32 of them.
-    int occ = 1;
-    SP_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kern, Cfg::kThreads, Cfg::kLds));
-    occ = occ < 1 ? 1 : occ;
+    static int occ = 0;  // workgroups of this kernel that fit a CU: asked once
+    if (occ == 0) {
+        int q = 1;
+        SP_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&q, kern, Cfg::kThreads, Cfg::kLds));
+        occ = q < 1 ? 1 : q;
+    }
     const int64_t rows_bytes = (m->n_in * (int64_t)cin + m->n_out * (int64_t)cout) * (int64_t)sizeof(T);
     const int64_t stretch = std::max<int64_t>(1024, per / 32);
     int64_t M = std::min<int64_t>((rows_bytes / 8 + (3 << 18)) / (3 << 19), m->total / (8 * kvol * stretch));
