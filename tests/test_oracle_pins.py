@@ -430,3 +430,25 @@ def test_glue_closed_forms():
     want = np.full((B, m), 1.0 / m)
     want[np.arange(B), labels] -= 1.0
     assert np.allclose(d, want / B)
+
+
+@pytest.mark.parametrize("K,stride,ts", [(3, 2, 1), (2, 2, 1), (3, 3, 1), (3, 2, 2), (5, 2, 1)])
+def test_strided_links_follow_the_position_class(K, stride, ts):
+    """In a strided map an input voxel at residue r (its lattice position modulo the stride, per axis) can only be
+    linked by offsets whose displacement is congruent to r modulo the stride: the output coordinates are multiples
+    of the stride.  (The GPU path orders the input rows of strided maps by that residue and skips the other
+    offsets; this pins the property on the oracle's maps.)"""
+    rng = np.random.default_rng(100 + K * 10 + stride)
+    raw = np.concatenate([rng.integers(0, 2, (4000, 1)), rng.integers(-12, 12, (4000, 3)) * ts], 1).astype(np.int32)
+    c_in, _ = oracle.unique_coords(raw)
+    c_out, _, ts_out = oracle.strided_coords(c_in, ts, stride)
+    pin, pout, counts = oracle.kernel_map(c_in, c_out, K, ts)
+    assert counts.sum() > 0
+    centre = (K - 1) // 2 if K % 2 else 0
+    k = np.repeat(np.arange(K ** 3), counts)
+    d = np.stack([k // (K * K) - centre, (k // K) % K - centre, k % K - centre], 1)
+    r = (c_in[pin][:, 1:] // ts) % stride            # numpy's floor modulo
+    assert np.array_equal(d % stride, r)
+    # and for an even kernel as wide as the stride (offsets 0 .. K-1) the class fixes the offset completely
+    if K == stride and K % 2 == 0:
+        assert np.array_equal(d, r)
