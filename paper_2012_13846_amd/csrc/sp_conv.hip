@@ -663,7 +663,7 @@ int conv_gather(const MapSide& side, int kvol, int64_t total_links, const void* 
     const size_t elt = dt == SP_F32 ? 4 : 2;
     // Row-stationary kernel: it multiplies all kvol offsets of every row, the link-list kernels only the links
     // that exist but pay per link for bookkeeping, weight re-reads and the accumulator update.  Measured, it is
-    // the faster one from about 1 link in 20 row-offsets upwards on 128- and 256-channel inputs, from 28 in 100
+    // the faster one from about 1 link in 20 row-offsets upwards on 128- and 256-channel inputs, from 1 in 4
     // on 64-channel inputs.
     const uint64_t lim = 0x7fffffffull;
     const double min_fill = dense_min_fill(cc);

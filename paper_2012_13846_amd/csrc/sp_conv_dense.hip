@@ -360,7 +360,7 @@ bool dense_shape_ok(int cc, int co, sp_dtype dt) {
     return dt == SP_BF16 && (cc == 64 || cc == 128 || cc == 256) && co % 64 == 0;
 }
 // smallest links / (rows * kvol) from which the row-stationary kernel is the faster one (measured)
-double dense_min_fill(int cc) { return cc == 64 ? 0.28 : 0.06; }
+double dense_min_fill(int cc) { return cc == 64 ? 0.25 : 0.06; }
 
 // d_w: [kvol][co][cc] (contraction index fastest).  Buffers must be smaller than 2 GiB.
 int conv_gather_dense(const MapSide& side, int kvol, const void* d_f, const void* d_w, void* d_g, int cc, int co,
