@@ -468,13 +468,13 @@ __global__ __launch_bounds__(kThreads) void pool_partial_vec_kernel(const int4* 
     }
 }
 
-__global__ __launch_bounds__(kThreads) void pool_final_kernel(const float* __restrict__ partial,
+__global__ __launch_bounds__(1024) void pool_final_kernel(const float* __restrict__ partial,
                                                               const int32_t* __restrict__ cnt_partial, int64_t nblk,
                                                               int c, int nb, float* __restrict__ out,
                                                               float* __restrict__ counts) {
-    // block = 32 (cloud, channel) elements x 8 slices of the row blocks; slices are added in order
-    __shared__ double red[8][32];
-    __shared__ long long redc[8][32];
+    // block = 32 (cloud, channel) elements x 32 slices of the row blocks; slices are added in order
+    __shared__ double red[32][32];
+    __shared__ long long redc[32][32];
     const int ex = threadIdx.x & 31, slice = threadIdx.x >> 5;
     const int i = blockIdx.x * 32 + ex;
     const bool live = i < nb * c;
@@ -482,7 +482,7 @@ __global__ __launch_bounds__(kThreads) void pool_final_kernel(const float* __res
     double s = 0.0;
     long long cnt = 0;
     if (live)
-        for (int64_t k = slice; k < nblk; k += 8) {
+        for (int64_t k = slice; k < nblk; k += 32) {
             s += (double)partial[(size_t)k * nb * c + i];
             cnt += cnt_partial[(size_t)k * nb + b];
         }
@@ -490,7 +490,7 @@ __global__ __launch_bounds__(kThreads) void pool_final_kernel(const float* __res
     redc[slice][ex] = cnt;
     __syncthreads();
     if (slice != 0 || !live) return;
-    for (int j = 1; j < 8; ++j) {
+    for (int j = 1; j < 32; ++j) {
         s += red[j][ex];
         cnt += redc[j][ex];
     }
@@ -511,6 +511,27 @@ __global__ __launch_bounds__(kThreads) void pool_bwd_kernel(const int4* __restri
         float v = 0.f;
         if ((unsigned)b < (unsigned)nb) v = dout[(size_t)b * c + ch] / fmaxf(counts[b], 1.f);
         st(dx, i, v);
+    }
+}
+
+// 16-byte-vector version: one thread per 16 bytes of dx
+template <typename T>
+__global__ __launch_bounds__(kThreads) void pool_bwd_vec_kernel(const int4* __restrict__ coords,
+                                                                const float* __restrict__ dout,
+                                                                const float* __restrict__ counts, T* __restrict__ dx,
+                                                                int64_t n, int c, int nb) {
+    constexpr int kN = Vec<T>::kN;
+    const int tpr = c / kN;
+    const int64_t chunks = n * tpr;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < chunks; i += (int64_t)gridDim.x * kThreads) {
+        const int64_t r = i / tpr;
+        const int ch = (int)(i % tpr) * kN;
+        const int b = coords[r].x;
+        Vec<T> o;
+        const bool live = (unsigned)b < (unsigned)nb;
+#pragma unroll
+        for (int j = 0; j < kN; ++j) o.v[j] = live ? dout[(size_t)b * c + ch + j] / fmaxf(counts[b], 1.f) : 0.f;
+        *reinterpret_cast<u32x4*>(dx + (size_t)i * kN) = pack(o);
     }
 }
 
@@ -708,7 +729,7 @@ int pool_fwd_typed(const int32_t* coords, const void* x, int64_t n, int c, int n
                                reinterpret_cast<const int4*>(coords), static_cast<const T*>(x), n, c, nb,
                                ptr<float>(partial), ptr<int32_t>(cnt));
     }
-    hipLaunchKernelGGL(pool_final_kernel, dim3((nb * c + 31) / 32), dim3(kThreads), 0, s, ptr<float>(partial),
+    hipLaunchKernelGGL(pool_final_kernel, dim3((nb * c + 31) / 32), dim3(1024), 0, s, ptr<float>(partial),
                        ptr<int32_t>(cnt), nblk, c, nb, out, counts);
     SP_HIP(hipGetLastError());
     return SP_OK;
@@ -763,9 +784,19 @@ int sp_pool_avg_bwd(const int32_t* d_coords, const float* d_dout, const float* d
         return fail(SP_ERR_INVALID_ARG, "bad cloud count or NULL pointer");
     if (n == 0) return SP_OK;
     hipStream_t s = (hipStream_t)stream;
-    if (dt == SP_F32)
+    const int kn = dt == SP_F32 ? 4 : 8;
+    const bool vec = c % kn == 0 && ((uintptr_t)d_dx & 15) == 0;
+    if (dt == SP_F32 && vec)
+        hipLaunchKernelGGL(pool_bwd_vec_kernel<float>, dim3(stream_blocks(n * c / kn)), dim3(kThreads), 0, s,
+                           reinterpret_cast<const int4*>(d_coords), d_dout, d_counts, static_cast<float*>(d_dx), n, c,
+                           n_clouds);
+    else if (dt == SP_F32)
         hipLaunchKernelGGL(pool_bwd_kernel<float>, dim3(stream_blocks(n * c)), dim3(kThreads), 0, s,
                            reinterpret_cast<const int4*>(d_coords), d_dout, d_counts, static_cast<float*>(d_dx), n, c,
+                           n_clouds);
+    else if (vec)
+        hipLaunchKernelGGL(pool_bwd_vec_kernel<bf16_t>, dim3(stream_blocks(n * c / kn)), dim3(kThreads), 0, s,
+                           reinterpret_cast<const int4*>(d_coords), d_dout, d_counts, static_cast<bf16_t*>(d_dx), n, c,
                            n_clouds);
     else
         hipLaunchKernelGGL(pool_bwd_kernel<bf16_t>, dim3(stream_blocks(n * c)), dim3(kThreads), 0, s,
