@@ -179,6 +179,21 @@ __device__ __forceinline__ int cell_class(const int4& c, int ts, int stride) {
     return (r(c.y) * stride + r(c.z)) * stride + r(c.w);
 }
 
+// Even kernel as wide as the stride (offsets 0 .. K-1 = the positions inside a coarse cell): every input row
+// has exactly one link, to its own coarse cell (parent[i], from the coarse coordinates' merge), at the offset
+// that is its position in the cell.  No searches.
+__global__ __launch_bounds__(kThreads) void child_map_kernel(const int4* __restrict__ c_in, int64_t n_in, int ts,
+                                                             int stride, const int32_t* __restrict__ parent,
+                                                             int64_t n_out, int32_t* __restrict__ nbr_out,
+                                                             int32_t* __restrict__ nbr_in) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= n_in) return;
+    const int k = cell_class(c_in[i], ts, stride);
+    const int32_t o = parent[i];
+    nbr_in[(int64_t)k * n_in + i] = o;
+    nbr_out[(int64_t)k * n_out + o] = (int32_t)i;
+}
+
 // cnt[cls * ntiles + tile] = rows of the tile in class cls (tiles of 256 rows in row order)
 __global__ __launch_bounds__(kThreads) void class_count_kernel(const int4* __restrict__ coords, int64_t n, int ts,
                                                                int stride, int nclass, int32_t* __restrict__ cnt) {
@@ -355,7 +370,16 @@ int sp_kmap_build(const sp_coords_t* in, int32_t kernel_size, int32_t stride, in
                                n_in * kvol, -1);
     }
     int32_t* d_koff = ptr<int32_t>(small);
-    if (nt_out > 0) {
+    const bool children = stride > 1 && kernel_size == stride && kernel_size % 2 == 0;
+    if (nt_out > 0 && children) {
+        hipLaunchKernelGGL(fill_i32_kernel, dim3(blocks256(n_out * (int64_t)kvol)), dim3(256), 0, s, ptr<int32_t>(so.nbr),
+                           n_out * (int64_t)kvol, -1);
+        hipLaunchKernelGGL(child_map_kernel, dim3(blocks256(n_in)), dim3(kThreads), 0, s, ptr<int4>(in->coords), n_in,
+                           in->ts, stride, ptr<int32_t>(m->c_out->inverse), n_out, ptr<int32_t>(so.nbr),
+                           ptr<int32_t>(si.nbr));
+        hipLaunchKernelGGL(count_kernel, dim3((unsigned)nt_out, kvol), dim3(kThreads), 0, s, ptr<int32_t>(so.nbr), n_out,
+                           ptr<int32_t>(so.tl_off), ptr<int32_t>(blk));
+    } else if (nt_out > 0) {
         const int identity_k = symmetric ? (kvol - 1) / 2 : -1;
         // mirrored table: only the (ax, ay) pairs that hold an offset up to the centre are launched, and the
         // entries above the centre start as "no link"
