@@ -27,12 +27,14 @@
  *     borrowed and die with the handle.  Feature / weight / gradient buffers are
  *     owned by the caller and must stay alive until the stream passed the call.
  *   - All calls that touch one handle must use the same stream (or be ordered by
- *     the caller).  Coordinates must satisfy 0 <= b < 65536 and
+ *     the caller).  Different handles may be driven from different streams and
+ *     host threads at the same time.  Coordinates must satisfy 0 <= b < 65536 and
  *     -32768 <= x,y,z < 32768, else SP_ERR_RANGE.
  */
 #ifndef SP_CONV_H
 #define SP_CONV_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -112,7 +114,11 @@ int sp_kmap_destroy(sp_kmap_t* m);
  * cin / cout are N_in / N_out of W[kvol][cout][cin].  dt is the storage type of x, w, y, dy, dx
  * (SP_BF16: 16-bit bfloat16, results rounded to nearest even once); accumulation is always fp32.
  * Outputs are overwritten (rows / offsets without pairs become zero).  No host synchronisation.
- * Channel counts that are multiples of 16 run on the matrix cores; others on a plain kernel.
+ * All feature / weight / gradient pointers must be 16-byte aligned (SP_ERR_INVALID_ARG otherwise).
+ * Matrix-core kernels exist for: forward / data gradient with a contraction width (cin for the forward pass,
+ * cout for the data gradient) of 16 (fp32 only), 32, 64, 128 or 256 and the other width a multiple of 16;
+ * weight gradient with both widths multiples of 16.  Every other channel count runs on a plain
+ * one-thread-per-output kernel (correct, slow).
  *
  *   sp_conv_fwd:        y[o,:]  = sum_k sum_{(i,o) in M_k} W_k   x[i,:]      x [n_in][cin]   -> y  [n_out][cout]
  *   sp_conv_bwd_data:   dx[i,:] = sum_k sum_{(i,o) in M_k} W_k^T dy[o,:]     dy [n_out][cout] -> dx [n_in][cin]
@@ -166,8 +172,24 @@ int sp_softmax_ce(const float* d_logits, const int32_t* d_labels, int32_t n_clou
 
 /* ---- housekeeping -------------------------------------------------------------------------------------- */
 const char* sp_last_error(void);  /* message of the calling thread's last failure ("" if none) */
+
+/* Device memory.  By default handles and per-call scratch come from a caching pool inside the library
+ * (hipMalloc on a miss; a freed block is reused at once by the stream that used it last, and by another
+ * stream only after that stream has been made to wait for the first).  sp_set_allocator installs the caller's
+ * allocator instead (for instance a framework's caching allocator, so that one allocator owns all device
+ * memory): alloc(bytes, stream, ctx) returns device memory, at least 256-byte aligned, that may be used by
+ * work enqueued on `stream` from now on, or NULL on failure (reported as SP_ERR_ALLOC); free_(ptr, ctx) is
+ * called when the library drops the block, possibly while the last kernels using it are still in flight on
+ * the stream it was allocated for (the semantics of stream-ordered caching allocators).  Both callbacks may
+ * be called from any thread that calls the library.  Blocks taken from an allocator go back to that same
+ * allocator even if another one has been installed since.  NULL, NULL restores the pool. */
+typedef void* (*sp_alloc_fn)(size_t bytes, void* stream, void* ctx);
+typedef void (*sp_free_fn)(void* ptr, void* ctx);
+int sp_set_allocator(sp_alloc_fn alloc, sp_free_fn free_, void* ctx);
+
 int sp_pool_trim(void);           /* synchronises the device and frees all cached (unused) device memory */
 int64_t sp_pool_bytes(void);      /* device bytes currently held by the pool (in use + cached) */
+int64_t sp_pool_cross_stream(void); /* blocks handed from one stream to another so far (diagnostics) */
 const char* sp_version(void);
 
 #ifdef __cplusplus

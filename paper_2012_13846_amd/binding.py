@@ -234,6 +234,57 @@ def sp_pool_trim():
     _check(lib().sp_pool_trim())
 
 
+def sp_pool_cross_stream() -> int:
+    l = lib()
+    l.sp_pool_cross_stream.restype = C.c_int64
+    return int(l.sp_pool_cross_stream())
+
+
+_ALLOC_T = C.CFUNCTYPE(C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p)
+_FREE_T = C.CFUNCTYPE(None, C.c_void_p, C.c_void_p)
+_allocator_refs = None          # keeps the ctypes callbacks alive while they are installed
+allocator_calls = {"alloc": 0, "free": 0}
+
+
+def sp_set_allocator(alloc=None, free=None):
+    """Installs Python callables alloc(nbytes, stream) -> device address (0 on failure) and free(address) as the
+    library's device allocator; sp_set_allocator() restores the library's own pool."""
+    global _allocator_refs
+    l = lib()
+    l.sp_set_allocator.argtypes = [_ALLOC_T, _FREE_T, _vp]
+    if alloc is None and free is None:
+        _check(l.sp_set_allocator(C.cast(None, _ALLOC_T), C.cast(None, _FREE_T), None))
+        return
+
+    def _a(nbytes, stream, ctx):
+        try:
+            allocator_calls["alloc"] += 1
+            return int(alloc(int(nbytes), int(stream or 0)))
+        except Exception:
+            return 0
+
+    def _f(ptr, ctx):
+        try:
+            allocator_calls["free"] += 1
+            free(int(ptr))
+        except Exception:
+            pass
+
+    refs = (_ALLOC_T(_a), _FREE_T(_f))
+    _check(l.sp_set_allocator(refs[0], refs[1], None))
+    _allocator_refs = (_allocator_refs, refs)   # earlier callbacks stay alive: blocks taken from them return to them
+
+
+def use_torch_allocator(enable: bool = True):
+    """Routes all of the library's device memory through torch's caching allocator (one allocator owns the
+    GPU's memory), or back to the library's own pool."""
+    if not enable:
+        sp_set_allocator()
+        return
+    sp_set_allocator(lambda nbytes, stream: torch.cuda.caching_allocator_alloc(nbytes, stream=stream),
+                     lambda ptr: torch.cuda.caching_allocator_delete(ptr))
+
+
 def sp_pool_bytes() -> int:
     return int(lib().sp_pool_bytes())
 

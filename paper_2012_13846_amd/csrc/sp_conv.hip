@@ -7,6 +7,7 @@
 // adds each result row into the accumulator row of its destination.  A destination row belongs to exactly
 // one workgroup and appears at most once per offset, so nothing is atomic and the summation order is
 // fixed (results are reproducible run to run).  The accumulator is written once, rounded once.
+#include <mutex>
 #include <type_traits>
 
 #include "sp_internal.h"
@@ -518,19 +519,24 @@ int launch_wave(GatherArgs a, hipStream_t s) {
     a.lds_per_wave = Cfg::per_wave_bytes(a.kvol);
     a.w_bytes = (uint32_t)((size_t)a.kvol * a.co_total * CC * sizeof(T));
     const int lds = a.lds_per_wave;  // one wavefront per workgroup: they are independent, small groups place freely
-    static int attr_lds = 0;  // largest dynamic LDS size opted into so far
-    if (lds > attr_lds) {
-        SP_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-        attr_lds = lds;
+    {
+        static std::mutex mu;
+        static int attr_lds = 0;  // largest dynamic LDS size opted into so far
+        std::lock_guard<std::mutex> lk(mu);
+        if (lds > attr_lds) {
+            SP_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+            attr_lds = lds;
+        }
     }
     // fragment-major copy of the weights (also undoes the data gradient's transposition)
     const int64_t n = (int64_t)a.kvol * a.co_total * CC;
-    Buf wf = dev_alloc((size_t)n * sizeof(T));
+    Buf wf = dev_alloc((size_t)n * sizeof(T), s);
     if (!wf) return SP_ERR_ALLOC;
+    T* d_wf = ptr<T>(wf);
     const int s_co = a.w_transposed ? 1 : CC, s_cc = a.w_transposed ? a.co_total : 1;
     hipLaunchKernelGGL((weight_frag_kernel<T, CC, COT>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
-                       static_cast<const T*>(a.w), ptr<T>(wf), a.kvol, a.co_total, s_co, s_cc);
-    a.w = wf->p;
+                       static_cast<const T*>(a.w), d_wf, a.kvol, a.co_total, s_co, s_cc);
+    a.w = d_wf;
     const int64_t nwt = (a.n_rows + 63) / 64;
     // A launch whose sub-tiles fit the GPU's LDS at once runs as long as its longest wavefront: then long
     // sub-tiles (48 blocks and more, against a typical 27-35; measured best of 32..64) are shared by two
@@ -592,16 +598,20 @@ template <typename T, int CC, int COT, int TR>
 int launch_gather(GatherArgs a, hipStream_t s) {
     using Cfg = GatherCfg<T, CC, COT, TR>;
     auto kern = gather_mma_kernel<T, CC, COT, TR>;
-    static bool attr_set = false;  // one-time opt-in to > 64 KB of dynamic LDS
-    if (!attr_set) {
-        SP_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   (int)Cfg::kLds));
-        attr_set = true;
+    {
+        static std::mutex mu;
+        static bool attr_set = false;  // one-time opt-in to > 64 KB of dynamic LDS
+        std::lock_guard<std::mutex> lk(mu);
+        if (!attr_set) {
+            SP_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)Cfg::kLds));
+            attr_set = true;
+        }
     }
     Buf wt;
     if (a.w_transposed) {  // stored matrix is [cout = cc][cin = co]; the kernel wants [co][cc]
         const int64_t n = (int64_t)a.kvol * CC * a.co_total;
-        wt = dev_alloc((size_t)n * sizeof(T));
+        wt = dev_alloc((size_t)n * sizeof(T), s);
         if (!wt) return SP_ERR_ALLOC;
         hipLaunchKernelGGL(transpose_w_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
                            static_cast<const T*>(a.w), ptr<T>(wt), a.kvol, CC, a.co_total);
@@ -675,7 +685,7 @@ int conv_gather(const MapSide& side, int kvol, int64_t total_links, const void* 
         const void* w = d_w;
         if (w_transposed) {  // stored matrix is [cout = cc][cin = co]; the kernel wants [co][cc]
             const int64_t n = (int64_t)kvol * cc * co;
-            wt = dev_alloc((size_t)n * elt);
+            wt = dev_alloc((size_t)n * elt, s);
             if (!wt) return SP_ERR_ALLOC;
             hipLaunchKernelGGL(transpose_w_kernel<bf16_t>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
                                static_cast<const bf16_t*>(d_w), ptr<bf16_t>(wt), kvol, cc, co);

@@ -10,6 +10,8 @@
 // throughput is 16 times the fp32 one while this form needs no per-link bookkeeping, no scatter and no
 // accumulator traffic.  Each destination row belongs to one workgroup and the offsets are added in index
 // order: no atomics, reproducible, rounded once.
+#include <mutex>
+
 #include "sp_internal.h"
 
 namespace sp {
@@ -338,11 +340,15 @@ template <int CC, int COT, int KS>
 int launch_dense(const DenseArgs& a, hipStream_t s) {
     using Cfg = DenseCfg<CC, COT, KS>;
     auto kern = gather_dense_kernel<CC, COT, KS>;
-    static bool attr_set = false;  // one-time opt-in to > 64 KB of dynamic LDS
-    if (!attr_set) {
-        SP_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   (int)Cfg::kLds));
-        attr_set = true;
+    {
+        static std::mutex mu;
+        static bool attr_set = false;  // one-time opt-in to > 64 KB of dynamic LDS
+        std::lock_guard<std::mutex> lk(mu);
+        if (!attr_set) {
+            SP_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)Cfg::kLds));
+            attr_set = true;
+        }
     }
     const int64_t ntiles = (a.n_rows + Cfg::kTR - 1) / Cfg::kTR;
     const int nslice = a.co_total / COT;

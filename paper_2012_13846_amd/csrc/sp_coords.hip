@@ -176,14 +176,14 @@ int coords_build_impl(const int32_t* d_src, int64_t n_src, int32_t floor_step, i
     while ((int64_t)cap < 2 * n_src) cap <<= 1;
     c->tab.cap = cap;
     for (int t = tensor_stride; t > 1; t >>= 1) ++c->tab.zshift;
-    c->tab.slots = dev_alloc((size_t)cap * sizeof(HashSlot));
-    c->coords = dev_alloc((size_t)(n_src ? n_src : 1) * 16);
-    c->inverse = dev_alloc((size_t)(n_src ? n_src : 1) * 4);
-    Buf slot_of = dev_alloc((size_t)(n_src ? n_src : 1) * 4);
+    c->tab.slots = dev_alloc((size_t)cap * sizeof(HashSlot), s);
+    c->coords = dev_alloc((size_t)(n_src ? n_src : 1) * 16, s);
+    c->inverse = dev_alloc((size_t)(n_src ? n_src : 1) * 4, s);
+    Buf slot_of = dev_alloc((size_t)(n_src ? n_src : 1) * 4, s);
     const int64_t nb = (n_src + kBlockRows - 1) / kBlockRows;
-    Buf block_counts = dev_alloc((size_t)(nb ? nb : 1) * 4);
-    Buf first_mask = dev_alloc((size_t)(nb ? nb : 1) * (kBlockRows / 64) * 8);
-    Buf small = dev_alloc(8);  // [0] total, [1] error bits
+    Buf block_counts = dev_alloc((size_t)(nb ? nb : 1) * 4, s);
+    Buf first_mask = dev_alloc((size_t)(nb ? nb : 1) * (kBlockRows / 64) * 8, s);
+    Buf small = dev_alloc(8, s);  // [0] total, [1] error bits
     if (!c->tab.slots || !c->coords || !c->inverse || !slot_of || !block_counts || !first_mask || !small) return SP_ERR_ALLOC;
     HashSlot* tab = ptr<HashSlot>(c->tab.slots);
     int32_t* d_small = ptr<int32_t>(small);

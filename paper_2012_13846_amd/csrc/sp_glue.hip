@@ -634,7 +634,7 @@ int bn_fwd_typed(const void* x, int64_t n, int c, const float* gamma, const floa
     const bool vec = vec_ok<T>(c, x, y, nullptr, nullptr);
     const int64_t rpb = vec ? vec_rows_per_block(n) : kSlabRows;
     const int64_t nblk = (n + rpb - 1) / rpb;
-    Buf partial = dev_alloc((size_t)(nblk ? nblk : 1) * 2 * c * 4);
+    Buf partial = dev_alloc((size_t)(nblk ? nblk : 1) * 2 * c * 4, s);
     if (!partial) return SP_ERR_ALLOC;
     if (nblk > 0) {
         if (vec) {
@@ -670,7 +670,7 @@ int bn_bwd_typed(const void* x, const void* y, const void* dy, int64_t n, int c,
     const bool vec = vec_ok<T>(c, x, y, dy, dx);
     const int64_t rpb = vec ? vec_rows_per_block(n) : kSlabRows;
     const int64_t nblk = (n + rpb - 1) / rpb;
-    Buf partial = dev_alloc((size_t)(nblk ? nblk : 1) * 2 * c * 4);
+    Buf partial = dev_alloc((size_t)(nblk ? nblk : 1) * 2 * c * 4, s);
     if (!partial) return SP_ERR_ALLOC;
     if (nblk > 0) {
         if (vec) {
@@ -716,8 +716,8 @@ int pool_fwd_typed(const int32_t* coords, const void* x, int64_t n, int c, int n
     int64_t slab = kSlabRows;
     if (vec) slab = std::max<int64_t>(128, (n + 1023) / 1024);
     const int64_t nblk = (n + slab - 1) / slab;
-    Buf partial = dev_alloc((size_t)(nblk ? nblk : 1) * nb * c * 4);
-    Buf cnt = dev_alloc((size_t)(nblk ? nblk : 1) * nb * 4);
+    Buf partial = dev_alloc((size_t)(nblk ? nblk : 1) * nb * c * 4, s);
+    Buf cnt = dev_alloc((size_t)(nblk ? nblk : 1) * nb * 4, s);
     if (!partial || !cnt) return SP_ERR_ALLOC;
     if (nblk > 0) {
         if (vec)
@@ -830,7 +830,7 @@ int sp_softmax_ce(const float* d_logits, const int32_t* d_labels, int32_t n_clou
                   float* d_dlogits, void* stream) {
     if (n_clouds < 1 || m < 1 || !d_logits || !d_labels || !d_loss || !d_dlogits)
         return fail(SP_ERR_INVALID_ARG, "bad cross-entropy arguments");
-    Buf per_cloud = dev_alloc((size_t)n_clouds * 4);
+    Buf per_cloud = dev_alloc((size_t)n_clouds * 4, (hipStream_t)stream);
     if (!per_cloud) return SP_ERR_ALLOC;
     hipLaunchKernelGGL(softmax_ce_kernel, dim3(1), dim3(kThreads), 0, (hipStream_t)stream, d_logits, d_labels, n_clouds,
                        m, d_loss, d_dlogits, ptr<float>(per_cloud));

@@ -31,21 +31,27 @@ int fail(int code, const char* fmt, ...);
         if (rc_ != SP_OK) return rc_; \
     } while (0)
 
-// ---- device memory: size-class caching pool -------------------------------------------------------------
-// Blocks are handed back to the pool when the last owner drops them and may be reused by the next
-// allocation at once: correct as long as the work that used them and the work that reuses them are
-// ordered on one stream, which is the library's documented contract.
+// ---- device memory: size-class caching pool, or the caller's allocator (sp_set_allocator) ------------------
+// A block remembers the stream it was allocated for; all work that touches it is enqueued on that stream
+// (one handle = one stream is the documented contract).  When the last owner drops it, the pool keeps it
+// with that stream: the next allocation for the same stream takes it at once, an allocation for another
+// stream first makes its stream wait for the old one (see sp_runtime.hip).
 struct DevBuf {
     void* p = nullptr;
     size_t bytes = 0;
+    hipStream_t stream = nullptr;
+    sp_free_fn free_ = nullptr;  // set when the block came from the caller's allocator
+    void* ctx = nullptr;
     ~DevBuf();
 };
 using Buf = std::shared_ptr<DevBuf>;
-Buf dev_alloc(size_t bytes);  // nullptr (and error set) on failure; bytes == 0 gives a valid tiny block
+// nullptr (and error set) on failure; bytes == 0 gives a valid tiny block.  s: the stream the block is used on.
+Buf dev_alloc(size_t bytes, hipStream_t s);
 template <class T>
 inline T* ptr(const Buf& b) { return b ? static_cast<T*>(b->p) : nullptr; }
 int pool_trim();
 int64_t pool_bytes();
+int64_t pool_cross_stream();
 
 // Pinned host staging area for small read-backs (one per process, guarded by a mutex inside).
 // Blocks until `bytes` at d_src, as of everything enqueued on s so far, are in h_dst.  `then_enqueue`, if given,

@@ -271,9 +271,9 @@ int build_classes(MapSide& side, const sp_coords* c, int stride, int K, hipStrea
     const int nclass = stride * stride * stride;
     const int64_t n = side.n_rows, ntiles = (n + kTileRows - 1) / kTileRows;
     if (nclass > 32 || n == 0) return SP_OK;  // larger strides: no class order, the kernels take all offsets
-    Buf cnt = dev_alloc((size_t)(nclass * ntiles + 1) * 4);
-    side.perm = dev_alloc((size_t)n * 4);
-    side.tile_mask = dev_alloc((size_t)ntiles * 16);
+    Buf cnt = dev_alloc((size_t)(nclass * ntiles + 1) * 4, s);
+    side.perm = dev_alloc((size_t)n * 4, s);
+    side.tile_mask = dev_alloc((size_t)ntiles * 16, s);
     if (!cnt || !side.perm || !side.tile_mask) return SP_ERR_ALLOC;
     hipLaunchKernelGGL(class_count_kernel, dim3((unsigned)ntiles), dim3(kThreads), 0, s, ptr<int4>(c->coords), n, c->ts,
                        stride, nclass, ptr<int32_t>(cnt));
@@ -294,8 +294,8 @@ int build_classes(MapSide& side, const sp_coords* c, int stride, int K, hipStrea
 int finish_side(MapSide& side, int kvol, int64_t total, const int32_t* d_blk_off, int32_t* d_pair_in,
                 int32_t* d_pair_out, hipStream_t s) {
     const int64_t ntiles = (side.n_rows + kTileRows - 1) / kTileRows;
-    side.tl_src = dev_alloc((size_t)(total ? total : 1) * 4);
-    side.tl_row = dev_alloc((size_t)(total ? total : 1) * 2);
+    side.tl_src = dev_alloc((size_t)(total ? total : 1) * 4, s);
+    side.tl_row = dev_alloc((size_t)(total ? total : 1) * 2, s);
     if (!side.tl_src || !side.tl_row) return SP_ERR_ALLOC;
     if (ntiles > 0 && total > 0)
         hipLaunchKernelGGL(emit_kernel, dim3((unsigned)ntiles, kvol), dim3(kThreads), 0, s, ptr<int32_t>(side.nbr),
@@ -353,17 +353,17 @@ int sp_kmap_build(const sp_coords_t* in, int32_t kernel_size, int32_t stride, in
     MapSide& so = m->out_side;
     so.n_rows = n_out;
     so.n_src = n_in;
-    so.nbr = dev_alloc((size_t)(n_out ? n_out : 1) * kvol * 4);
-    so.tl_off = dev_alloc((size_t)(nt_out * kvol * kSubTiles * kHalves + 1) * 4);
-    Buf blk = dev_alloc((size_t)(nt_out * kvol + 1) * 4);
-    Buf small = dev_alloc((size_t)(kvol + 2) * 4);  // [0..kvol] koff, [kvol+1] scratch total
+    so.nbr = dev_alloc((size_t)(n_out ? n_out : 1) * kvol * 4, s);
+    so.tl_off = dev_alloc((size_t)(nt_out * kvol * kSubTiles * kHalves + 1) * 4, s);
+    Buf blk = dev_alloc((size_t)(nt_out * kvol + 1) * 4, s);
+    Buf small = dev_alloc((size_t)(kvol + 2) * 4, s);  // [0..kvol] koff, [kvol+1] scratch total
     if (!so.nbr || !so.tl_off || !blk || !small) return SP_ERR_ALLOC;
     MapSide& si = m->in_side;
     if (!symmetric) {
         si.n_rows = n_in;
         si.n_src = n_out;
-        si.nbr = dev_alloc((size_t)(n_in ? n_in : 1) * kvol * 4);
-        si.tl_off = dev_alloc((size_t)(nt_in * kvol * kSubTiles * kHalves + 1) * 4);
+        si.nbr = dev_alloc((size_t)(n_in ? n_in : 1) * kvol * 4, s);
+        si.tl_off = dev_alloc((size_t)(nt_in * kvol * kSubTiles * kHalves + 1) * 4, s);
         if (!si.nbr || !si.tl_off) return SP_ERR_ALLOC;
         if (n_in > 0)
             hipLaunchKernelGGL(fill_i32_kernel, dim3(blocks256(n_in * kvol)), dim3(256), 0, s, ptr<int32_t>(si.nbr),
@@ -430,8 +430,8 @@ int sp_kmap_build(const sp_coords_t* in, int32_t kernel_size, int32_t stride, in
     const bool early = most * 14 <= ((int64_t)512 << 20);
     int early_rc = SP_OK;
     auto emit_out_side = [&](int64_t total) {
-        m->pair_in = dev_alloc((size_t)(total ? total : 1) * 4);
-        m->pair_out = dev_alloc((size_t)(total ? total : 1) * 4);
+        m->pair_in = dev_alloc((size_t)(total ? total : 1) * 4, s);
+        m->pair_out = dev_alloc((size_t)(total ? total : 1) * 4, s);
         if (!m->pair_in || !m->pair_out) return (int)SP_ERR_ALLOC;
         return finish_side(so, kvol, total, ptr<int32_t>(blk), ptr<int32_t>(m->pair_in), ptr<int32_t>(m->pair_out), s);
     };

@@ -30,12 +30,23 @@ int fail(int code, const char* fmt, ...) {
 }
 
 // ---- pool -----------------------------------------------------------------------------------------------
+// Size-class caching pool.  A block carries the stream its last owner used it on.  An allocation for the
+// same stream takes it at once (the stream orders the old and the new work).  An allocation for another
+// stream may still take it, but first makes that stream wait for everything enqueued so far on the block's
+// old stream (an event recorded there now is later than the block's last use), so library scratch and
+// handle memory can be recycled between callers that drive the library from different streams.
 namespace {
+struct FreeBlock {
+    void* p;
+    hipStream_t stream;
+};
 struct Pool {
     std::mutex mu;
-    std::multimap<size_t, void*> free_blocks;  // size class -> block
-    std::map<void*, size_t> live;              // block -> size class
+    std::multimap<size_t, FreeBlock> free_blocks;  // size class -> block
+    std::map<void*, size_t> live;                  // block -> size class
+    std::vector<hipEvent_t> events;                // spare events for cross-stream hand-overs
     int64_t held = 0;
+    int64_t cross_stream = 0;                      // hand-overs between streams so far (diagnostics)
 
     // Size classes: multiples of 1/8 of the power of two below the request (<= 12.5 % slack), min 512 B.
     static size_t size_class(size_t b) {
@@ -46,16 +57,47 @@ struct Pool {
         return (b + g - 1) / g * g;
     }
 
-    void* alloc(size_t bytes) {
+    // Orders `to` behind everything enqueued on `from` so far.  false: could not (the caller skips the block).
+    bool hand_over(hipStream_t from, hipStream_t to) {
+        hipEvent_t ev = nullptr;
+        if (!events.empty()) {
+            ev = events.back();
+            events.pop_back();
+        } else if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) {
+            (void)hipGetLastError();
+            return false;
+        }
+        bool ok = hipEventRecord(ev, from) == hipSuccess && hipStreamWaitEvent(to, ev, 0) == hipSuccess;
+        if (!ok) {
+            // the old stream may be gone: wait for the whole device instead
+            (void)hipGetLastError();
+            ok = hipDeviceSynchronize() == hipSuccess;
+        }
+        events.push_back(ev);  // a recorded event may be re-recorded: the wait above keeps its own snapshot
+        return ok;
+    }
+
+    void* alloc(size_t bytes, hipStream_t s) {
         size_t c = size_class(bytes);
         {
             std::lock_guard<std::mutex> lk(mu);
-            auto it = free_blocks.find(c);
-            if (it != free_blocks.end()) {
-                void* p = it->second;
-                free_blocks.erase(it);
-                live[p] = c;
-                return p;
+            auto range = free_blocks.equal_range(c);
+            auto pick = free_blocks.end();
+            for (auto it = range.first; it != range.second; ++it) {
+                if (it->second.stream == s) {
+                    pick = it;
+                    break;
+                }
+                if (pick == free_blocks.end()) pick = it;
+            }
+            if (pick != free_blocks.end()) {
+                const FreeBlock b = pick->second;
+                if (b.stream == s || hand_over(b.stream, s)) {
+                    if (b.stream != s) ++cross_stream;
+                    free_blocks.erase(pick);
+                    live[b.p] = c;
+                    return b.p;
+                }
             }
         }
         void* p = nullptr;
@@ -76,16 +118,16 @@ struct Pool {
         return p;
     }
 
-    void release(void* p) {
+    void release(void* p, hipStream_t s) {
         std::lock_guard<std::mutex> lk(mu);
         auto it = live.find(p);
         if (it == live.end()) return;
-        free_blocks.emplace(it->second, p);
+        free_blocks.emplace(it->second, FreeBlock{p, s});
         live.erase(it);
     }
 
     int trim() {
-        std::multimap<size_t, void*> blocks;
+        std::multimap<size_t, FreeBlock> blocks;
         {
             std::lock_guard<std::mutex> lk(mu);
             blocks.swap(free_blocks);
@@ -94,7 +136,7 @@ struct Pool {
         hipError_t e = hipDeviceSynchronize();
         int64_t freed = 0;
         for (auto& kv : blocks) {
-            (void)hipFree(kv.second);
+            (void)hipFree(kv.second.p);
             freed += (int64_t)kv.first;
         }
         std::lock_guard<std::mutex> lk(mu);
@@ -106,6 +148,18 @@ struct Pool {
 Pool& pool() {
     static Pool* p = new Pool;  // leaked on purpose: device memory goes with the process
     return *p;
+}
+
+// The caller's allocator, if one is installed (sp_set_allocator): then the pool above is not used.
+struct External {
+    std::mutex mu;
+    sp_alloc_fn alloc = nullptr;
+    sp_free_fn free_ = nullptr;
+    void* ctx = nullptr;
+};
+External& external() {
+    static External* e = new External;
+    return *e;
 }
 
 struct Stage {
@@ -120,15 +174,45 @@ Stage& stage() {
 }  // namespace
 
 DevBuf::~DevBuf() {
-    if (p) pool().release(p);
+    if (!p) return;
+    if (free_)
+        free_(p, ctx);
+    else
+        pool().release(p, stream);
 }
 
-Buf dev_alloc(size_t bytes) {
-    void* p = pool().alloc(bytes ? bytes : 1);
-    if (!p) return nullptr;
+Buf dev_alloc(size_t bytes, hipStream_t s) {
+    sp_alloc_fn ext_alloc;
+    sp_free_fn ext_free;
+    void* ext_ctx;
+    {
+        External& e = external();
+        std::lock_guard<std::mutex> lk(e.mu);
+        ext_alloc = e.alloc;
+        ext_free = e.free_;
+        ext_ctx = e.ctx;
+    }
     auto b = std::make_shared<DevBuf>();
-    b->p = p;
     b->bytes = bytes;
+    b->stream = s;
+    if (ext_alloc) {
+        b->p = ext_alloc(bytes ? bytes : 1, (void*)s, ext_ctx);
+        if (!b->p) {
+            set_error("the installed allocator returned NULL for %zu bytes", bytes);
+            return nullptr;
+        }
+        if (((uintptr_t)b->p & 255) != 0) {
+            ext_free(b->p, ext_ctx);
+            b->p = nullptr;
+            set_error("the installed allocator returned memory that is not 256-byte aligned");
+            return nullptr;
+        }
+        b->free_ = ext_free;  // the block goes back where it came from, whatever is installed by then
+        b->ctx = ext_ctx;
+        return b;
+    }
+    b->p = pool().alloc(bytes ? bytes : 1, s);
+    if (!b->p) return nullptr;
     return b;
 }
 
@@ -136,6 +220,10 @@ int pool_trim() { return pool().trim(); }
 int64_t pool_bytes() {
     std::lock_guard<std::mutex> lk(pool().mu);
     return pool().held;
+}
+int64_t pool_cross_stream() {
+    std::lock_guard<std::mutex> lk(pool().mu);
+    return pool().cross_stream;
 }
 
 // ---- small read-backs through a mailbox in pinned host memory ------------------------------------------------
@@ -238,6 +326,18 @@ int read_back(void* h_dst, const void* d_src, size_t bytes, hipStream_t s, const
 extern "C" {
 
 const char* sp_last_error(void) { return sp::g_err.c_str(); }
+
+int sp_set_allocator(sp_alloc_fn alloc, sp_free_fn free_, void* ctx) {
+    if ((alloc == nullptr) != (free_ == nullptr))
+        return sp::fail(SP_ERR_INVALID_ARG, "alloc and free must both be given or both be NULL");
+    sp::External& e = sp::external();
+    std::lock_guard<std::mutex> lk(e.mu);
+    e.alloc = alloc;
+    e.free_ = free_;
+    e.ctx = ctx;
+    return SP_OK;
+}
+int64_t sp_pool_cross_stream(void) { return sp::pool_cross_stream(); }
 int sp_pool_trim(void) { return sp::pool_trim(); }
 int64_t sp_pool_bytes(void) { return sp::pool_bytes(); }
 const char* sp_version(void) { return "sp_conv 0.1 (gfx950)"; }

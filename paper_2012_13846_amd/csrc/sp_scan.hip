@@ -10,7 +10,9 @@ namespace {
 constexpr int kScanThreads = 256;
 constexpr int kScanItems = 8;
 constexpr int kScanTile = kScanThreads * kScanItems;
-constexpr int64_t kSelfBaseMaxBlocks = 4096;
+// Up to this many blocks every block adds up its predecessors' sums itself; beyond, one more launch scans them.
+// (Not const: a test hook lowers it so that small inputs run the extra launch.)
+int64_t g_self_base_max_blocks = 4096;
 
 struct ScanJobDev {
     int32_t* data;
@@ -161,10 +163,10 @@ int exclusive_scan_jobs(const ScanJob* jobs, int njobs, hipStream_t s) {
             continue;
         }
         d.nb = (in.n + kScanTile - 1) / kScanTile;
-        partials[a.njobs] = dev_alloc((size_t)d.nb * sizeof(int32_t));
+        partials[a.njobs] = dev_alloc((size_t)d.nb * sizeof(int32_t), s);
         if (!partials[a.njobs]) return SP_ERR_ALLOC;
         d.partials = ptr<int32_t>(partials[a.njobs]);
-        d.partials_scanned = d.nb > kSelfBaseMaxBlocks ? 1 : 0;
+        d.partials_scanned = d.nb > g_self_base_max_blocks ? 1 : 0;
         a.job[a.njobs++] = d;
     }
     if (a.njobs > 0) {
@@ -180,3 +182,11 @@ int exclusive_scan_jobs(const ScanJob* jobs, int njobs, hipStream_t s) {
 }
 
 }  // namespace sp
+
+// Test hook, not part of the ABI (not declared in sp_conv.h): sets the block count above which a scan takes
+// the extra launch, returns the previous value.  Values < 1 only query.
+extern "C" int64_t sp_debug_scan_self_base_max(int64_t blocks) {
+    const int64_t old = sp::g_self_base_max_blocks;
+    if (blocks >= 1) sp::g_self_base_max_blocks = blocks;
+    return old;
+}

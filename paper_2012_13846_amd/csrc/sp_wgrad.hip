@@ -11,6 +11,7 @@
 // there: fp32 with one 4-byte read per lane (lane = channel, links in lane groups), bf16 with the LDS
 // transpose read, which hands a lane 4 consecutive links of one channel out of row-major storage.
 #include <algorithm>
+#include <mutex>
 #include <type_traits>
 
 #include "sp_internal.h"
@@ -96,13 +97,16 @@ __global__ __launch_bounds__(64) void wgrad_plan_kernel(PlanArgs pa, int32_t* __
 // dW[k][e] = sum of offset k's partial blocks, strip by strip, in a fixed order: 16 interleaved running sums
 // per element, each over every 16th block, then added in order 0..15.  grid (per/64, kvol); block = 16 lanes
 // x 4 elements each x 16 block slices.
-__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ part,
+// P: type of the partial blocks and of the sums (double on the fp32 path, see wgrad_staged_kernel).
+template <typename P>
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const P* __restrict__ part,
                                                            const int32_t* __restrict__ first,
                                                            const int32_t* __restrict__ count, int S8, int kvol, int per,
                                                            float* __restrict__ dw) {
+    typedef P Px4 __attribute__((ext_vector_type(4)));
     constexpr int kMaxStrips = 1024;
     __shared__ int s_first[kMaxStrips], s_count[kMaxStrips];
-    __shared__ f32x4 red[16][16];
+    __shared__ Px4 red[16][16];
     const int k = blockIdx.y;
     const int el = threadIdx.x & 15, grp = threadIdx.x >> 4;
     const int e = (blockIdx.x * 16 + el) * 4;
@@ -111,21 +115,21 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restri
         s_count[s] = count[s * kvol + k];
     }
     __syncthreads();
-    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+    Px4 sum = {0, 0, 0, 0};
     int n = 0;
     for (int s = 0; s < S8; ++s) {
         const int f = s_first[s], c = s_count[s];
         for (int j = (grp - n) & 15; j < c; j += 16)
-            sum += *reinterpret_cast<const f32x4*>(part + (size_t)(f + j) * per + e);
+            sum += *reinterpret_cast<const Px4*>(part + (size_t)(f + j) * per + e);
         n += c;
     }
     red[grp][el] = sum;
     __syncthreads();
     if (grp == 0) {
-        f32x4 t = red[0][el];
+        Px4 t = red[0][el];
 #pragma unroll
         for (int i = 1; i < 16; ++i) t += red[i][el];
-        *reinterpret_cast<f32x4*>(dw + (size_t)k * per + e) = t;
+        *reinterpret_cast<f32x4*>(dw + (size_t)k * per + e) = f32x4{(float)t[0], (float)t[1], (float)t[2], (float)t[3]};
     }
 }
 
@@ -155,7 +159,8 @@ struct StagedCfg {
     static constexpr int kLoadsA = (kPiecesA + kTPR - 1) / kTPR;  // per thread and step
     static constexpr int kLoadsB = (kPiecesB + kTPR - 1) / kTPR;
     static constexpr int kBufBytes = kS * (kPA + kPB);
-    static constexpr int kRedBytes = WK > 1 ? COB * CIB * 4 : 0;
+    static constexpr int kPartElt = kIsF32 ? 8 : 4;        // partial blocks: double on the fp32 path, float for bf16
+    static constexpr int kRedBytes = WK > 1 ? COB * CIB * kPartElt : 0;
     static constexpr int kLds = 2 * kBufBytes > kRedBytes ? 2 * kBufBytes : kRedBytes;
     static_assert(COB % (16 * WCO) == 0 && CIB % (16 * WCI) == 0, "tile split");
     static_assert(kThreads % kS == 0, "whole threads per row");
@@ -167,7 +172,7 @@ struct StagedArgs {
     const int32_t* pair_out;
     const void* x;
     const void* dy;
-    float* part;
+    void* part;   // partial blocks [slot][cout][cin], double (fp32 path) or float (bf16 path)
     int cin, cout;
     uint32_t x_bytes, dy_bytes, pair_bytes;  // buffer sizes (< 2 GiB each)
     PlanArgs plan;
@@ -264,9 +269,16 @@ __global__ __launch_bounds__(64 * WCO * WCI * WK) void wgrad_staged_kernel(Stage
                 *reinterpret_cast<u32x4*>(buf + st_b + j * kTPR * 16) = r.vb[j];
     };
 
+    // fp32 path: the matrix cores' accumulator only ever holds the sum of kFlushEvery * kD steps (64 links); it
+    // is then added into a double-precision total, the partial blocks are doubles and so are the final sums.
+    // Sums whose terms mostly share a sign within long stretches of rows and cancel between them (gradients
+    // that are constant per cloud, as global pooling produces) otherwise lose more than the 1e-5 parity bound
+    // to the rounding of the large intermediate sums.
+    typedef double f64x4 __attribute__((ext_vector_type(4)));
+    using Part = typename std::conditional<kIsF32, double, float>::type;
     f32x4 acc[kTA][kTB];
-    f32x4 tot[kIsF32 ? kTA : 1][kIsF32 ? kTB : 1];  // fp32: acc is added into tot every kFlushEvery * kD steps
-    constexpr int kFlushEvery = 8 / kD > 0 ? 8 / kD : 1;
+    f64x4 tot[kIsF32 ? kTA : 1][kIsF32 ? kTB : 1];
+    constexpr int kFlushEvery = 2 / kD > 0 ? 2 / kD : 1;
 
     // This wavefront's 32 links of the step and its channel slices.  Channel of (16x16 tile t, index m in the
     // tile) within the slice: bf16 t*16 + m; fp32 m*kT + t, so that a lane's kT values are adjacent in LDS.
@@ -358,7 +370,7 @@ __global__ __launch_bounds__(64 * WCO * WCI * WK) void wgrad_staged_kernel(Stage
 #pragma unroll
             for (int tb = 0; tb < kTB; ++tb) {
                 acc[ta][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
-                if constexpr (kIsF32) tot[ta][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+                if constexpr (kIsF32) tot[ta][tb] = f64x4{0., 0., 0., 0.};
             }
 #pragma unroll
         for (int d = 0; d < kD; ++d) {
@@ -399,7 +411,8 @@ __global__ __launch_bounds__(64 * WCO * WCI * WK) void wgrad_staged_kernel(Stage
                     for (int ta = 0; ta < kTA; ++ta)
 #pragma unroll
                         for (int tb = 0; tb < kTB; ++tb) {
-                            tot[ta][tb] += acc[ta][tb];
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) tot[ta][tb][j] += (double)acc[ta][tb][j];
                             acc[ta][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
                         }
                 }
@@ -409,15 +422,23 @@ __global__ __launch_bounds__(64 * WCO * WCI * WK) void wgrad_staged_kernel(Stage
 #pragma unroll
             for (int ta = 0; ta < kTA; ++ta)
 #pragma unroll
-                for (int tb = 0; tb < kTB; ++tb) acc[ta][tb] += tot[ta][tb];
+                for (int tb = 0; tb < kTB; ++tb)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) tot[ta][tb][j] += (double)acc[ta][tb][j];
         }
+        // value of this piece's element (ta, tb, j)
+        auto piece_val = [&](int ta, int tb, int j) __attribute__((always_inline)) -> Part {
+            if constexpr (kIsF32) return tot[ta][tb][j];
+            else return acc[ta][tb][j];
+        };
 
         // acc[ta][tb][j] is element (co: tile ta, index 4*g + j; ci: tile tb, index n16) of the wavefront's
         // slice.  The WK link slices are added in order.
         auto chan = [&](int t, int m, int kt) { return kIsF32 ? m * kt + t : t * 16 + m; };
-        float* dst = a.part + (size_t)slot * a.cout * a.cin;
+        typedef Part Partx4 __attribute__((ext_vector_type(4)));
+        Part* dst = static_cast<Part*>(a.part) + (size_t)slot * a.cout * a.cin;
         if constexpr (WK > 1) {
-            float* red = reinterpret_cast<float*>(smem);
+            Part* red = reinterpret_cast<Part*>(smem);
             for (int w = 0; w < WK; ++w) {
                 if (wk == w) {
 #pragma unroll
@@ -427,14 +448,14 @@ __global__ __launch_bounds__(64 * WCO * WCI * WK) void wgrad_staged_kernel(Stage
 #pragma unroll
                             for (int j = 0; j < 4; ++j) {
                                 const int e = (wco * kTA * 16 + chan(ta, g * 4 + j, kTA)) * CIB + wci * kTB * 16 + chan(tb, n16, kTB);
-                                red[e] = (w == 0 ? 0.f : red[e]) + acc[ta][tb][j];
+                                red[e] = (w == 0 ? (Part)0 : red[e]) + piece_val(ta, tb, j);
                             }
                 }
                 __syncthreads();
             }
             for (int e = tid * 4; e < COB * CIB; e += kThreads * 4) {
                 const int co = e / CIB, ci = e % CIB;
-                *reinterpret_cast<f32x4*>(dst + (size_t)(co0 + co) * a.cin + ci0 + ci) = *reinterpret_cast<const f32x4*>(red + e);
+                *reinterpret_cast<Partx4*>(dst + (size_t)(co0 + co) * a.cin + ci0 + ci) = *reinterpret_cast<const Partx4*>(red + e);
             }
         } else {
 #pragma unroll
@@ -444,7 +465,7 @@ __global__ __launch_bounds__(64 * WCO * WCI * WK) void wgrad_staged_kernel(Stage
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
                         dst[(size_t)(co0 + wco * kTA * 16 + chan(ta, g * 4 + j, kTA)) * a.cin + ci0 + wci * kTB * 16 +
-                            chan(tb, n16, kTB)] = acc[ta][tb][j];
+                            chan(tb, n16, kTB)] = piece_val(ta, tb, j);
         }
         __syncthreads();  // the next piece reuses the staging buffers
     }
@@ -471,11 +492,21 @@ template <typename T, int COB, int CIB, int WCO, int WCI, int WK, int kD>
 int launch_staged(const sp_kmap* m, const void* x, const void* dy, int cin, int cout, float* dw, hipStream_t s) {
     using Cfg = StagedCfg<T, COB, CIB, WCO, WCI, WK>;
     auto kern = wgrad_staged_kernel<T, COB, CIB, WCO, WCI, WK, kD>;
+    static std::mutex mu;  // guards the two one-time queries below
     static bool attr_set = false;  // one-time opt-in to > 64 KB of dynamic LDS
-    if (!attr_set) {
-        SP_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   (int)Cfg::kLds));
-        attr_set = true;
+    static int occ = 0;  // workgroups of this kernel that fit a CU: asked once
+    {
+        std::lock_guard<std::mutex> lk(mu);
+        if (!attr_set) {
+            SP_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)Cfg::kLds));
+            attr_set = true;
+        }
+        if (occ == 0) {
+            int q = 1;
+            SP_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&q, kern, Cfg::kThreads, Cfg::kLds));
+            occ = q < 1 ? 1 : q;
+        }
     }
     const int kvol = m->kvol, per = cin * cout;
     StagedArgs a;
@@ -485,12 +516,6 @@ int launch_staged(const sp_kmap* m, const void* x, const void* dy, int cin, int 
     for (int k = 0; k <= kvol; ++k) pa.koff[k] = (int32_t)m->koff[k];
     // Strips: about 1.5 MB of rows (both operands) each, but long enough that an offset's stretch in a strip
     // (which costs a partial block of per * 4 bytes) has at least ~1024 links or per / 32 of them.
-    static int occ = 0;  // workgroups of this kernel that fit a CU: asked once
-    if (occ == 0) {
-        int q = 1;
-        SP_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&q, kern, Cfg::kThreads, Cfg::kLds));
-        occ = q < 1 ? 1 : q;
-    }
     const int64_t rows_bytes = (m->n_in * (int64_t)cin + m->n_out * (int64_t)cout) * (int64_t)sizeof(T);
     const int64_t stretch = std::max<int64_t>(1024, per / 32);
     int64_t M = std::min<int64_t>((rows_bytes / 8 + (3 << 18)) / (3 << 19), m->total / (8 * kvol * stretch));
@@ -509,9 +534,9 @@ int launch_staged(const sp_kmap* m, const void* x, const void* dy, int cin, int 
     pa.C = (int)C;
     pa.slots_per_strip = (int)nc + kvol;
     const int64_t slots = (int64_t)pa.S8 * pa.slots_per_strip;
-    Buf part = dev_alloc((size_t)slots * per * 4);
+    Buf part = dev_alloc((size_t)slots * per * Cfg::kPartElt, s);
     const size_t nsk = (size_t)pa.S8 * kvol;
-    Buf plan = dev_alloc((nsk * 4 + (size_t)pa.S8 * nc * 3) * 4);
+    Buf plan = dev_alloc((nsk * 4 + (size_t)pa.S8 * nc * 3) * 4, s);
     if (!part || !plan) return SP_ERR_ALLOC;
     int32_t* d_lo = ptr<int32_t>(plan);
     int32_t *d_len = d_lo + nsk, *d_first = d_len + nsk, *d_count = d_first + nsk, *d_cstart = d_count + nsk;
@@ -522,7 +547,7 @@ int launch_staged(const sp_kmap* m, const void* x, const void* dy, int cin, int 
     a.pair_out = ptr<int32_t>(m->pair_out);
     a.x = x;
     a.dy = dy;
-    a.part = ptr<float>(part);
+    a.part = part->p;
     a.cin = cin;
     a.cout = cout;
     a.x_bytes = (uint32_t)((uint64_t)m->n_in * cin * sizeof(T));
@@ -532,8 +557,12 @@ int launch_staged(const sp_kmap* m, const void* x, const void* dy, int cin, int 
                        d_cstart);
     const int64_t wgs = (int64_t)pa.S8 * nc * pa.tiles;
     hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(Cfg::kThreads), Cfg::kLds, s, a);
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(per / 64, kvol), dim3(256), 0, s, ptr<float>(part), d_first, d_count,
-                       pa.S8, kvol, per, dw);
+    if constexpr (Cfg::kIsF32)
+        hipLaunchKernelGGL(wgrad_reduce_kernel<double>, dim3(per / 64, kvol), dim3(256), 0, s, ptr<double>(part), d_first,
+                           d_count, pa.S8, kvol, per, dw);
+    else
+        hipLaunchKernelGGL(wgrad_reduce_kernel<float>, dim3(per / 64, kvol), dim3(256), 0, s, ptr<float>(part), d_first,
+                           d_count, pa.S8, kvol, per, dw);
     SP_HIP(hipGetLastError());
     return SP_OK;
 }
@@ -598,5 +627,7 @@ extern "C" int sp_conv_bwd_weight(const sp_kmap_t* m, const void* d_x, const voi
     if (dt != SP_F32 && dt != SP_BF16) return fail(SP_ERR_INVALID_ARG, "bad dtype");
     if ((!d_x && m->n_in > 0) || (!d_dy && m->n_out > 0) || !d_dw)
         return fail(SP_ERR_INVALID_ARG, "a feature/gradient pointer is NULL");
+    if ((((uintptr_t)d_x | (uintptr_t)d_dy | (uintptr_t)d_dw) & 15) != 0)
+        return fail(SP_ERR_INVALID_ARG, "feature/gradient pointers must be 16-byte aligned");
     return conv_wgrad(m, d_x, d_dy, d_dw, cin, cout, dt, (hipStream_t)stream);
 }

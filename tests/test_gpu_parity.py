@@ -10,7 +10,7 @@ import torch
 
 import oracle
 from paper_2012_13846_amd import spgen
-from util import TOL_BF16, TOL_F32, oracle_steps, rel_err, sort_lists
+from util import TOL_BF16, TOL_F32, oracle_steps, rel_err, rel_err_large, sort_lists
 
 pytestmark = pytest.mark.gpu
 
@@ -52,6 +52,41 @@ def test_coords_build_matches_oracle(sp, name, raw):
     assert np.array_equal(c.inverse().cpu().numpy(), want_inv)
 
 
+def test_coords_build_more_than_4M_rows_few_distinct(sp):
+    """4.5 M raw rows drawn from ~50 k distinct coordinates: more than 4096 numbering blocks, so the block counts
+    are scanned by an extra launch instead of every block adding up its predecessors."""
+    rng = np.random.default_rng(21)
+    distinct = random_coords(22, 50000, 60, batches=4, lo=-30)
+    raw = distinct[rng.integers(0, len(distinct), 4_500_000)]
+    want_c, want_inv = oracle.unique_coords(raw)
+    c = sp.sp_coords_build(dev(raw), 1)
+    assert c.n == len(want_c)
+    assert np.array_equal(c.coords().cpu().numpy(), want_c)
+    assert np.array_equal(c.inverse().cpu().numpy(), want_inv)
+
+
+def test_map_build_with_scanned_block_sums(sp):
+    """The scans' "too many blocks for every block to add up its predecessors" path, forced on a small input
+    through the library's test hook, against the oracle's pair lists."""
+    import ctypes
+    hook = sp.lib().sp_debug_scan_self_base_max
+    hook.restype, hook.argtypes = ctypes.c_int64, [ctypes.c_int64]
+    old = hook(1)
+    try:
+        for K, stride in ((3, 1), (3, 2), (2, 2)):
+            raw = spgen.coords_config(1, 0.5)
+            want = oracle_steps(raw, K, stride, 1, 1)
+            c = sp.sp_coords_build(dev(raw), 1)
+            km, co = sp.sp_kmap_build(c, K, stride, 1)
+            assert np.array_equal(co.coords().cpu().numpy(), want["c_out"])
+            check_map(sp, km, want, len(want["c_in"]), len(want["c_out"]))
+            kt = sp.sp_kmap_transpose(km)
+            tin, tout, tcounts = oracle.transpose_map(want["pair_in"], want["pair_out"], want["counts"])
+            check_map(sp, kt, dict(pair_in=tin, pair_out=tout, counts=tcounts), len(want["c_out"]), len(want["c_in"]))
+    finally:
+        hook(old)
+
+
 def test_coords_build_empty(sp):
     c = sp.sp_coords_build(torch.empty((0, 4), dtype=torch.int32, device="cuda"), 1)
     assert c.n == 0
@@ -90,6 +125,9 @@ MAP_CASES = [
     ("cfg0_k5", spgen.coords_config(0), 1, 5, 1, 1),
     ("cfg0_k1", spgen.coords_config(0), 1, 1, 1, 1),
     ("cfg0_k2s1", spgen.coords_config(0), 1, 2, 1, 1),
+    ("cfg0_k4s1", spgen.coords_config(0), 1, 4, 1, 1),
+    ("cfg1_k4s2", spgen.coords_config(1, 0.3), 1, 4, 2, 1),
+    ("neg_k4s4", random_coords(4, 30000, 30, batches=2, lo=-15), 1, 4, 4, 1),
     ("neg_k3s2", random_coords(5, 30000, 30, batches=2, lo=-15), 1, 3, 2, 1),
     ("neg_k2s2", random_coords(6, 30000, 30, batches=2, lo=-15), 1, 2, 2, 1),
     ("ts2_k3", random_coords(7, 20000, 20, batches=2, lo=-10) * np.array([1, 2, 2, 2], np.int32), 2, 3, 1, 1),
@@ -146,7 +184,7 @@ def test_kmap_matches_oracle(sp, name, raw, ts, K, stride, dil):
 def test_map_build_is_deterministic(sp):
     raw = dev(spgen.coords_config(1))
     ref = None
-    for _ in range(5):
+    for _ in range(20):
         c = sp.sp_coords_build(raw, 1)
         km, co = sp.sp_kmap_build(c, 3, 2, 1)
         got = (c.coords().cpu().numpy().tobytes(), co.coords().cpu().numpy().tobytes(),
@@ -187,8 +225,9 @@ def conv_case(sp, raw, ts, K, stride, dil, cin, cout, bf16, seed, transposed=Fal
     e_y = rel_err(y.float().cpu().numpy(), Y)
     e_dx = rel_err(dx.float().cpu().numpy(), dX)
     e_dw = rel_err(dw.cpu().numpy(), dW)
-    print(f"rel err fwd {e_y:.2e} dgrad {e_dx:.2e} wgrad {e_dw:.2e} (tol {tol:g}); n_in {n_in} n_out {n_out} "
-          f"pairs {int(counts.sum())}")
+    print(f"rel err fwd {e_y:.2e} dgrad {e_dx:.2e} wgrad {e_dw:.2e} (tol {tol:g}); plain |g-r|/|r| over |r| >= rms: "
+          f"{rel_err_large(y.float().cpu().numpy(), Y):.2e} {rel_err_large(dx.float().cpu().numpy(), dX):.2e} "
+          f"{rel_err_large(dw.cpu().numpy(), dW):.2e}; n_in {n_in} n_out {n_out} pairs {int(counts.sum())}")
     assert e_y <= tol and e_dx <= tol
     assert e_dw <= (TOL_F32 if not bf16 else TOL_BF16)       # dW is fp32 storage for both
     # rows / offsets without pairs are exact zeros

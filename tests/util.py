@@ -26,6 +26,20 @@ def rel_err(got, ref) -> float:
     return float(np.max(np.abs(g - r) / den))
 
 
+def rel_err_large(got, ref) -> float:
+    """Plain elementwise relative error max_j |g_j - r_j| / |r_j| over the elements with |r_j| >= rms(r): the
+    part of rel_err's maximum that no floor of the denominator touches (reported next to rel_err)."""
+    g = np.asarray(got, dtype=np.float64)
+    r = np.asarray(ref, dtype=np.float64)
+    if r.size == 0:
+        return 0.0
+    rms = float(np.sqrt(np.mean(r * r)))
+    big = np.abs(r) >= rms
+    if rms == 0 or not big.any():
+        return 0.0
+    return float(np.max(np.abs(g[big] - r[big]) / np.abs(r[big])))
+
+
 def oracle_steps(raw, kernel_size, stride=1, dilation=1, tensor_stride=1):
     """Steps 0-2 on the CPU oracle.  Returns dict with coords, inverse, c_out, parent, ts_out, pairs."""
     c_in, inverse = oracle.unique_coords(raw)
