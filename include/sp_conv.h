@@ -131,6 +131,18 @@ int sp_conv_bwd_data(const sp_kmap_t* m, const void* d_dy, const void* d_w, void
 int sp_conv_bwd_weight(const sp_kmap_t* m, const void* d_x, const void* d_dy, float* d_dw, int32_t cin,
                        int32_t cout, sp_dtype dt, void* stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): sp_conv_fwd with the same arguments, results and kernel choice, except that the
+ * call allocates nothing (no hipMalloc / hipFree, no pool request).  Where sp_conv_fwd takes scratch from the
+ * pool (the fragment-major copy of the weights that the link-list kernel reads), this call uses a 4 MiB
+ * array in static device memory, which every GPU the library runs on holds until the process ends.
+ * Weights larger than that on a shape that needs the copy give SP_ERR_UNSUPPORTED (kvol * cin * cout *
+ * element size <= 4 MiB always fits).  All calls on one GPU share that array: calls that overlap in time on
+ * one GPU (different streams) race; calls on one stream are ordered and safe.  The array's contents are
+ * rewritten by every call, nothing in it needs to start at zero. */
+int sp_conv_fwd_noalloc(const sp_kmap_t* m, const void* d_x, const void* d_w, void* d_y, int32_t cin, int32_t cout,
+                        sp_dtype dt, void* stream);
+
 /* ---- the layers between sparse convolutions ----------------------------------------------------------------
  * (Sec. III, caption of the partition-overview figure: batch normalisation, activation and pooling layers sit
  * between the SparseConv blocks; Sec. IV-A: a 40-category classifier.)  The paper gives no formulas; these are

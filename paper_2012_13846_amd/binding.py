@@ -48,7 +48,7 @@ def lib() -> C.CDLL:
         l.sp_kmap_pairs.argtypes = [_vp, C.POINTER(_vp), C.POINTER(_vp)]
         l.sp_kmap_table.argtypes = [_vp, C.POINTER(_vp), C.POINTER(_vp), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         l.sp_kmap_destroy.argtypes = [_vp]
-        for name in ("sp_conv_fwd", "sp_conv_bwd_data", "sp_conv_bwd_weight"):
+        for name in ("sp_conv_fwd", "sp_conv_bwd_data", "sp_conv_bwd_weight", "sp_conv_fwd_noalloc"):
             getattr(l, name).argtypes = [_vp, _vp, _vp, _vp, C.c_int32, C.c_int32, C.c_int32, _vp]
         _lib = l
     return _lib
@@ -200,6 +200,17 @@ def sp_conv_fwd(kmap: KMap, x: torch.Tensor, w: torch.Tensor, out: torch.Tensor 
         raise ValueError("out has the wrong shape")
     _check(lib().sp_conv_fwd(kmap._h, x.data_ptr(), w.data_ptr(), y.data_ptr(), cin, cout, _dt(x), _stream()))
     return y
+
+
+def sp_conv_fwd_noalloc(kmap: KMap, x: torch.Tensor, w: torch.Tensor, out: torch.Tensor) -> torch.Tensor:
+    """sp_conv_fwd into the caller's `out`, through the entry point that allocates no device memory."""
+    _need_cuda(x, None, "x"), _need_cuda(w, x.dtype, "w"), _need_cuda(out, x.dtype, "out")
+    kvol, cout, cin = w.shape
+    if kvol != kmap.kvol or tuple(x.shape) != (kmap.n_in, cin) or tuple(out.shape) != (kmap.n_out, cout):
+        raise ValueError("shape mismatch between kmap, x, w and out")
+    _check(lib().sp_conv_fwd_noalloc(kmap._h, x.data_ptr(), w.data_ptr(), out.data_ptr(), cin, cout, _dt(x),
+                                     _stream()))
+    return out
 
 
 def sp_conv_bwd_data(kmap: KMap, dy: torch.Tensor, w: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:

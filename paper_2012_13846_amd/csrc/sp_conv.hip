@@ -43,6 +43,8 @@ struct GatherArgs {
     uint32_t f_bytes, w_bytes, src_bytes, row_bytes;  // sizes of f / w / tl_src / tl_row for buffer addressing (< 4 GiB)
     int wave_ok;       // host-side only: buffers small enough for 32-bit buffer addressing
     int w_transposed;  // host-side only: the stored weights are [k][cc][co] (data gradient) instead of [k][co][cc]
+    void* scratch;     // host-side only: if set, device memory for the weight copy instead of a pool allocation
+    size_t scratch_bytes;
 };
 
 // ---------------------------------------------------------------------------------------------------------
@@ -530,9 +532,17 @@ int launch_wave(GatherArgs a, hipStream_t s) {
     }
     // fragment-major copy of the weights (also undoes the data gradient's transposition)
     const int64_t n = (int64_t)a.kvol * a.co_total * CC;
-    Buf wf = dev_alloc((size_t)n * sizeof(T), s);
-    if (!wf) return SP_ERR_ALLOC;
-    T* d_wf = ptr<T>(wf);
+    Buf wf;
+    T* d_wf = static_cast<T*>(a.scratch);
+    if (d_wf) {
+        if ((size_t)n * sizeof(T) > a.scratch_bytes)
+            return fail(SP_ERR_UNSUPPORTED, "weights of %lld bytes exceed the %zu bytes of static scratch",
+                        (long long)(n * sizeof(T)), a.scratch_bytes);
+    } else {
+        wf = dev_alloc((size_t)n * sizeof(T), s);
+        if (!wf) return SP_ERR_ALLOC;
+        d_wf = ptr<T>(wf);
+    }
     const int s_co = a.w_transposed ? 1 : CC, s_cc = a.w_transposed ? a.co_total : 1;
     hipLaunchKernelGGL((weight_frag_kernel<T, CC, COT>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
                        static_cast<const T*>(a.w), d_wf, a.kvol, a.co_total, s_co, s_cc);
@@ -668,8 +678,9 @@ bool mma_shape_ok(int cc, int co, sp_dtype dt) {
 // side: which rows are destinations.  w_transposed = false: W[k][co][cc] as stored (forward);
 // true: the stored W is [k][cc][co] (data gradient), transposed into pool memory first for the MFMA path.
 int conv_gather(const MapSide& side, int kvol, int64_t total_links, const void* d_f, const void* d_w, bool w_transposed,
-                void* d_g, int cc, int co, sp_dtype dt, hipStream_t s) {
+                void* d_g, int cc, int co, sp_dtype dt, hipStream_t s, void* scratch, size_t scratch_bytes) {
     if (side.n_rows == 0) return SP_OK;
+    if (scratch && w_transposed) return fail(SP_ERR_UNSUPPORTED, "no allocation-free path for transposed weights");
     const size_t elt = dt == SP_F32 ? 4 : 2;
     // Row-stationary kernel: it multiplies all kvol offsets of every row, the link-list kernels only the links
     // that exist but pay per link for bookkeeping, weight re-reads and the accumulator update.  Measured, it is
@@ -701,6 +712,8 @@ int conv_gather(const MapSide& side, int kvol, int64_t total_links, const void* 
         a.f = d_f;
         a.w = d_w;
         a.w_transposed = w_transposed ? 1 : 0;
+        a.scratch = scratch;
+        a.scratch_bytes = scratch_bytes;
         const uint64_t fb = (uint64_t)side.n_src * cc * elt, sb = (uint64_t)total_links * 4;
         a.wave_ok = fb < 0xffffffffull && sb < 0xffffffffull;
         a.f_bytes = (uint32_t)fb;
@@ -732,7 +745,34 @@ int conv_gather(const MapSide& side, int kvol, int64_t total_links, const void* 
 
 using namespace sp;
 
+// Scratch of the allocation-free entry point: the fragment-major weight copy that sp_conv_fwd takes from the
+// pool.  One copy of the array exists on every GPU the library is loaded on, at its own address; host code
+// must not use the array's name as a pointer, only the address hipGetSymbolAddress reports for the current
+// device.
+constexpr size_t kStaticScratchBytes = (size_t)4 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (looked up once per device).
+int static_scratch(void** out) {
+    int dev = 0;
+    SP_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(SP_ERR_UNSUPPORTED, "device %d: more devices than expected", dev);
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        SP_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(SP_ERR_HIP, "hipGetSymbolAddress returned a null address");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return SP_OK;
+}
+
 // a: source features (rows_a), b: weights, c: destination (rows_c); a zero-sized buffer may be NULL
 int check_conv_args(const sp_kmap_t* m, const void* a, int64_t rows_a, const void* b, const void* c, int64_t rows_c,
                     int cin, int cout, sp_dtype dt) {
@@ -759,6 +799,15 @@ int sp_conv_bwd_data(const sp_kmap_t* m, const void* d_dy, const void* d_w, void
                      sp_dtype dt, void* stream) {
     SP_TRY(check_conv_args(m, d_dy, m ? m->n_out : 0, d_w, d_dx, m ? m->n_in : 0, cin, cout, dt));
     return conv_gather(m->in_side, m->kvol, m->total, d_dy, d_w, true, d_dx, cout, cin, dt, (hipStream_t)stream);
+}
+
+int sp_conv_fwd_noalloc(const sp_kmap_t* m, const void* d_x, const void* d_w, void* d_y, int32_t cin, int32_t cout,
+                        sp_dtype dt, void* stream) {
+    SP_TRY(check_conv_args(m, d_x, m ? m->n_in : 0, d_w, d_y, m ? m->n_out : 0, cin, cout, dt));
+    void* scratch = nullptr;
+    SP_TRY(static_scratch(&scratch));
+    return conv_gather(m->out_side, m->kvol, m->total, d_x, d_w, false, d_y, cin, cout, dt, (hipStream_t)stream,
+                       scratch, kStaticScratchBytes);
 }
 
 }  // extern "C"

@@ -137,8 +137,9 @@ struct sp_kmap {
 
 namespace sp {
 // conv launchers (sp_conv.hip / sp_wgrad.hip)
+// scratch != null: the call must not allocate; the weight copy of the link-list kernel goes there (forward only)
 int conv_gather(const MapSide& side, int kvol, int64_t total_links, const void* d_f, const void* d_w, bool w_transposed,
-                void* d_g, int cc, int co, sp_dtype dt, hipStream_t s);
+                void* d_g, int cc, int co, sp_dtype dt, hipStream_t s, void* scratch = nullptr, size_t scratch_bytes = 0);
 // wide bf16 layers on maps where most offsets of a row have a neighbour (sp_conv_dense.hip); d_w is [kvol][co][cc]
 bool dense_shape_ok(int cc, int co, sp_dtype dt);
 double dense_min_fill(int cc);
