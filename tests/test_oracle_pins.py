@@ -452,3 +452,159 @@ def test_strided_links_follow_the_position_class(K, stride, ts):
     # and for an even kernel as wide as the stride (offsets 0 .. K-1) the class fixes the offset completely
     if K == stride and K % 2 == 0:
         assert np.array_equal(d, r)
+
+
+# ------------------------------------------------------------------ pooling over kernel maps
+from oracle import pool as opool
+
+
+def _pool_dense_case(seed, K, stride, grid=8, B=2, ch=3, n=260, ties=False):
+    rng = np.random.default_rng(seed)
+    c, _ = oracle.unique_coords(random_coords(rng, n, grid, B))
+    X = rng.standard_normal((len(c), ch))
+    if ties:
+        X = np.round(X)                      # many equal values inside one window
+    cout, _, _ = oracle.strided_coords(c, 1, stride)
+    maps = oracle.kernel_map(c, cout, K, 1)
+    return rng, c, cout, X, maps
+
+
+@pytest.mark.parametrize("K,stride,ties", [(2, 2, False), (3, 1, False), (3, 2, False), (2, 2, True), (3, 1, True)])
+def test_pool_max_equals_dense_max_pool3d_with_autograd(K, stride, ties):
+    grid, B, ch = 8, 2, 3
+    rng, c, cout, X, maps = _pool_dense_case(60 + K + stride, K, stride, grid, B, ch, ties=ties)
+    Y, arg = opool.pool_fwd(*maps, X, len(cout), "max")
+    dY = rng.standard_normal(Y.shape)
+    dX = opool.pool_bwd(*maps, dY, arg, len(c), "max")
+    # dense: absent sites hold -inf, so a window's maximum is the maximum over the inputs present
+    neg = -1e300
+    leaf = torch.from_numpy(X).requires_grad_(True)
+    idx = tuple(torch.from_numpy(c[:, j].astype(np.int64)) for j in range(4))
+    xd = torch.full((B, grid, grid, grid, ch), neg, dtype=torch.float64).index_put(idx, leaf).permute(0, 4, 1, 2, 3)
+    pad = (K - 1) // 2 if K % 2 else 0
+    if pad:
+        xd = torch.nn.functional.pad(xd, (pad,) * 6, value=neg)
+    yd = torch.nn.functional.max_pool3d(xd, K, stride=stride)
+    q = stride
+    got = yd[cout[:, 0], :, cout[:, 1] // q, cout[:, 2] // q, cout[:, 3] // q]
+    assert np.array_equal(Y, got.detach().numpy())
+    if not ties:        # with ties the gradient's destination is a convention (lowest offset), pinned below
+        (got * torch.from_numpy(dY)).sum().backward()
+        assert np.allclose(dX, leaf.grad.numpy(), rtol=0, atol=1e-13)
+
+
+def test_pool_max_ties_go_to_the_lowest_offset_and_gradient_is_conserved():
+    rng, c, cout, X, maps = _pool_dense_case(71, 3, 1, ties=True)
+    pin, pout, counts = maps
+    Y, arg = opool.pool_fwd(*maps, X, len(cout), "max")
+    lists = split_lists(pin, pout, counts)
+    # brute force per output row and channel: the lowest offset among the links attaining the maximum
+    for o in rng.choice(len(cout), 60, replace=False):
+        links = [(k, int(l[l[:, 1] == o][0, 0])) for k, l in enumerate(lists) if (l[:, 1] == o).any()]
+        for ch in range(X.shape[1]):
+            best = max(X[i, ch] for _, i in links)
+            assert Y[o, ch] == best
+            assert arg[o, ch] == min(k for k, i in links if X[i, ch] == best)
+    dY = rng.standard_normal(Y.shape)
+    dX = opool.pool_bwd(*maps, dY, arg, len(c), "max")
+    assert np.allclose(dX.sum(0), dY.sum(0), rtol=0, atol=1e-11)      # every output's gradient lands on one input
+
+
+@pytest.mark.parametrize("K,stride", [(2, 2), (3, 1), (3, 2)])
+def test_pool_avg_and_sum_equal_dense_avg_pool3d_with_autograd(K, stride):
+    grid, B, ch = 8, 2, 3
+    rng, c, cout, X, maps = _pool_dense_case(80 + K + stride, K, stride, grid, B, ch)
+    leaf = torch.from_numpy(X).requires_grad_(True)
+    idx = tuple(torch.from_numpy(c[:, j].astype(np.int64)) for j in range(4))
+    xd = torch.zeros(B, grid, grid, grid, ch, dtype=torch.float64).index_put(idx, leaf).permute(0, 4, 1, 2, 3)
+    occ = torch.zeros(B, 1, grid, grid, grid, dtype=torch.float64)
+    occ[c[:, 0], :, c[:, 1], c[:, 2], c[:, 3]] = 1.0
+    pad = (K - 1) // 2 if K % 2 else 0
+    # avg_pool3d with zero padding counted divides by K^3: times K^3 it is the window sum
+    win_sum = torch.nn.functional.avg_pool3d(xd, K, stride=stride, padding=pad, count_include_pad=True) * K ** 3
+    win_cnt = torch.nn.functional.avg_pool3d(occ, K, stride=stride, padding=pad, count_include_pad=True) * K ** 3
+    q = stride
+    at = (cout[:, 0], slice(None), cout[:, 1] // q, cout[:, 2] // q, cout[:, 3] // q)
+    n_links = opool.link_counts(maps[1], len(cout))
+    assert np.array_equal(n_links, np.rint(win_cnt[at].numpy()[:, 0]).astype(np.int64))
+    for mode, dense in (("sum", win_sum[at]), ("avg", win_sum[at] / win_cnt[at])):
+        Y, arg = opool.pool_fwd(*maps, X, len(cout), mode)
+        assert np.allclose(Y, dense.detach().numpy(), rtol=0, atol=1e-12) and (arg == -1).all()
+        dY = rng.standard_normal(Y.shape)
+        leaf.grad = None
+        (dense * torch.from_numpy(dY)).sum().backward(retain_graph=True)
+        dX = opool.pool_bwd(*maps, dY, arg, len(c), mode)
+        assert np.allclose(dX, leaf.grad.numpy(), rtol=0, atol=1e-12)
+
+
+def test_pool_closed_forms():
+    # a constant feature is its own max and average; its window sum is the link count
+    rng, c, cout, X, maps = _pool_dense_case(90, 3, 2)
+    ones = np.full((len(c), 2), 2.5)
+    n_links = opool.link_counts(maps[1], len(cout))
+    assert (n_links >= 1).all()
+    assert np.array_equal(opool.pool_fwd(*maps, ones, len(cout), "max")[0], np.full((len(cout), 2), 2.5))
+    assert np.allclose(opool.pool_fwd(*maps, ones, len(cout), "avg")[0], 2.5, rtol=0, atol=1e-14)
+    assert np.allclose(opool.pool_fwd(*maps, ones, len(cout), "sum")[0], 2.5 * n_links[:, None])
+    # sum pooling is the convolution of Eq. 2 with every W_k the identity
+    W = np.tile(np.eye(3, dtype=np.float32), (27, 1, 1))
+    Xf = X.astype(np.float32)
+    assert np.allclose(opool.pool_fwd(*maps, Xf, len(cout), "sum")[0], oracle.conv_fwd(*maps, Xf, W, len(cout)), atol=1e-12)
+    assert opool.kernel_offsets(3).tolist() == [list(o) for o in offsets(3)]
+    assert opool.kernel_offsets(2).tolist() == [list(o) for o in offsets(2)]
+
+
+# ------------------------------------------------------------------ generative transposed convolution
+@pytest.mark.parametrize("K,stride,ts_in", [(2, 2, 2), (3, 2, 2), (3, 2, 4), (3, 1, 1), (2, 2, 8)])
+def test_generative_coords_first_occurrence_order_matches_numpy(K, stride, ts_in):
+    rng = np.random.default_rng(100 + K + stride + ts_in)
+    c_in, _ = oracle.unique_coords(random_coords(rng, 300, 6, 2, lo=-3) * np.array([1, ts_in, ts_in, ts_in], np.int32))
+    c_out, where, ts_out = opool.generative_coords(c_in, ts_in, K, stride)
+    assert ts_out == ts_in // stride
+    # candidates written out independently, input row by input row, offsets in offset order
+    cand = np.array([[r[0], r[1] + o[0] * ts_out, r[2] + o[1] * ts_out, r[3] + o[2] * ts_out]
+                     for r in c_in.tolist() for o in offsets(K)], np.int32)
+    u, first, inverse = np.unique(cand, axis=0, return_index=True, return_inverse=True)
+    order = np.argsort(first)
+    assert np.array_equal(c_out, u[order])
+    rank = np.empty_like(order)
+    rank[order] = np.arange(len(order))
+    assert np.array_equal(where.reshape(-1), rank[inverse.reshape(-1)])
+    # the map of the generative layer is the stride-`stride` convolution's map from C_out to C_in, transposed:
+    # every candidate is one link, so each offset has exactly n_in pairs
+    pin, pout, counts = oracle.kernel_map(c_out, c_in, K, ts_out)
+    assert (counts == len(c_in)).all()
+    tin, tout, tcounts = oracle.transpose_map(pin, pout, counts)
+    for k, l in enumerate(split_lists(tin, tout, tcounts)):          # (coarse row, fine row) sorted by coarse row
+        assert np.array_equal(l[:, 0], np.arange(len(c_in))) and np.array_equal(l[:, 1], where[:, k])
+    if K == stride:
+        assert len(c_out) == len(c_in) * K ** 3                      # children of distinct cells never coincide
+
+
+@pytest.mark.parametrize("K,stride", [(2, 2), (3, 2), (3, 1)])
+def test_generative_transposed_conv_equals_dense_conv_transpose3d(K, stride):
+    grid, B, cc, cf = 5, 2, 4, 3            # coarse grid cells, coarse channels (input), fine channels (output)
+    rng = np.random.default_rng(110 + K + stride)
+    cells, _ = oracle.unique_coords(random_coords(rng, 90, grid, B))
+    c_in = cells * np.array([1, stride, stride, stride], np.int32)   # tensor stride = stride, so ts_out = 1
+    c_out, where, ts_out = opool.generative_coords(c_in, stride, K, stride)
+    assert ts_out == 1
+    pin, pout, counts = oracle.kernel_map(c_out, c_in, K, 1)
+    tin, tout, tcounts = oracle.transpose_map(pin, pout, counts)
+    Xc = rng.standard_normal((len(c_in), cc)).astype(np.float32)
+    V = rng.standard_normal((K ** 3, cf, cc)).astype(np.float32)     # [K^3][out = fine ch][in = coarse ch]
+    Z = oracle.conv_fwd(tin, tout, tcounts, Xc, V, len(c_out))
+
+    xd = torch.zeros(B, cc, grid, grid, grid, dtype=torch.float64)
+    xd[cells[:, 0], :, cells[:, 1], cells[:, 2], cells[:, 3]] = torch.from_numpy(Xc.astype(np.float64))
+    wt = torch.from_numpy(V.astype(np.float64)).reshape(K, K, K, cf, cc).permute(4, 3, 0, 1, 2).contiguous()
+    zd = torch.nn.functional.conv_transpose3d(xd, wt, stride=stride)          # zd[s*u + a] += W[a] x[u], a in 0..K-1
+    ctr = (K - 1) // 2 if K % 2 else 0                                         # dense index = coordinate + ctr
+    got = zd[c_out[:, 0], :, c_out[:, 1] + ctr, c_out[:, 2] + ctr, c_out[:, 3] + ctr].numpy()
+    assert np.allclose(Z, got, rtol=0, atol=1e-12)
+    # C_out is exactly the set of sites a transposed convolution with an all-positive kernel reaches
+    reach = torch.nn.functional.conv_transpose3d((xd.abs().sum(1, keepdim=True) > 0).double(),
+                                                 torch.ones(1, 1, K, K, K, dtype=torch.float64), stride=stride)
+    sites = torch.nonzero(reach[:, 0] > 0).numpy()
+    sites[:, 1:] -= ctr
+    assert {tuple(r) for r in sites.tolist()} == {tuple(r) for r in c_out.tolist()}
