@@ -110,6 +110,20 @@ int sp_kmap_table(const sp_kmap_t* m, const int32_t** d_nbr_out, const int32_t**
 
 int sp_kmap_destroy(sp_kmap_t* m);
 
+/* Generative transposed (upsampling) convolution: creates the finer coordinates instead of looking them up in
+ * a cached level.  (The paper defines no transposed convolution; this completes the reading taken by
+ * sp_kmap_transpose for the case where no finer level exists.)  `in` has tensor stride ts_in, a multiple of
+ * `stride`; ts_out = ts_in / stride; the output set is { u + offset_k * ts_out : u in `in`, all K^3 offsets },
+ * duplicates merged, rows numbered in first-occurrence order over the candidates taken input row by input row
+ * and, inside a row, in offset order.  The returned map has the roles of sp_kmap_transpose's result: its
+ * inputs are the rows of `in`, its outputs the created rows, M_k = {(j, o) : c_out[o] = c_in[j] + offset_k *
+ * ts_out}; every offset has exactly n_in pairs.  sp_conv_fwd on it is the transposed convolution
+ * (W[k][cout][cin], cin = channels on `in`); sp_kmap_transpose of it is the stride-`stride` convolution back.
+ * *out_coords' inverse array (sp_coords_data) has K^3 * n_in entries: entry j*K^3 + k is the output row of
+ * candidate (j, k).  Synchronises `stream`.  Caller destroys both handles. */
+int sp_kmap_build_generative(const sp_coords_t* in, int32_t kernel_size, int32_t stride, void* stream,
+                             sp_kmap_t** kmap, sp_coords_t** out_coords);
+
 /* ---- step 3 and its gradients (Eq. 2; Sec. II-A for the backward pass) --------------------------------
  * cin / cout are N_in / N_out of W[kvol][cout][cin].  dt is the storage type of x, w, y, dy, dx
  * (SP_BF16: 16-bit bfloat16, results rounded to nearest even once); accumulation is always fp32.
@@ -142,6 +156,23 @@ int sp_conv_bwd_weight(const sp_kmap_t* m, const void* d_x, const void* d_dy, fl
  * rewritten by every call, nothing in it needs to start at zero. */
 int sp_conv_fwd_noalloc(const sp_kmap_t* m, const void* d_x, const void* d_w, void* d_y, int32_t cin, int32_t cout,
                         sp_dtype dt, void* stream);
+
+/* ---- pooling over a kernel map (Sec. III, caption of the partition-overview figure: pooling layers sit
+ * between the SparseConv blocks; the paper gives no formula) -------------------------------------------------
+ * Eq. 2 with the weighted sum replaced by a reduction over the same neighbour set: for every output row o and
+ * channel, over the inputs i linked to o by any offset of the map,
+ *   SP_POOL_MAX: the maximum;  SP_POOL_SUM: the sum;  SP_POOL_AVG: the sum / number of linked inputs (the
+ *   inputs present, not the kernel volume).  An output without links becomes 0.
+ * x [n_in][c] -> y [n_out][c], storage type dt, accumulation fp32, rounded once.  d_arg (MAX only; may be NULL
+ * if no backward pass follows): uint8 [n_out][c], the offset number of the link that gave the maximum, 255
+ * where the row has no link; among equal maxima the lowest offset number wins.
+ * Backward: dx [n_in][c] from dy [n_out][c]: SUM passes dy to every linked input, AVG dy / links, MAX passes
+ * dy to the input recorded in d_arg.  No atomics, fixed summation order.  No host synchronisation. */
+typedef enum { SP_POOL_MAX = 0, SP_POOL_AVG = 1, SP_POOL_SUM = 2 } sp_pool_mode;
+int sp_pool_fwd(const sp_kmap_t* m, const void* d_x, void* d_y, uint8_t* d_arg, int32_t c, sp_pool_mode mode,
+                sp_dtype dt, void* stream);
+int sp_pool_bwd(const sp_kmap_t* m, const void* d_dy, const uint8_t* d_arg, void* d_dx, int32_t c, sp_pool_mode mode,
+                sp_dtype dt, void* stream);
 
 /* ---- the layers between sparse convolutions ----------------------------------------------------------------
  * (Sec. III, caption of the partition-overview figure: batch normalisation, activation and pooling layers sit

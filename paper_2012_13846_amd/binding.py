@@ -43,6 +43,9 @@ def lib() -> C.CDLL:
         l.sp_coords_destroy.argtypes = [_vp]
         l.sp_kmap_build.argtypes = [_vp, C.c_int32, C.c_int32, C.c_int32, _vp, C.POINTER(_vp), C.POINTER(_vp)]
         l.sp_kmap_transpose.argtypes = [_vp, C.POINTER(_vp)]
+        l.sp_kmap_build_generative.argtypes = [_vp, C.c_int32, C.c_int32, _vp, C.POINTER(_vp), C.POINTER(_vp)]
+        l.sp_pool_fwd.argtypes = [_vp, _vp, _vp, _vp, C.c_int32, C.c_int32, C.c_int32, _vp]
+        l.sp_pool_bwd.argtypes = [_vp, _vp, _vp, _vp, C.c_int32, C.c_int32, C.c_int32, _vp]
         l.sp_kmap_info.argtypes = [_vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int32),
                                    C.POINTER(C.c_int64), _vp]
         l.sp_kmap_pairs.argtypes = [_vp, C.POINTER(_vp), C.POINTER(_vp)]
@@ -174,6 +177,14 @@ def sp_kmap_build(coords: Coords, kernel_size: int, stride: int = 1, dilation: i
     return KMap(hk), Coords(hc)
 
 
+def sp_kmap_build_generative(coords: Coords, kernel_size: int, stride: int = 1):
+    """Generative transposed convolution: returns (KMap with inputs = `coords`' rows and outputs = the created
+    rows, Coords of the created rows)."""
+    hk, hc = _vp(), _vp()
+    _check(lib().sp_kmap_build_generative(coords._h, kernel_size, stride, _stream(), C.byref(hk), C.byref(hc)))
+    return KMap(hk), Coords(hc)
+
+
 def sp_kmap_transpose(kmap: KMap) -> KMap:
     h = _vp()
     _check(lib().sp_kmap_transpose(kmap._h, C.byref(h)))
@@ -239,6 +250,36 @@ def sp_conv_bwd_weight(kmap: KMap, x: torch.Tensor, dy: torch.Tensor, out: torch
         raise ValueError("out has the wrong shape")
     _check(lib().sp_conv_bwd_weight(kmap._h, x.data_ptr(), dy.data_ptr(), dw.data_ptr(), cin, cout, _dt(x), _stream()))
     return dw
+
+
+SP_POOL_MAX, SP_POOL_AVG, SP_POOL_SUM = 0, 1, 2
+_POOL_MODES = {"max": SP_POOL_MAX, "avg": SP_POOL_AVG, "sum": SP_POOL_SUM}
+
+
+def sp_pool_fwd(kmap: KMap, x: torch.Tensor, mode: str, want_arg: bool = True):
+    """Pooling over the map's neighbour sets.  Returns (y [n_out][c], arg uint8 [n_out][c] or None)."""
+    _need_cuda(x, None, "x")
+    if x.shape[0] != kmap.n_in:
+        raise ValueError("x does not have the map's input rows")
+    c = x.shape[1]
+    y = torch.empty((kmap.n_out, c), dtype=x.dtype, device=x.device)
+    arg = torch.empty((kmap.n_out, c), dtype=torch.uint8, device=x.device) if (mode == "max" and want_arg) else None
+    _check(lib().sp_pool_fwd(kmap._h, x.data_ptr() if x.numel() else None, y.data_ptr() if y.numel() else None,
+                             arg.data_ptr() if arg is not None and arg.numel() else None, c, _POOL_MODES[mode], _dt(x),
+                             _stream()))
+    return y, arg
+
+
+def sp_pool_bwd(kmap: KMap, dy: torch.Tensor, arg, mode: str) -> torch.Tensor:
+    _need_cuda(dy, None, "dy")
+    if dy.shape[0] != kmap.n_out:
+        raise ValueError("dy does not have the map's output rows")
+    c = dy.shape[1]
+    dx = torch.empty((kmap.n_in, c), dtype=dy.dtype, device=dy.device)
+    _check(lib().sp_pool_bwd(kmap._h, dy.data_ptr() if dy.numel() else None,
+                             arg.data_ptr() if arg is not None and arg.numel() else None,
+                             dx.data_ptr() if dx.numel() else None, c, _POOL_MODES[mode], _dt(dy), _stream()))
+    return dx
 
 
 def sp_pool_trim():

@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <functional>
 #include <memory>
+#include <mutex>
 #include <vector>
 
 #include "sp_conv.h"
@@ -133,6 +134,9 @@ struct sp_kmap {
     sp::Buf d_koff;                // int32 [kvol+1], the same prefix on the device
     sp_coords* c_in = nullptr;     // references held
     sp_coords* c_out = nullptr;
+    // filled on first use (average pooling's backward pass): links per output row, int32 [n_out]
+    mutable std::mutex cache_mu;
+    mutable sp::Buf out_link_cnt;
 };
 
 namespace sp {

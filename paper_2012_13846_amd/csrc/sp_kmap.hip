@@ -289,6 +289,37 @@ int build_classes(MapSide& side, const sp_coords* c, int stride, int K, hipStrea
     return SP_OK;
 }
 
+// Generative transposed convolution.  Candidate (j, k) = input row j displaced by offset k times the output
+// lattice step; rows (j*kvol + k) of cand, i.e. input row by input row, offsets in offset order.
+__global__ __launch_bounds__(kThreads) void gen_candidates_kernel(const int4* __restrict__ c_in, int64_t n_in, int K,
+                                                                  int step, int4* __restrict__ cand) {
+    const int kvol = K * K * K;
+    const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (t >= n_in * kvol) return;
+    const int64_t j = t / kvol;
+    const int k = (int)(t % kvol);
+    const int centre = (K & 1) ? (K - 1) / 2 : 0;
+    int4 c = c_in[j];
+    c.y += (k / (K * K) - centre) * step;
+    c.z += (k / K % K - centre) * step;
+    c.w += (k % K - centre) * step;
+    cand[t] = c;
+}
+
+// where[j*kvol + k] = fine row of candidate (j, k).  As a stride-s convolution from the fine rows (inputs) to
+// the coarse rows (outputs) every candidate is one link: nbr_out[k][j] = that fine row, nbr_in[k][fine] = j.
+__global__ __launch_bounds__(kThreads) void gen_tables_kernel(const int32_t* __restrict__ where, int64_t n_coarse,
+                                                              int64_t n_fine, int kvol, int32_t* __restrict__ nbr_out,
+                                                              int32_t* __restrict__ nbr_in) {
+    const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;   // = k * n_coarse + j: coalesced table writes
+    if (t >= n_coarse * kvol) return;
+    const int k = (int)(t / n_coarse);
+    const int64_t j = t % n_coarse;
+    const int32_t f = where[j * kvol + k];
+    nbr_out[t] = f;
+    nbr_in[(int64_t)k * n_fine + f] = (int32_t)j;
+}
+
 // Turns sub-tile counts (already in side.tl_off) into offsets and fills the tile lists.
 // `total`: the number of links, or any upper bound of it (the lists are then allocated larger than needed).
 int finish_side(MapSide& side, int kvol, int64_t total, const int32_t* d_blk_off, int32_t* d_pair_in,
@@ -302,6 +333,84 @@ int finish_side(MapSide& side, int kvol, int64_t total, const int32_t* d_blk_off
                            side.n_rows, ptr<int32_t>(side.tl_off), ptr<int32_t>(side.tl_src),
                            ptr<uint16_t>(side.tl_row), d_blk_off, d_pair_in, d_pair_out);
     SP_HIP(hipGetLastError());
+    return SP_OK;
+}
+
+
+// Second half of a map build, shared by every way of filling the neighbour tables: on entry both tables are
+// complete, so.tl_off holds the output side's link counts per (sub-tile, offset, half) and blk those per
+// (offset, tile).  Scans them, reads the per-offset pair counts back, and compacts the tables into the pair
+// lists and the tile lists of both sides (a symmetric map shares one table and one set of lists).
+int finish_map(sp_kmap* m, bool symmetric, const Buf& blk, const Buf& small, hipStream_t s) {
+    MapSide& so = m->out_side;
+    MapSide& si = m->in_side;
+    sp_coords* cin = m->c_in;
+    const int kvol = m->kvol, stride = m->stride, kernel_size = m->K;
+    const int64_t n_in = m->n_in, n_out = m->n_out;
+    const int64_t nt_out = (n_out + kTileRows - 1) / kTileRows, nt_in = (n_in + kTileRows - 1) / kTileRows;
+    int32_t* d_koff = ptr<int32_t>(small);
+    // both scans in one launch pair: sub-tile-major list offsets, and offset-major pair-list offsets whose
+    // values at the start of each offset (every nt_out-th element) are the per-offset prefix koff[]
+    {
+        const int64_t n_sub = nt_out * kvol * kSubTiles * kHalves;
+        ScanJob jobs[2];
+        jobs[0].data = ptr<int32_t>(so.tl_off);
+        jobs[0].n = n_sub;
+        jobs[0].total = ptr<int32_t>(so.tl_off) + n_sub;
+        jobs[1].data = ptr<int32_t>(blk);
+        jobs[1].n = nt_out * kvol;
+        jobs[1].koff = d_koff;
+        jobs[1].koff_stride = nt_out > 0 ? nt_out : 1;
+        jobs[1].koff_n = kvol;
+        SP_TRY(exclusive_scan_jobs(jobs, 2, s));
+    }
+    // The host needs the pair counts (for its own bookkeeping and the callers'), the device does not: unless
+    // the lists would be huge, they are allocated for the most links there can be and the compaction is
+    // enqueued behind the read-back, so the GPU does not idle while the host wakes up and launches.
+    const int64_t most = std::min(n_out, n_in) * kvol;
+    const bool early = most * 14 <= ((int64_t)512 << 20);
+    int early_rc = SP_OK;
+    auto emit_out_side = [&](int64_t total) {
+        m->pair_in = dev_alloc((size_t)(total ? total : 1) * 4, s);
+        m->pair_out = dev_alloc((size_t)(total ? total : 1) * 4, s);
+        if (!m->pair_in || !m->pair_out) return (int)SP_ERR_ALLOC;
+        return finish_side(so, kvol, total, ptr<int32_t>(blk), ptr<int32_t>(m->pair_in), ptr<int32_t>(m->pair_out), s);
+    };
+    // the input side of a map without the stride-1 symmetry: its own counts, list offsets, lists and classes
+    auto emit_in_side = [&](int64_t total) {
+        if (nt_in > 0)
+            hipLaunchKernelGGL(count_kernel, dim3((unsigned)nt_in, kvol), dim3(kThreads), 0, s, ptr<int32_t>(si.nbr),
+                               n_in, ptr<int32_t>(si.tl_off), (int32_t*)nullptr);
+        const int64_t n_sub_in = nt_in * kvol * kSubTiles * kHalves;
+        ScanJob job;
+        job.data = ptr<int32_t>(si.tl_off);
+        job.n = n_sub_in;
+        job.total = ptr<int32_t>(si.tl_off) + n_sub_in;
+        SP_TRY(exclusive_scan_jobs(&job, 1, s));
+        SP_TRY(finish_side(si, kvol, total, nullptr, nullptr, nullptr, s));
+        if (stride > 1) SP_TRY(build_classes(si, cin, stride, kernel_size, s));
+        return (int)SP_OK;
+    };
+    std::vector<int32_t> h_koff(kvol + 1);
+    SP_TRY(read_back(h_koff.data(), d_koff, (size_t)(kvol + 1) * 4, s, [&]() {
+        if (!early) return;
+        early_rc = emit_out_side(most);
+        if (early_rc == SP_OK && !symmetric) early_rc = emit_in_side(most);
+    }));
+    SP_TRY(early_rc);
+    m->koff.resize(kvol + 1);
+    m->counts.resize(kvol);
+    for (int k = 0; k <= kvol; ++k) m->koff[k] = h_koff[k];
+    for (int k = 0; k < kvol; ++k) m->counts[k] = m->koff[k + 1] - m->koff[k];
+    m->total = m->koff[kvol];
+    m->d_koff = small;
+    if (!early) SP_TRY(emit_out_side(m->total));
+    if (symmetric) {
+        si = so;  // same lists; the link (i, o) at offset k is the link (o, i) at offset kvol-1-k
+        si.flip = true;
+    } else if (!early) {
+        SP_TRY(emit_in_side(m->total));
+    }
     return SP_OK;
 }
 
@@ -369,7 +478,6 @@ int sp_kmap_build(const sp_coords_t* in, int32_t kernel_size, int32_t stride, in
             hipLaunchKernelGGL(fill_i32_kernel, dim3(blocks256(n_in * kvol)), dim3(256), 0, s, ptr<int32_t>(si.nbr),
                                n_in * kvol, -1);
     }
-    int32_t* d_koff = ptr<int32_t>(small);
     const bool children = stride > 1 && kernel_size == stride && kernel_size % 2 == 0;
     if (nt_out > 0 && children) {
         hipLaunchKernelGGL(fill_i32_kernel, dim3(blocks256(n_out * (int64_t)kvol)), dim3(256), 0, s, ptr<int32_t>(so.nbr),
@@ -408,73 +516,87 @@ int sp_kmap_build(const sp_coords_t* in, int32_t kernel_size, int32_t stride, in
                                n_out, ptr<int32_t>(so.tl_off), ptr<int32_t>(blk));
     }
     SP_HIP(hipGetLastError());
-    // both scans in one launch pair: sub-tile-major list offsets, and offset-major pair-list offsets whose
-    // values at the start of each offset (every nt_out-th element) are the per-offset prefix koff[]
-    {
-        const int64_t n_sub = nt_out * kvol * kSubTiles * kHalves;
-        ScanJob jobs[2];
-        jobs[0].data = ptr<int32_t>(so.tl_off);
-        jobs[0].n = n_sub;
-        jobs[0].total = ptr<int32_t>(so.tl_off) + n_sub;
-        jobs[1].data = ptr<int32_t>(blk);
-        jobs[1].n = nt_out * kvol;
-        jobs[1].koff = d_koff;
-        jobs[1].koff_stride = nt_out > 0 ? nt_out : 1;
-        jobs[1].koff_n = kvol;
-        SP_TRY(exclusive_scan_jobs(jobs, 2, s));
-    }
-    // The host needs the pair counts (for its own bookkeeping and the callers'), the device does not: unless
-    // the lists would be huge, they are allocated for the most links there can be and the compaction is
-    // enqueued behind the read-back, so the GPU does not idle while the host wakes up and launches.
-    const int64_t most = std::min(n_out, n_in) * kvol;
-    const bool early = most * 14 <= ((int64_t)512 << 20);
-    int early_rc = SP_OK;
-    auto emit_out_side = [&](int64_t total) {
-        m->pair_in = dev_alloc((size_t)(total ? total : 1) * 4, s);
-        m->pair_out = dev_alloc((size_t)(total ? total : 1) * 4, s);
-        if (!m->pair_in || !m->pair_out) return (int)SP_ERR_ALLOC;
-        return finish_side(so, kvol, total, ptr<int32_t>(blk), ptr<int32_t>(m->pair_in), ptr<int32_t>(m->pair_out), s);
-    };
-    // the input side of a map without the stride-1 symmetry: its own counts, list offsets, lists and classes
-    auto emit_in_side = [&](int64_t total) {
-        if (nt_in > 0)
-            hipLaunchKernelGGL(count_kernel, dim3((unsigned)nt_in, kvol), dim3(kThreads), 0, s, ptr<int32_t>(si.nbr),
-                               n_in, ptr<int32_t>(si.tl_off), (int32_t*)nullptr);
-        const int64_t n_sub_in = nt_in * kvol * kSubTiles * kHalves;
-        ScanJob job;
-        job.data = ptr<int32_t>(si.tl_off);
-        job.n = n_sub_in;
-        job.total = ptr<int32_t>(si.tl_off) + n_sub_in;
-        SP_TRY(exclusive_scan_jobs(&job, 1, s));
-        SP_TRY(finish_side(si, kvol, total, nullptr, nullptr, nullptr, s));
-        if (stride > 1) SP_TRY(build_classes(si, cin, stride, kernel_size, s));
-        return (int)SP_OK;
-    };
-    std::vector<int32_t> h_koff(kvol + 1);
-    SP_TRY(read_back(h_koff.data(), d_koff, (size_t)(kvol + 1) * 4, s, [&]() {
-        if (!early) return;
-        early_rc = emit_out_side(most);
-        if (early_rc == SP_OK && !symmetric) early_rc = emit_in_side(most);
-    }));
-    SP_TRY(early_rc);
-    m->koff.resize(kvol + 1);
-    m->counts.resize(kvol);
-    for (int k = 0; k <= kvol; ++k) m->koff[k] = h_koff[k];
-    for (int k = 0; k < kvol; ++k) m->counts[k] = m->koff[k + 1] - m->koff[k];
-    m->total = m->koff[kvol];
-    m->d_koff = small;
-    if (!early) SP_TRY(emit_out_side(m->total));
-    if (symmetric) {
-        si = so;  // same lists; the link (i, o) at offset k is the link (o, i) at offset kvol-1-k
-        si.flip = true;
-    } else if (!early) {
-        SP_TRY(emit_in_side(m->total));
-    }
+    SP_TRY(finish_map(m.get(), symmetric, blk, small, s));
     if (out_coords) {
         m->c_out->ref.fetch_add(1);
         *out_coords = m->c_out;
     }
     *kmap = m.release();
+    return SP_OK;
+}
+
+int sp_kmap_build_generative(const sp_coords_t* in, int32_t kernel_size, int32_t stride, void* stream, sp_kmap_t** kmap,
+                             sp_coords_t** out_coords) {
+    if (kmap) *kmap = nullptr;
+    if (out_coords) *out_coords = nullptr;
+    if (!in || !kmap) return fail(SP_ERR_INVALID_ARG, "coords handle or kmap out pointer is NULL");
+    if (kernel_size < 1 || kernel_size > 5) return fail(SP_ERR_INVALID_ARG, "kernel_size %d not in 1..5", kernel_size);
+    if (stride < 1) return fail(SP_ERR_INVALID_ARG, "stride must be >= 1");
+    if (in->ts % stride != 0)
+        return fail(SP_ERR_INVALID_ARG, "the tensor stride (%d) must be a multiple of the layer stride (%d)", in->ts, stride);
+    hipStream_t s = (hipStream_t)stream;
+    const int kvol = kernel_size * kernel_size * kernel_size;
+    const int64_t n_coarse = in->n, n_cand = n_coarse * kvol;
+    if (n_cand >= ((int64_t)1 << 30)) return fail(SP_ERR_INVALID_ARG, "n * kernel volume exceeds 2^30 candidates");
+    const int ts_out = in->ts / stride;
+
+    // candidates -> fine coordinates (first-occurrence order) and the candidate -> fine row table
+    Buf cand = dev_alloc((size_t)(n_cand ? n_cand : 1) * 16, s);
+    if (!cand) return SP_ERR_ALLOC;
+    if (n_cand > 0)
+        hipLaunchKernelGGL(gen_candidates_kernel, dim3(blocks256(n_cand)), dim3(kThreads), 0, s, ptr<int4>(in->coords),
+                           n_coarse, kernel_size, ts_out, ptr<int4>(cand));
+    SP_HIP(hipGetLastError());
+    sp_coords* fine = nullptr;
+    SP_TRY(coords_build_impl(ptr<int32_t>(cand), n_cand, 1, ts_out, s, &fine));
+
+    // the stride-s convolution's map from the fine rows (inputs) to the coarse rows (outputs) ...
+    std::unique_ptr<sp_kmap, int (*)(sp_kmap*)> m(new sp_kmap, sp_kmap_destroy);
+    m->K = kernel_size;
+    m->kvol = kvol;
+    m->stride = stride;
+    m->dilation = 1;
+    m->c_in = fine;  // takes over the reference
+    sp_coords* coarse = const_cast<sp_coords*>(in);
+    coarse->ref.fetch_add(1);
+    m->c_out = coarse;
+    const int64_t n_fine = fine->n;
+    m->n_in = n_fine;
+    m->n_out = n_coarse;
+    if (n_fine * (int64_t)kvol >= ((int64_t)1 << 31) - 4096)
+        return fail(SP_ERR_INVALID_ARG, "n * kernel volume exceeds 32-bit list offsets");
+    const int64_t nt_out = (n_coarse + kTileRows - 1) / kTileRows, nt_in = (n_fine + kTileRows - 1) / kTileRows;
+    MapSide& so = m->out_side;
+    MapSide& si = m->in_side;
+    so.n_rows = n_coarse;
+    so.n_src = n_fine;
+    si.n_rows = n_fine;
+    si.n_src = n_coarse;
+    so.nbr = dev_alloc((size_t)(n_cand ? n_cand : 1) * 4, s);
+    so.tl_off = dev_alloc((size_t)(nt_out * kvol * kSubTiles * kHalves + 1) * 4, s);
+    si.nbr = dev_alloc((size_t)(n_fine ? n_fine : 1) * kvol * 4, s);
+    si.tl_off = dev_alloc((size_t)(nt_in * kvol * kSubTiles * kHalves + 1) * 4, s);
+    Buf blk = dev_alloc((size_t)(nt_out * kvol + 1) * 4, s);
+    Buf small = dev_alloc((size_t)(kvol + 2) * 4, s);
+    if (!so.nbr || !so.tl_off || !si.nbr || !si.tl_off || !blk || !small) return SP_ERR_ALLOC;
+    if (n_cand > 0) {
+        hipLaunchKernelGGL(fill_i32_kernel, dim3(blocks256(n_fine * kvol)), dim3(256), 0, s, ptr<int32_t>(si.nbr),
+                           n_fine * kvol, -1);
+        hipLaunchKernelGGL(gen_tables_kernel, dim3(blocks256(n_cand)), dim3(kThreads), 0, s, ptr<int32_t>(fine->inverse),
+                           n_coarse, n_fine, kvol, ptr<int32_t>(so.nbr), ptr<int32_t>(si.nbr));
+        hipLaunchKernelGGL(count_kernel, dim3((unsigned)nt_out, kvol), dim3(kThreads), 0, s, ptr<int32_t>(so.nbr), n_coarse,
+                           ptr<int32_t>(so.tl_off), ptr<int32_t>(blk));
+    }
+    SP_HIP(hipGetLastError());
+    SP_TRY(finish_map(m.get(), false, blk, small, s));
+    // ... handed out with the roles swapped: inputs = the given (coarse) rows, outputs = the created rows
+    sp_kmap_t* t = nullptr;
+    SP_TRY(sp_kmap_transpose(m.get(), &t));
+    if (out_coords) {
+        fine->ref.fetch_add(1);
+        *out_coords = fine;
+    }
+    *kmap = t;
     return SP_OK;
 }
 
