@@ -608,3 +608,34 @@ def test_generative_transposed_conv_equals_dense_conv_transpose3d(K, stride):
     sites = torch.nonzero(reach[:, 0] > 0).numpy()
     sites[:, 1:] -= ctr
     assert {tuple(r) for r in sites.tolist()} == {tuple(r) for r in c_out.tolist()}
+
+
+# ------------------------------------------------------------------ stage-boundary packing of (C, F)
+from oracle import pack as opack
+
+
+@pytest.mark.parametrize("n,c,dtype", [(0, 8, 0), (1, 1, 1), (1001, 5, 0), (777, 3, 1), (4096, 64, 1)])
+def test_pack_layout_parsed_independently_and_round_trip(n, c, dtype):
+    import struct
+    rng = np.random.default_rng(n + c)
+    coords = rng.integers(-30000, 30000, (n, 4)).astype(np.int32)
+    feats = rng.standard_normal((n, c)).astype(np.float32)
+    bits = feats if dtype == 0 else spgen.f32_to_bf16_bits(feats)
+    buf = opack.pack(coords, bits, dtype, 4)
+    raw = buf.tobytes()
+    magic, ver, nn, cc, dd, ts, zero, c_off, f_off, total = struct.unpack("<4sIqiiiiqqq", raw[:56])
+    assert (magic, ver, nn, cc, dd, ts, zero) == (b"SPCF", 1, n, c, dtype, 4, 0)
+    elt = 4 if dtype == 0 else 2
+    up = lambda v: -(-v // 256) * 256
+    assert (c_off, f_off, total) == (256, 256 + up(16 * n), 256 + up(16 * n) + up(n * c * elt))
+    assert len(raw) == total == opack.packed_bytes(n, c, dtype)
+    assert raw[c_off:c_off + 16 * n] == coords.tobytes()
+    assert raw[f_off:f_off + n * c * elt] == bits.tobytes()
+    payload = set(range(c_off, c_off + 16 * n)) | set(range(f_off, f_off + n * c * elt)) | set(range(56))
+    assert all(raw[i] == 0 for i in range(total) if i not in payload and i < 4096)    # padding is zero
+    c2, f2, d2, ts2 = opack.unpack(buf)
+    assert np.array_equal(c2, coords) and np.array_equal(f2, bits) and (d2, ts2) == (dtype, 4)
+    bad = buf.copy()
+    bad[0] = 0
+    with pytest.raises(ValueError):
+        opack.unpack(bad)
