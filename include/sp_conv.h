@@ -213,6 +213,25 @@ int sp_linear_bwd(const float* d_in, const float* d_w, const float* d_dout, int3
 int sp_softmax_ce(const float* d_logits, const int32_t* d_labels, int32_t n_clouds, int32_t m, float* d_loss,
                   float* d_dlogits, void* stream);
 
+/* ---- stage-boundary packing of a sparse tensor (Sec. III-B, last paragraph: the coordinate matrix and the
+ * feature matrix are what is exchanged between pipeline stages) ---------------------------------------------
+ * (C, F) -> one contiguous device buffer that any transport can send as a single message, and back.  Layout,
+ * little-endian, every section 256-byte aligned, padding zero:
+ *   0 "SPCF" | 4 u32 version (1) | 8 i64 n | 16 i32 channels | 20 i32 dtype | 24 i32 tensor stride | 28 0 |
+ *   32 i64 coordinates offset (256) | 40 i64 features offset | 48 i64 total bytes | 56..255 0 |
+ *   coordinates int32 [n][4] | features [n][channels]
+ * sp_pack_bytes: size of the buffer (-1 for invalid sizes).  sp_pack: one kernel launch, no synchronisation;
+ * d_buf (caller-owned, >= sp_pack_bytes, 256-byte aligned) is fully written, header included.
+ * sp_unpack_info: reads the header back to the host (synchronises `stream`) and validates it.
+ * sp_unpack: one kernel launch; d_coords int32 [n][4] and d_feats [n][c] are caller-owned; n, c, dt are the
+ * header's values as sp_unpack_info returned them. */
+int64_t sp_pack_bytes(int64_t n, int32_t c, sp_dtype dt);
+int sp_pack(const int32_t* d_coords, const void* d_feats, int64_t n, int32_t c, sp_dtype dt, int32_t tensor_stride,
+            void* d_buf, void* stream);
+int sp_unpack_info(const void* d_buf, void* stream, int64_t* n, int32_t* c, sp_dtype* dt, int32_t* tensor_stride,
+                   int64_t* total_bytes);
+int sp_unpack(const void* d_buf, int64_t n, int32_t c, sp_dtype dt, int32_t* d_coords, void* d_feats, void* stream);
+
 /* ---- housekeeping -------------------------------------------------------------------------------------- */
 const char* sp_last_error(void);  /* message of the calling thread's last failure ("" if none) */
 

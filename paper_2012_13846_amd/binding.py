@@ -252,6 +252,46 @@ def sp_conv_bwd_weight(kmap: KMap, x: torch.Tensor, dy: torch.Tensor, out: torch
     return dw
 
 
+def sp_pack(coords: torch.Tensor, feats: torch.Tensor, tensor_stride: int = 1) -> torch.Tensor:
+    """(C, F) -> one contiguous uint8 device buffer (header + coordinates + features)."""
+    _need_cuda(coords, torch.int32, "coords"), _need_cuda(feats, None, "feats")
+    n, c = feats.shape
+    if tuple(coords.shape) != (n, 4):
+        raise ValueError("coords must be [n][4] with the features' row count")
+    l = lib()
+    l.sp_pack_bytes.restype = C.c_int64
+    l.sp_pack_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int32]
+    l.sp_pack.argtypes = [_vp, _vp, C.c_int64, C.c_int32, C.c_int32, C.c_int32, _vp, _vp]
+    total = l.sp_pack_bytes(n, c, _dt(feats))
+    if total < 0:
+        raise ValueError("sizes cannot be packed")
+    buf = torch.empty(total, dtype=torch.uint8, device=feats.device)
+    _check(l.sp_pack(coords.data_ptr() if n else None, feats.data_ptr() if n else None, n, c, _dt(feats), tensor_stride,
+                     buf.data_ptr(), _stream()))
+    return buf
+
+
+def sp_unpack(buf: torch.Tensor):
+    """Packed buffer -> (coords int32 [n][4], feats [n][c], tensor_stride)."""
+    _need_cuda(buf, torch.uint8, "buf")
+    l = lib()
+    l.sp_unpack_info.argtypes = [_vp, _vp, C.POINTER(C.c_int64), C.POINTER(C.c_int32), C.POINTER(C.c_int32),
+                                 C.POINTER(C.c_int32), C.POINTER(C.c_int64)]
+    l.sp_unpack.argtypes = [_vp, C.c_int64, C.c_int32, C.c_int32, _vp, _vp, _vp]
+    n, c, dt, ts, total = C.c_int64(), C.c_int32(), C.c_int32(), C.c_int32(), C.c_int64()
+    if buf.numel() < 256:
+        raise ValueError("buffer shorter than a header")
+    _check(l.sp_unpack_info(buf.data_ptr(), _stream(), C.byref(n), C.byref(c), C.byref(dt), C.byref(ts), C.byref(total)))
+    if total.value > buf.numel():
+        raise ValueError("buffer shorter than its header says")
+    coords = torch.empty((n.value, 4), dtype=torch.int32, device=buf.device)
+    feats = torch.empty((n.value, c.value), dtype=torch.float32 if dt.value == SP_F32 else torch.bfloat16,
+                        device=buf.device)
+    _check(l.sp_unpack(buf.data_ptr(), n.value, c.value, dt.value, coords.data_ptr() if n.value else None,
+                       feats.data_ptr() if n.value else None, _stream()))
+    return coords, feats, ts.value
+
+
 SP_POOL_MAX, SP_POOL_AVG, SP_POOL_SUM = 0, 1, 2
 _POOL_MODES = {"max": SP_POOL_MAX, "avg": SP_POOL_AVG, "sum": SP_POOL_SUM}
 
