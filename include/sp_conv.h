@@ -253,6 +253,10 @@ int sp_pool_trim(void);           /* synchronises the device and frees all cache
 int64_t sp_pool_bytes(void);      /* device bytes currently held by the pool (in use + cached) */
 int64_t sp_pool_cross_stream(void); /* blocks handed from one stream to another so far (diagnostics) */
 const char* sp_version(void);
+/* Name of the gather kernel that sp_conv_fwd (direction 0) or sp_conv_bwd_data (direction 1) launches for this
+ * map and these channel counts ("" for invalid arguments).  For benchmarks and profiles that must name the
+ * kernel they time; the choice itself is the library's and may change between versions. */
+const char* sp_conv_kernel_name(const sp_kmap_t* m, int32_t cin, int32_t cout, sp_dtype dt, int32_t direction);
 
 #ifdef __cplusplus
 }

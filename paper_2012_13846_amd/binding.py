@@ -381,6 +381,13 @@ def sp_pool_bytes() -> int:
     return int(lib().sp_pool_bytes())
 
 
+def sp_conv_kernel_name(kmap: KMap, cin: int, cout: int, dtype: torch.dtype, direction: int = 0) -> str:
+    l = lib()
+    l.sp_conv_kernel_name.restype = C.c_char_p
+    l.sp_conv_kernel_name.argtypes = [_vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+    return l.sp_conv_kernel_name(kmap._h, cin, cout, SP_F32 if dtype == torch.float32 else SP_BF16, direction).decode()
+
+
 def sp_version() -> str:
     return lib().sp_version().decode()
 

@@ -634,17 +634,28 @@ int launch_gather(GatherArgs a, hipStream_t s) {
     return SP_OK;
 }
 
+// Narrow layers take the wavefront-private kernel, with the widest channel tile whose weight matrix fits in
+// 32 fragment registers (CC/group * COT/16 fragments of 4 registers each).  Returns that tile, or 0 when the
+// workgroup-cooperative kernel takes the layer.
+int wave_tile(int cc, int co, bool is_f32, bool wave_ok) {
+    const int groups = cc / (is_f32 ? 16 : 32);
+    if (!wave_ok) return 0;
+    if (groups * 4 <= 8 && co % 64 == 0) return 64;
+    if (groups * 2 <= 8 && co % 32 == 0) return 32;
+    if (groups <= 2 && (co == 16 || co == 48)) return 16;
+    return 0;
+}
+
 template <typename T, int CC>
 int dispatch_co(const GatherArgs& a, hipStream_t s) {
-    // Narrow layers: the wavefront-private kernel, with the widest channel tile whose weight matrix fits
-    // in 32 fragment registers (CC/group * COT/16 fragments of 4 registers each).
     constexpr int kGroups = CC / (std::is_same<T, float>::value ? 16 : 32);
+    const int cot = wave_tile(CC, a.co_total, std::is_same<T, float>::value, a.wave_ok != 0);
     if constexpr (kGroups * 4 <= 8)
-        if (a.wave_ok && a.co_total % 64 == 0) return launch_wave<T, CC, 64>(a, s);
+        if (cot == 64) return launch_wave<T, CC, 64>(a, s);
     if constexpr (kGroups * 2 <= 8)
-        if (a.wave_ok && a.co_total % 32 == 0) return launch_wave<T, CC, 32>(a, s);
+        if (cot == 32) return launch_wave<T, CC, 32>(a, s);
     if constexpr (kGroups <= 2)
-        if (a.wave_ok && (a.co_total == 16 || a.co_total == 48)) return launch_wave<T, CC, 16>(a, s);
+        if (cot == 16) return launch_wave<T, CC, 16>(a, s);
     // Wide layers: workgroup-cooperative kernel; rows per workgroup keep accumulator + staging within
     // ~64 KB so two workgroups share a CU
     if (a.co_total % 64 == 0) return launch_gather<T, CC, 64, 128>(a, s);
@@ -675,6 +686,29 @@ bool mma_shape_ok(int cc, int co, sp_dtype dt) {
 
 }  // namespace
 
+namespace {
+// Which gather kernel a layer takes: 0 row-stationary (sp_conv_dense.hip), 1 wavefront-private link lists,
+// 2 workgroup-cooperative link lists, 3 plain.
+int select_gather(const MapSide& side, int kvol, int64_t total_links, int cc, int co, sp_dtype dt) {
+    const size_t elt = dt == SP_F32 ? 4 : 2;
+    // Row-stationary kernel: it multiplies all kvol offsets of every row, the link-list kernels only the links
+    // that exist but pay per link for bookkeeping, weight re-reads and the accumulator update.  Measured, it is
+    // the faster one from about 1 link in 20 row-offsets upwards on 128- and 256-channel inputs, from 1 in 4
+    // on 64-channel inputs.
+    // (A side with position classes skips the offsets its tiles cannot have: its cost follows the links.)
+    const uint64_t lim = 0x7fffffffull;
+    if (dense_shape_ok(cc, co, dt) &&
+        (side.tile_mask || (double)total_links >= dense_min_fill(cc) * (double)side.n_rows * kvol) &&
+        (uint64_t)side.n_src * cc * elt < lim && (uint64_t)side.n_rows * kvol * 4 < lim && (uint64_t)kvol * cc * co * elt < lim)
+        return 0;
+    if (mma_shape_ok(cc, co, dt)) {
+        const bool wave_ok = (uint64_t)side.n_src * cc * elt < 0xffffffffull && (uint64_t)total_links * 4 < 0xffffffffull;
+        return wave_tile(cc, co, dt == SP_F32, wave_ok) ? 1 : 2;
+    }
+    return 3;
+}
+}  // namespace
+
 // side: which rows are destinations.  w_transposed = false: W[k][co][cc] as stored (forward);
 // true: the stored W is [k][cc][co] (data gradient), transposed into pool memory first for the MFMA path.
 int conv_gather(const MapSide& side, int kvol, int64_t total_links, const void* d_f, const void* d_w, bool w_transposed,
@@ -682,16 +716,8 @@ int conv_gather(const MapSide& side, int kvol, int64_t total_links, const void* 
     if (side.n_rows == 0) return SP_OK;
     if (scratch && w_transposed) return fail(SP_ERR_UNSUPPORTED, "no allocation-free path for transposed weights");
     const size_t elt = dt == SP_F32 ? 4 : 2;
-    // Row-stationary kernel: it multiplies all kvol offsets of every row, the link-list kernels only the links
-    // that exist but pay per link for bookkeeping, weight re-reads and the accumulator update.  Measured, it is
-    // the faster one from about 1 link in 20 row-offsets upwards on 128- and 256-channel inputs, from 1 in 4
-    // on 64-channel inputs.
-    const uint64_t lim = 0x7fffffffull;
-    const double min_fill = dense_min_fill(cc);
-    // (A side with position classes skips the offsets its tiles cannot have: its cost follows the links.)
-    if (dense_shape_ok(cc, co, dt) && (side.tile_mask || (double)total_links >= min_fill * (double)side.n_rows * kvol) &&
-        (uint64_t)side.n_src * cc * elt < lim && (uint64_t)side.n_rows * kvol * 4 < lim &&
-        (uint64_t)kvol * cc * co * elt < lim) {
+    const int kind = select_gather(side, kvol, total_links, cc, co, dt);
+    if (kind == 0) {
         Buf wt;
         const void* w = d_w;
         if (w_transposed) {  // stored matrix is [cout = cc][cin = co]; the kernel wants [co][cc]
@@ -704,7 +730,7 @@ int conv_gather(const MapSide& side, int kvol, int64_t total_links, const void* 
         }
         return conv_gather_dense(side, kvol, d_f, w, d_g, cc, co, s);
     }
-    if (mma_shape_ok(cc, co, dt)) {
+    if (kind == 1 || kind == 2) {
         GatherArgs a;
         a.tl_off = ptr<int32_t>(side.tl_off);
         a.tl_src = ptr<int32_t>(side.tl_src);
@@ -799,6 +825,14 @@ int sp_conv_bwd_data(const sp_kmap_t* m, const void* d_dy, const void* d_w, void
                      sp_dtype dt, void* stream) {
     SP_TRY(check_conv_args(m, d_dy, m ? m->n_out : 0, d_w, d_dx, m ? m->n_in : 0, cin, cout, dt));
     return conv_gather(m->in_side, m->kvol, m->total, d_dy, d_w, true, d_dx, cout, cin, dt, (hipStream_t)stream);
+}
+
+const char* sp_conv_kernel_name(const sp_kmap_t* m, int32_t cin, int32_t cout, sp_dtype dt, int32_t direction) {
+    static const char* const names[] = {"gather_dense_kernel", "gather_wave_kernel", "gather_mma_kernel",
+                                        "gather_plain_kernel"};
+    if (!m || cin < 1 || cout < 1 || (dt != SP_F32 && dt != SP_BF16)) return "";
+    return direction == 0 ? names[select_gather(m->out_side, m->kvol, m->total, cin, cout, dt)]
+                          : names[select_gather(m->in_side, m->kvol, m->total, cout, cin, dt)];
 }
 
 int sp_conv_fwd_noalloc(const sp_kmap_t* m, const void* d_x, const void* d_w, void* d_y, int32_t cin, int32_t cout,

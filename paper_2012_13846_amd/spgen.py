@@ -119,10 +119,11 @@ def sphere_cloud(seed: int, n_pts: int, grid: int, batch: int = 0, radius: float
     return quantize(p, -1.0, 2.0 / grid, grid, batch)
 
 
-def primitives_cloud(seed: int, n_pts: int, grid: int, batch: int = 0) -> np.ndarray:
+def primitives_cloud(seed: int, n_pts: int, grid: int, batch: int = 0, scale_lo: float = 0.2,
+                     scale_hi: float = 0.8) -> np.ndarray:
     """n_pts points on the surfaces of 1-4 random primitives in the unit cube, quantised to grid^3.
 
-    Each primitive is a box, sphere or cylinder of scale U[0.2,0.8] (full extent),
+    Each primitive is a box, sphere or cylinder of scale U[scale_lo, scale_hi] (full extent; default U[0.2,0.8]),
     uniformly rotated, centred so that its bounding sphere mostly fits; points are
     allotted area-weighted; points that fall outside [0,1)^3 are dropped.
     """
@@ -131,7 +132,7 @@ def primitives_cloud(seed: int, n_pts: int, grid: int, batch: int = 0) -> np.nda
     prims = []
     for _ in range(n_prim):
         kind = int(rng.integers(0, 3))
-        scale = rng.uniform(0.2, 0.8)
+        scale = rng.uniform(scale_lo, scale_hi)
         rot = _random_rotation(rng)
         if kind == 0:
             half = 0.5 * scale * rng.uniform(0.5, 1.0, 3)
@@ -233,6 +234,42 @@ def coords_config(cfg: int, scale: float = 1.0) -> np.ndarray:
     if cfg == 4:
         return room_cloud(seed_for(4, 0), voxel=0.025, pts_per_cell=5.0 * scale)
     raise ValueError(f"unknown config {cfg}")
+
+
+def coords_literal(which: str) -> np.ndarray:
+    """The literal readings of two BASELINE configs whose text contradicts its own voxel count:
+    "cfg2_2048pt": the config-0 generator with its 2048 points per cloud at a 256^3 grid, 8 clouds (latency datapoint);
+    "cfg4_5cm": the room at 5 cm voxels (about a quarter of the ~1 M voxels the config names)."""
+    if which == "cfg2_2048pt":
+        return batch_of(sphere_cloud, 2, 8, n_pts=2048, grid=256)
+    if which == "cfg4_5cm":
+        return room_cloud(seed_for(4, 0), voxel=0.05, pts_per_cell=5.0)
+    raise ValueError(which)
+
+
+# ----------------------------------------------------------------------------
+# the paper's sparsity sweep (Sec. IV-C, Table II): many small clouds per batch, with point dropout
+# ----------------------------------------------------------------------------
+SWEEP_POINTS = 4096            # points kept per shape before dropout (Sec. IV-A)
+SWEEP_GRIDS = (32, 50)
+SWEEP_P = (1.0, 0.5, 0.25)
+
+
+def sweep_cloud(seed: int, grid: int, p: float, batch: int = 0) -> np.ndarray:
+    """One shape of the sparsity sweep: 4096 surface points of 1-4 primitives that fill most of the unit cube
+    (scale U[0.6,1]: 7.6 % occupied voxels at 32^3, 2.6 % at 50^3, the paper's figures for its shapes), of which
+    a fraction theta ~ U[0, 1-p] is dropped, quantised to grid^3."""
+    raw = primitives_cloud(seed, SWEEP_POINTS, grid, batch, 0.6, 1.0)
+    theta = np.random.default_rng(seed + 77_000_000).uniform(0.0, 1.0 - p) if p < 1.0 else 0.0
+    keep = int(round((1.0 - theta) * len(raw)))     # the points are i.i.d.: dropping a random subset = keeping a prefix
+    return np.ascontiguousarray(raw[:keep])
+
+
+def coords_sweep(grid: int, p: float, n_clouds: int) -> np.ndarray:
+    """Raw coordinates of one batch of the sparsity sweep (workload index 5)."""
+    stream = 10 + SWEEP_GRIDS.index(grid) * len(SWEEP_P) + SWEEP_P.index(p)
+    parts = [sweep_cloud(seed_for(5, c, stream), grid, p, batch=c) for c in range(n_clouds)]
+    return np.ascontiguousarray(np.concatenate(parts, axis=0))
 
 
 # ----------------------------------------------------------------------------
