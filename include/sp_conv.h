@@ -17,8 +17,10 @@
  *     Offsets are multiplied by dilation * (input tensor stride).
  *   - Pointers named d_* are DEVICE pointers, h_* are HOST pointers.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
- *     work of a call is enqueued on it.  Calls that "synchronise" block the host
- *     until that stream has drained.
+ *     work of a call is enqueued on it.  The build calls return without waiting:
+ *     row and pair counts reach the host through pinned memory and the first call
+ *     that needs one on the host (the size queries, the convolutions, transpose)
+ *     waits for it then, and only for that build's last kernel, not for the stream.
  *   - Every function returns SP_OK (0) or a negative sp_status; sp_last_error()
  *     gives a message for the calling thread's last failure.  Argument checks are
  *     done on the host before anything is launched.
@@ -60,15 +62,19 @@ typedef struct sp_kmap sp_kmap_t;     /* kernel map of one (coords, kernel, stri
  * Hashes d_raw [n_raw][4] into an open-addressing table, merges duplicate rows and numbers the
  * distinct rows in first-occurrence order (unique row r = r-th distinct coordinate met walking the
  * rows in order).  tensor_stride (>= 1) is recorded, coordinates are expected on that lattice.
- * Blocks until the count N has come back to the host (everything but the filling of the inverse array, which
- * may still be in flight on `stream` when the call returns, is complete by then).  n_raw may be 0.
- * *out receives a new handle (caller destroys).  d_raw is not referenced after the call returns. */
+ * Returns without waiting for the stream: d_raw must stay valid until the stream has passed the call.  A
+ * coordinate outside the packable range is found on the device and reported (SP_ERR_RANGE) by the first later
+ * call that needs this set's row count on the host (sp_coords_size, or any call on a map built from it).
+ * n_raw may be 0.  *out receives a new handle (caller destroys). */
 int sp_coords_build(const int32_t* d_raw, int64_t n_raw, int32_t tensor_stride, void* stream, sp_coords_t** out);
 
-/* N and the tensor stride (host values, no synchronisation). Either out pointer may be NULL. */
+/* N and the tensor stride.  Asking for N waits (the first time) until the build's numbering kernel has delivered
+ * it, and returns the build's device-detected error if there was one.  Either out pointer may be NULL. */
 int sp_coords_size(const sp_coords_t* c, int64_t* n, int32_t* tensor_stride);
 
-/* d_coords: int32 [N][4]; d_inverse: int32 [n_raw], inverse[j] = distinct row that raw row j merged into. */
+/* d_coords: int32 [N][4]; d_inverse: int32 [n_raw], inverse[j] = distinct row that raw row j merged into.
+ * (The buffers are allocated for the source row count; only the first N rows of d_coords are meaningful.)
+ * No waiting, except that n_raw of a coarser set made by sp_kmap_build waits for its source set's N. */
 int sp_coords_data(const sp_coords_t* c, const int32_t** d_coords, const int32_t** d_inverse, int64_t* n_raw);
 
 /* Drops one reference; the memory is returned to the pool when the last reference goes. */
@@ -81,7 +87,9 @@ int sp_coords_destroy(sp_coords_t* c);
  *   order, and the new tensor stride is S.
  * Step 2: M_k = {(i,o) : c_in[i] = c_out[o] + offset_k * dilation * tensor_stride, same batch index},
  *   found by probing the input set's hash table.
- * Synchronises `stream` (pair counts, and N_out when stride > 1, come back to the host).
+ * Returns without waiting: where `in`'s N has not reached the host yet the kernels read it from device memory
+ * and buffers are sized from `in`'s source row count (if that bound is wasteful - above 1 GiB of tables and
+ * lists - the call waits for N first).
  * *kmap and *out_coords receive new handles (caller destroys both; out_coords may be NULL if unwanted). */
 int sp_kmap_build(const sp_coords_t* in, int32_t kernel_size, int32_t stride, int32_t dilation, void* stream,
                   sp_kmap_t** kmap, sp_coords_t** out_coords);
@@ -92,14 +100,16 @@ int sp_kmap_build(const sp_coords_t* in, int32_t kernel_size, int32_t stride, in
  * coordinate-hierarchy-reusing reading.)  No device work; shares fwd's buffers.  Caller destroys. */
 int sp_kmap_transpose(const sp_kmap_t* fwd, sp_kmap_t** transposed);
 
-/* Host-side facts (no synchronisation). h_counts, if not NULL, receives kvol pair counts |M_k|. */
+/* Host-side facts; everything but kvol waits (the first time) until the build has delivered its counts.
+ * h_counts, if not NULL, receives kvol pair counts |M_k|. */
 int sp_kmap_info(const sp_kmap_t* m, int64_t* n_in, int64_t* n_out, int32_t* kvol, int64_t* total_pairs,
                  int64_t* h_counts);
 
-/* Pair lists of all offsets concatenated in offset order: list k occupies
- * [sum_{j<k} counts[j], +counts[k]) of both arrays; entry p links input row d_pair_in[p] to output row
- * d_pair_out[p].  Order inside one offset's list is deterministic but unspecified. */
-int sp_kmap_pairs(const sp_kmap_t* m, const int32_t** d_pair_in, const int32_t** d_pair_out);
+/* Pair lists, one row of *pair_stride entries per offset: list k is entries [k * pair_stride, k * pair_stride +
+ * counts[k]) of both arrays (the rest of a row is unused); entry p links input row d_pair_in[p] to output row
+ * d_pair_out[p].  (A row has room for the most pairs an offset can have, so that the build can place a
+ * pair before the totals of the other offsets are known.)  Order inside a list: ascending output row. */
+int sp_kmap_pairs(const sp_kmap_t* m, const int32_t** d_pair_in, const int32_t** d_pair_out, int64_t* pair_stride);
 
 /* Neighbour tables, offset-major: d_nbr_out [kvol][n_out] = input row linked to (o,k) or -1;
  * d_nbr_in [kvol][n_in] = output row linked to (i,k) or -1.  A stride-1 map with an odd kernel stores one

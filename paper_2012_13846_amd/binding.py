@@ -48,7 +48,7 @@ def lib() -> C.CDLL:
         l.sp_pool_bwd.argtypes = [_vp, _vp, _vp, _vp, C.c_int32, C.c_int32, C.c_int32, _vp]
         l.sp_kmap_info.argtypes = [_vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int32),
                                    C.POINTER(C.c_int64), _vp]
-        l.sp_kmap_pairs.argtypes = [_vp, C.POINTER(_vp), C.POINTER(_vp)]
+        l.sp_kmap_pairs.argtypes = [_vp, C.POINTER(_vp), C.POINTER(_vp), C.POINTER(C.c_int64)]
         l.sp_kmap_table.argtypes = [_vp, C.POINTER(_vp), C.POINTER(_vp), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         l.sp_kmap_destroy.argtypes = [_vp]
         for name in ("sp_conv_fwd", "sp_conv_bwd_data", "sp_conv_bwd_weight", "sp_conv_fwd_noalloc"):
@@ -81,13 +81,22 @@ def _view(ptr, shape, typestr, dtype) -> torch.Tensor:
 
 
 class Coords:
-    """Owns one reference to an sp_coords_t."""
+    """Owns one reference to an sp_coords_t.  The row count `n` is asked for (and waited for) on first use."""
 
     def __init__(self, handle):
         self._h = handle
-        n, ts = C.c_int64(), C.c_int32()
-        _check(lib().sp_coords_size(self._h, C.byref(n), C.byref(ts)))
-        self.n, self.tensor_stride = n.value, ts.value
+        self._n = None
+        ts = C.c_int32()
+        _check(lib().sp_coords_size(self._h, None, C.byref(ts)))
+        self.tensor_stride = ts.value
+
+    @property
+    def n(self) -> int:
+        if self._n is None:
+            n = C.c_int64()
+            _check(lib().sp_coords_size(self._h, C.byref(n), None))
+            self._n = n.value
+        return self._n
 
     def _data(self):
         pc, pi, nr = _vp(), _vp(), C.c_int64()
@@ -117,22 +126,44 @@ class Coords:
 
 
 class KMap:
-    """Owns an sp_kmap_t."""
+    """Owns an sp_kmap_t.  Sizes and pair counts are asked for (and waited for) on first use."""
 
     def __init__(self, handle):
         self._h = handle
-        ni, no, kv, tot = C.c_int64(), C.c_int64(), C.c_int32(), C.c_int64()
-        _check(lib().sp_kmap_info(self._h, C.byref(ni), C.byref(no), C.byref(kv), C.byref(tot), None))
-        self.n_in, self.n_out, self.kvol, self.total = ni.value, no.value, kv.value, tot.value
-        counts = np.zeros(self.kvol, dtype=np.int64)
-        _check(lib().sp_kmap_info(self._h, None, None, None, None, counts.ctypes.data_as(_vp)))
-        self.counts = counts
+        self._info = None
+        kv = C.c_int32()
+        _check(lib().sp_kmap_info(self._h, None, None, C.byref(kv), None, None))
+        self.kvol = kv.value
+
+    def _sizes(self):
+        if self._info is None:
+            ni, no, tot = C.c_int64(), C.c_int64(), C.c_int64()
+            counts = np.zeros(self.kvol, dtype=np.int64)
+            _check(lib().sp_kmap_info(self._h, C.byref(ni), C.byref(no), None, C.byref(tot), counts.ctypes.data_as(_vp)))
+            self._info = (ni.value, no.value, tot.value, counts)
+        return self._info
+
+    n_in = property(lambda self: self._sizes()[0])
+    n_out = property(lambda self: self._sizes()[1])
+    total = property(lambda self: self._sizes()[2])
+    counts = property(lambda self: self._sizes()[3])
+
+    def pairs_strided(self):
+        """(pair_in, pair_out): int32 [kvol][pair_stride] views; list k is the first counts[k] entries of row k."""
+        a, b, st = _vp(), _vp(), C.c_int64()
+        _check(lib().sp_kmap_pairs(self._h, C.byref(a), C.byref(b), C.byref(st)))
+        shape = (self.kvol, st.value)
+        return _view(a.value, shape, "<i4", torch.int32), _view(b.value, shape, "<i4", torch.int32)
 
     def pairs(self):
-        """(pair_in, pair_out): int32 [total] views, lists of all offsets concatenated in offset order."""
-        a, b = _vp(), _vp()
-        _check(lib().sp_kmap_pairs(self._h, C.byref(a), C.byref(b)))
-        return _view(a.value, (self.total,), "<i4", torch.int32), _view(b.value, (self.total,), "<i4", torch.int32)
+        """(pair_in, pair_out): int32 [total], the lists of all offsets concatenated in offset order (a copy)."""
+        pi, po = self.pairs_strided()
+        counts = self.counts
+        if self.total == 0:
+            e = torch.empty((0,), dtype=torch.int32, device="cuda")
+            return e, e.clone()
+        return (torch.cat([pi[k, :int(c)] for k, c in enumerate(counts)]),
+                torch.cat([po[k, :int(c)] for k, c in enumerate(counts)]))
 
     def table(self):
         """(nbr_out [kvol][n_out], nbr_in [kvol][n_in], out_reversed, in_reversed) views."""

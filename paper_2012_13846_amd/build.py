@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsp_conv.so")
-SOURCES = ["sp_runtime.hip", "sp_scan.hip", "sp_coords.hip", "sp_kmap.hip", "sp_conv.hip", "sp_conv_dense.hip", "sp_wgrad.hip", "sp_glue.hip", "sp_pool.hip", "sp_pack.hip"]
+SOURCES = ["sp_runtime.hip", "sp_coords.hip", "sp_kmap.hip", "sp_conv.hip", "sp_conv_dense.hip", "sp_wgrad.hip", "sp_glue.hip", "sp_pool.hip", "sp_pack.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function", "-Wno-pass-failed",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 code generation
          "-I", INCLUDE, "-I", CSRC]

@@ -800,9 +800,12 @@ int static_scratch(void** out) {
 }
 
 // a: source features (rows_a), b: weights, c: destination (rows_c); a zero-sized buffer may be NULL
-int check_conv_args(const sp_kmap_t* m, const void* a, int64_t rows_a, const void* b, const void* c, int64_t rows_c,
-                    int cin, int cout, sp_dtype dt) {
+// a_is_in: a holds the map's input rows and c its output rows (forward), else the other way round
+int check_conv_args(const sp_kmap_t* m, const void* a, bool a_is_in, const void* b, const void* c, int cin, int cout,
+                    sp_dtype dt) {
     if (!m) return fail(SP_ERR_INVALID_ARG, "kmap handle is NULL");
+    SP_TRY(kmap_resolve(m));  // the sizes of a map whose build has not reported yet
+    const int64_t rows_a = a_is_in ? m->n_in : m->n_out, rows_c = a_is_in ? m->n_out : m->n_in;
     if (cin < 1 || cout < 1 || cin > 4096 || cout > 4096) return fail(SP_ERR_INVALID_ARG, "bad channel count");
     if (dt != SP_F32 && dt != SP_BF16) return fail(SP_ERR_INVALID_ARG, "bad dtype");
     if (!b || (!a && rows_a > 0) || (!c && rows_c > 0))
@@ -817,27 +820,27 @@ extern "C" {
 
 int sp_conv_fwd(const sp_kmap_t* m, const void* d_x, const void* d_w, void* d_y, int32_t cin, int32_t cout,
                 sp_dtype dt, void* stream) {
-    SP_TRY(check_conv_args(m, d_x, m ? m->n_in : 0, d_w, d_y, m ? m->n_out : 0, cin, cout, dt));
+    SP_TRY(check_conv_args(m, d_x, true, d_w, d_y, cin, cout, dt));
     return conv_gather(m->out_side, m->kvol, m->total, d_x, d_w, false, d_y, cin, cout, dt, (hipStream_t)stream);
 }
 
 int sp_conv_bwd_data(const sp_kmap_t* m, const void* d_dy, const void* d_w, void* d_dx, int32_t cin, int32_t cout,
                      sp_dtype dt, void* stream) {
-    SP_TRY(check_conv_args(m, d_dy, m ? m->n_out : 0, d_w, d_dx, m ? m->n_in : 0, cin, cout, dt));
+    SP_TRY(check_conv_args(m, d_dy, false, d_w, d_dx, cin, cout, dt));
     return conv_gather(m->in_side, m->kvol, m->total, d_dy, d_w, true, d_dx, cout, cin, dt, (hipStream_t)stream);
 }
 
 const char* sp_conv_kernel_name(const sp_kmap_t* m, int32_t cin, int32_t cout, sp_dtype dt, int32_t direction) {
     static const char* const names[] = {"gather_dense_kernel", "gather_wave_kernel", "gather_mma_kernel",
                                         "gather_plain_kernel"};
-    if (!m || cin < 1 || cout < 1 || (dt != SP_F32 && dt != SP_BF16)) return "";
+    if (!m || cin < 1 || cout < 1 || (dt != SP_F32 && dt != SP_BF16) || kmap_resolve(m) != SP_OK) return "";
     return direction == 0 ? names[select_gather(m->out_side, m->kvol, m->total, cin, cout, dt)]
                           : names[select_gather(m->in_side, m->kvol, m->total, cout, cin, dt)];
 }
 
 int sp_conv_fwd_noalloc(const sp_kmap_t* m, const void* d_x, const void* d_w, void* d_y, int32_t cin, int32_t cout,
                         sp_dtype dt, void* stream) {
-    SP_TRY(check_conv_args(m, d_x, m ? m->n_in : 0, d_w, d_y, m ? m->n_out : 0, cin, cout, dt));
+    SP_TRY(check_conv_args(m, d_x, true, d_w, d_y, cin, cout, dt));
     void* scratch = nullptr;
     SP_TRY(static_scratch(&scratch));
     return conv_gather(m->out_side, m->kvol, m->total, d_x, d_w, false, d_y, cin, cout, dt, (hipStream_t)stream,

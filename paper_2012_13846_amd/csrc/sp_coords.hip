@@ -1,12 +1,17 @@
 // Coordinate sets: hash insertion, duplicate merging in first-occurrence order, strided (coarser)
 // coordinate generation.  Sec. III-B: sparse tensor definition and step 1.
 //
-// Five launches: fill the table; insert every row (slot.first = smallest row carrying the key); count the
-// first occurrences per 1024-row block; number them (each block adds up the counts of the blocks before
-// it, then ranks its own rows with ballots) and write coordinates + row numbers; read the row numbers
-// back per source row (the inverse map).
+// Four launches, no host round trip: (1) reset the table and the bookkeeping words; (2) insert every row
+// (slot.first = smallest row carrying the key); (3) number the first occurrences in row order in a single pass
+// (every block of 1024 rows counts its first occurrences, gets the count of all earlier blocks by decoupled
+// look-back, ranks its rows with ballots, writes coordinates + row numbers; the last block writes the row count
+// N to device memory for later kernels and to a mail slot for the host); (4) read the row numbers back per
+// source row (the inverse map).  The host learns N when it first asks (coords_resolve).
+#include <algorithm>
+
 #include "sp_hash.h"
 #include "sp_internal.h"
+#include "sp_lookback.h"
 
 namespace sp {
 namespace {
@@ -31,9 +36,16 @@ __device__ __forceinline__ int4 load_row(const int4* __restrict__ src, int64_t i
     return c;
 }
 
-__global__ __launch_bounds__(kThreads) void fill_table_kernel(HashSlot* __restrict__ tab, uint32_t cap,
-                                                              int32_t* __restrict__ small, int n_small) {
-    const uint32_t i = blockIdx.x * kThreads + threadIdx.x;
+// the source row count: a host value, or a count in device memory that the host has not seen yet
+__device__ __forceinline__ int64_t row_count(int64_t n_host, const int32_t* __restrict__ d_n) {
+    return d_n ? (int64_t)*d_n : n_host;
+}
+
+// table slots <- empty; meta words and look-back words <- 0
+__global__ __launch_bounds__(kThreads) void reset_kernel(HashSlot* __restrict__ tab, uint32_t cap,
+                                                         int32_t* __restrict__ meta, unsigned long long* __restrict__ desc,
+                                                         int64_t n_desc) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (i < cap) {
         uint4 v;
         v.x = 0xffffffffu;
@@ -42,13 +54,16 @@ __global__ __launch_bounds__(kThreads) void fill_table_kernel(HashSlot* __restri
         v.w = (uint32_t)-1;
         *reinterpret_cast<uint4*>(&tab[i]) = v;
     }
-    if (i < (uint32_t)n_small) small[i] = 0;
+    if (i < kMetaWords) meta[i] = 0;
+    if (i < n_desc) desc[i] = 0ull;
 }
 
 // Every source row inserts its key; slot.first becomes the smallest source row carrying that key.
-__global__ __launch_bounds__(kThreads) void insert_kernel(const int4* __restrict__ src, int64_t n, int32_t floor_step,
+__global__ __launch_bounds__(kThreads) void insert_kernel(const int4* __restrict__ src, int64_t n_host,
+                                                          const int32_t* __restrict__ d_n, int32_t floor_step,
                                                           HashSlot* __restrict__ tab, uint32_t cap, int zshift,
                                                           int32_t* __restrict__ slot_of, int32_t* __restrict__ err, int always) {
+    const int64_t n = row_count(n_host, d_n);
     const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (i >= n) return;
     const int4 c = load_row(src, i, floor_step);
@@ -72,70 +87,58 @@ __global__ __launch_bounds__(kThreads) void insert_kernel(const int4* __restrict
     slot_of[i] = (int32_t)slot;
 }
 
-__device__ __forceinline__ bool is_first(const HashSlot* __restrict__ tab, const int32_t* __restrict__ slot_of,
-                                         int64_t i, int64_t n) {
-    if (i >= n) return false;
-    const int32_t s = slot_of[i];
-    return s >= 0 && tab[s].first == (int32_t)i;
-}
-
-// Block b counts the first occurrences among rows [b*1024, b*1024+1024) and keeps them as one bit per row
-// (first_mask[row / 64]), so that the numbering pass does not have to look every row up in the table again.
-__global__ __launch_bounds__(kThreads) void count_first_kernel(const HashSlot* __restrict__ tab,
-                                                               const int32_t* __restrict__ slot_of, int64_t n,
-                                                               int32_t* __restrict__ block_counts,
-                                                               unsigned long long* __restrict__ first_mask) {
-    __shared__ int s_cnt[kThreads / 64];
-    const int64_t base = (int64_t)blockIdx.x * kBlockRows;
-    int c = 0;
-#pragma unroll
-    for (int j = 0; j < kRowsPerThread; ++j) {
-        const unsigned long long m = __ballot(is_first(tab, slot_of, base + j * kThreads + threadIdx.x, n));
-        if ((threadIdx.x & 63) == 0) first_mask[(base + j * kThreads + threadIdx.x) >> 6] = m;
-        c += __popcll(m);
-    }
-    if ((threadIdx.x & 63) == 0) s_cnt[threadIdx.x >> 6] = c;
-    __syncthreads();
-    if (threadIdx.x == 0) block_counts[blockIdx.x] = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
-}
-
-// Block b numbers its first occurrences: rank = (firsts in earlier blocks) + (firsts before it in this
-// block, row order).  Writes the (floored) coordinates at that rank and the rank into the table slot.
-// block_base: if `scanned`, block_counts already holds exclusive prefixes.
-__global__ __launch_bounds__(kThreads) void emit_first_kernel(const int4* __restrict__ src, int64_t n,
-                                                              int32_t floor_step, HashSlot* __restrict__ tab,
-                                                              const int32_t* __restrict__ slot_of,
-                                                              const int32_t* __restrict__ block_counts, int scanned,
-                                                              const unsigned long long* __restrict__ first_mask,
-                                                              int4* __restrict__ coords, int32_t* __restrict__ total) {
-    __shared__ int s_red[kThreads / 64];
+// Block t numbers the first occurrences among rows [t*1024, t*1024+1024): rank = (first
+// occurrences in earlier blocks, by look-back) + (those before it in this block, row order).  Writes the
+// (floored) coordinates at that rank and the rank into the table slot.  The block holding the last rows
+// delivers the total.
+__global__ __launch_bounds__(kThreads) void number_kernel(const int4* __restrict__ src, int64_t n_host,
+                                                          const int32_t* __restrict__ d_n, int32_t floor_step,
+                                                          HashSlot* __restrict__ tab, const int32_t* __restrict__ slot_of,
+                                                          Chain chain, int32_t* __restrict__ meta, int4* __restrict__ coords,
+                                                          uint32_t* __restrict__ mail, uint32_t mail_seq) {
+    __shared__ int s_own[1], s_excl[1], s_state[2];
     __shared__ int s_row[kRowsPerThread][kThreads / 64];
+    const int64_t n = row_count(n_host, d_n);
+    const int64_t nb = (n + kBlockRows - 1) / kBlockRows;
+    const int t = blockIdx.x;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    // firsts in the blocks before this one
-    int before = 0;
-    if (scanned) {
-        before = block_counts[blockIdx.x];
-    } else {
-        int s = 0;
-        for (int b = threadIdx.x; b < (int)blockIdx.x; b += kThreads) s += block_counts[b];
-#pragma unroll
-        for (int d = 32; d > 0; d >>= 1) s += __shfl_down(s, d, 64);
-        if (lane == 0) s_red[w] = s;
-        __syncthreads();
-        before = s_red[0] + s_red[1] + s_red[2] + s_red[3];
+    if (t >= nb) {
+        if (t == 0 && threadIdx.x == 0) {  // no rows at all: block 0 reports N = 0
+            meta[kMetaN] = 0;
+            if (mail) {
+                mail[0] = 0u;
+                mail[1] = (uint32_t)meta[kMetaErr];
+                __threadfence_system();
+                __hip_atomic_store(mail + kMailSeqWord, mail_seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+            }
+        }
+        return;
     }
-    const int64_t base = (int64_t)blockIdx.x * kBlockRows;
+    const int64_t base = (int64_t)t * kBlockRows;
     bool f[kRowsPerThread];
     int pos[kRowsPerThread];
 #pragma unroll
     for (int j = 0; j < kRowsPerThread; ++j) {
-        const unsigned long long m = first_mask[(base + j * kThreads + threadIdx.x) >> 6];
-        f[j] = (m >> lane) & 1ull;
+        const int64_t i = base + j * kThreads + threadIdx.x;
+        bool first = false;
+        if (i < n) {
+            const int32_t s = slot_of[i];
+            first = s >= 0 && tab[s].first == (int32_t)i;
+        }
+        const unsigned long long m = __ballot(first);
+        f[j] = first;
         pos[j] = __popcll(m & ((1ull << lane) - 1ull));
         if (lane == 0) s_row[j][w] = __popcll(m);
     }
     __syncthreads();
-    int run = before;
+    if (threadIdx.x == 0) {
+        int c = 0;
+        for (int j = 0; j < kRowsPerThread; ++j)
+            for (int ww = 0; ww < kThreads / 64; ++ww) c += s_row[j][ww];
+        s_own[0] = c;
+    }
+    chain_lookback(chain, t, s_own, s_excl, s_state, meta + kMetaErr);
+    int run = s_excl[0];
 #pragma unroll
     for (int j = 0; j < kRowsPerThread; ++j) {
         int mine = run;
@@ -150,12 +153,21 @@ __global__ __launch_bounds__(kThreads) void emit_first_kernel(const int4* __rest
             tab[slot_of[i]].row = r;
         }
     }
-    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) *total = run;
+    if (t == nb - 1 && threadIdx.x == 0) {
+        meta[kMetaN] = run;
+        if (mail) {
+            mail[0] = (uint32_t)run;
+            mail[1] = (uint32_t)__hip_atomic_load(meta + kMetaErr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __threadfence_system();
+            __hip_atomic_store(mail + kMailSeqWord, mail_seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+    }
 }
 
 __global__ __launch_bounds__(kThreads) void inverse_kernel(const HashSlot* __restrict__ tab,
-                                                           const int32_t* __restrict__ slot_of, int64_t n,
-                                                           int32_t* __restrict__ inverse) {
+                                                           const int32_t* __restrict__ slot_of, int64_t n_host,
+                                                           const int32_t* __restrict__ d_n, int32_t* __restrict__ inverse) {
+    const int64_t n = row_count(n_host, d_n);
     const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (i >= n) return;
     const int32_t s = slot_of[i];
@@ -166,65 +178,84 @@ inline unsigned blocks_for(int64_t n, int per) { return (unsigned)((n + per - 1)
 
 }  // namespace
 
-int coords_build_impl(const int32_t* d_src, int64_t n_src, int32_t floor_step, int32_t tensor_stride, hipStream_t s,
-                      sp_coords_t** out) {
+int coords_build_impl(const int32_t* d_src, int64_t n_src, const int32_t* d_n_src, int32_t floor_step,
+                      int32_t tensor_stride, hipStream_t s, sp_coords_t** out) {
     if (n_src >= (int64_t)1 << 30) return fail(SP_ERR_INVALID_ARG, "too many rows (%lld)", (long long)n_src);
     std::unique_ptr<sp_coords> c(new sp_coords);
     c->n_raw = n_src;
     c->ts = tensor_stride;
+    c->stream = s;
     uint32_t cap = 1024;
     while ((int64_t)cap < 2 * n_src) cap <<= 1;
     c->tab.cap = cap;
     for (int t = tensor_stride; t > 1; t >>= 1) ++c->tab.zshift;
+    const int64_t nb = (n_src + kBlockRows - 1) / kBlockRows;
     c->tab.slots = dev_alloc((size_t)cap * sizeof(HashSlot), s);
     c->coords = dev_alloc((size_t)(n_src ? n_src : 1) * 16, s);
     c->inverse = dev_alloc((size_t)(n_src ? n_src : 1) * 4, s);
+    c->meta = dev_alloc(kMetaWords * 4, s);
     Buf slot_of = dev_alloc((size_t)(n_src ? n_src : 1) * 4, s);
-    const int64_t nb = (n_src + kBlockRows - 1) / kBlockRows;
-    Buf block_counts = dev_alloc((size_t)(nb ? nb : 1) * 4, s);
-    Buf first_mask = dev_alloc((size_t)(nb ? nb : 1) * (kBlockRows / 64) * 8, s);
-    Buf small = dev_alloc(8, s);  // [0] total, [1] error bits
-    if (!c->tab.slots || !c->coords || !c->inverse || !slot_of || !block_counts || !first_mask || !small) return SP_ERR_ALLOC;
+    Buf chain_mem = dev_alloc((size_t)(nb ? nb : 1) * 8, s);  // one look-back word per numbering block
+    if (!c->tab.slots || !c->coords || !c->inverse || !c->meta || !slot_of || !chain_mem) return SP_ERR_ALLOC;
     HashSlot* tab = ptr<HashSlot>(c->tab.slots);
-    int32_t* d_small = ptr<int32_t>(small);
+    int32_t* meta = ptr<int32_t>(c->meta);
+    Chain chain;
+    chain.desc = ptr<unsigned long long>(chain_mem);
+    chain.n_tiles = nb ? nb : 1;
+    chain.width = 1;
+    const bool mailed = mail_acquire(&c->mail);
 
-    hipLaunchKernelGGL(fill_table_kernel, dim3(blocks_for(cap, kThreads)), dim3(kThreads), 0, s, tab, cap, d_small, 2);
-    int32_t host_small[2] = {0, 0};
-    if (n_src > 0) {
-        const int4* src = reinterpret_cast<const int4*>(d_src);
-        hipLaunchKernelGGL(insert_kernel, dim3(blocks_for(n_src, kThreads)), dim3(kThreads), 0, s, src, n_src,
-                           floor_step, tab, cap, c->tab.zshift, ptr<int32_t>(slot_of), d_small + 1, n_src < (1 << 20) ? 1 : 0);
-        hipLaunchKernelGGL(count_first_kernel, dim3((unsigned)nb), dim3(kThreads), 0, s, tab, ptr<int32_t>(slot_of),
-                           n_src, ptr<int32_t>(block_counts), ptr<unsigned long long>(first_mask));
-        int scanned = 0;
-        if (nb > 4096) {  // too many blocks for every block to add up its predecessors: scan the counts first
-            ScanJob job;
-            job.data = ptr<int32_t>(block_counts);
-            job.n = nb;
-            SP_TRY(exclusive_scan_jobs(&job, 1, s));
-            scanned = 1;
-        }
-        hipLaunchKernelGGL(emit_first_kernel, dim3((unsigned)nb), dim3(kThreads), 0, s, src, n_src, floor_step, tab,
-                           ptr<int32_t>(slot_of), ptr<int32_t>(block_counts), scanned,
-                           ptr<unsigned long long>(first_mask), ptr<int4>(c->coords), d_small);
-        SP_HIP(hipGetLastError());
-    }
-    // the host only waits for N; the inverse array is filled behind the read-back, while the host wakes up
-    SP_TRY(read_back(host_small, d_small, 8, s, [&]() {
-        if (n_src > 0)
-            hipLaunchKernelGGL(inverse_kernel, dim3(blocks_for(n_src, kThreads)), dim3(kThreads), 0, s, tab,
-                               ptr<int32_t>(slot_of), n_src, ptr<int32_t>(c->inverse));
-    }));
+    hipLaunchKernelGGL(reset_kernel, dim3(blocks_for(std::max<int64_t>(cap, nb), kThreads)), dim3(kThreads), 0, s, tab, cap, meta,
+                       chain.desc, nb);
+    const int4* src = reinterpret_cast<const int4*>(d_src);
+    if (n_src > 0)
+        hipLaunchKernelGGL(insert_kernel, dim3(blocks_for(n_src, kThreads)), dim3(kThreads), 0, s, src, n_src, d_n_src,
+                           floor_step, tab, cap, c->tab.zshift, ptr<int32_t>(slot_of), meta + kMetaErr,
+                           n_src < (1 << 20) ? 1 : 0);
+    hipLaunchKernelGGL(number_kernel, dim3((unsigned)(nb ? nb : 1)), dim3(kThreads), 0, s, src, n_src, d_n_src, floor_step, tab,
+                       ptr<int32_t>(slot_of), chain, meta, ptr<int4>(c->coords), mailed ? c->mail.d : (uint32_t*)nullptr,
+                       c->mail.seq);
+    if (n_src > 0)
+        hipLaunchKernelGGL(inverse_kernel, dim3(blocks_for(n_src, kThreads)), dim3(kThreads), 0, s, tab, ptr<int32_t>(slot_of),
+                           n_src, d_n_src, ptr<int32_t>(c->inverse));
     SP_HIP(hipGetLastError());
-    if (host_small[1] & 1)
-        return fail(SP_ERR_RANGE, "a coordinate is outside 0 <= b < 65536, -32768 <= x,y,z < 32768");
-    if (host_small[1] & 2) return fail(SP_ERR_TABLE_FULL, "hash table overflow");
-    c->n = host_small[0];
+    if (!mailed) {  // no mail slot free: wait here, the old way
+        int32_t h[2] = {0, 0};
+        SP_TRY(read_back(h, meta, 8, s));
+        c->n = h[0];
+        c->status = (h[1] & 1) ? SP_ERR_RANGE : (h[1] & 2) ? SP_ERR_TABLE_FULL : (h[1] & kErrLookback) ? SP_ERR_HIP : SP_OK;
+        c->resolved = true;
+    }
     *out = c.release();
     return SP_OK;
 }
 
+static int status_message(int status) {
+    if (status == SP_ERR_RANGE) return fail(SP_ERR_RANGE, "a coordinate is outside 0 <= b < 65536, -32768 <= x,y,z < 32768");
+    if (status == SP_ERR_TABLE_FULL) return fail(SP_ERR_TABLE_FULL, "hash table overflow");
+    if (status == SP_ERR_HIP) return fail(SP_ERR_HIP, "internal: a look-back wait gave up");
+    return status;
+}
+
+int coords_resolve(const sp_coords_t* c) {
+    std::lock_guard<std::mutex> lk(c->mu);
+    if (!c->resolved) {
+        SP_TRY(mail_wait(c->mail, c->stream));
+        const uint32_t n = c->mail.h[0], e = c->mail.h[1];
+        c->n = (int64_t)n;
+        c->status = (e & 1) ? SP_ERR_RANGE : (e & 2) ? SP_ERR_TABLE_FULL : (e & kErrLookback) ? SP_ERR_HIP : SP_OK;
+        c->resolved = true;
+        mail_release(&c->mail);
+    }
+    return status_message(c->status);
+}
+
 }  // namespace sp
+
+sp_coords::~sp_coords() {
+    sp::mail_release(&mail);
+    if (src_of) sp_coords_destroy(src_of);
+}
 
 extern "C" {
 
@@ -235,13 +266,16 @@ int sp_coords_build(const int32_t* d_raw, int64_t n_raw, int32_t tensor_stride, 
     if (n_raw > 0 && !d_raw) return sp::fail(SP_ERR_INVALID_ARG, "d_raw is NULL");
     if (tensor_stride < 1) return sp::fail(SP_ERR_INVALID_ARG, "tensor_stride < 1");
     if (((uintptr_t)d_raw & 15) != 0) return sp::fail(SP_ERR_INVALID_ARG, "d_raw must be 16-byte aligned");
-    return sp::coords_build_impl(d_raw, n_raw, 1, tensor_stride, (hipStream_t)stream, out);
+    return sp::coords_build_impl(d_raw, n_raw, nullptr, 1, tensor_stride, (hipStream_t)stream, out);
 }
 
 int sp_coords_size(const sp_coords_t* c, int64_t* n, int32_t* tensor_stride) {
     if (!c) return sp::fail(SP_ERR_INVALID_ARG, "coords handle is NULL");
-    if (n) *n = c->n;
     if (tensor_stride) *tensor_stride = c->ts;
+    if (n) {
+        SP_TRY(sp::coords_resolve(c));
+        *n = c->n;
+    }
     return SP_OK;
 }
 
@@ -249,7 +283,13 @@ int sp_coords_data(const sp_coords_t* c, const int32_t** d_coords, const int32_t
     if (!c) return sp::fail(SP_ERR_INVALID_ARG, "coords handle is NULL");
     if (d_coords) *d_coords = sp::ptr<int32_t>(c->coords);
     if (d_inverse) *d_inverse = sp::ptr<int32_t>(c->inverse);
-    if (n_raw) *n_raw = c->n_raw;
+    if (n_raw) {
+        *n_raw = c->n_raw;
+        if (c->src_of) {  // derived from a set whose row count may have been unknown then: its rows are the source rows
+            SP_TRY(sp::coords_resolve(c->src_of));
+            *n_raw = c->src_of->n;
+        }
+    }
     return SP_OK;
 }
 

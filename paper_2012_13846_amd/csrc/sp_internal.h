@@ -61,6 +61,20 @@ int64_t pool_cross_stream();
 int read_back(void* h_dst, const void* d_src, size_t bytes, hipStream_t s,
               const std::function<void()>& then_enqueue = nullptr);
 
+// ---- mail slots (sp_runtime.hip): counts that a build's last kernel writes into pinned host memory ----------------
+constexpr int kMailSlots = 2048;      // builds whose counts nobody has asked for yet
+constexpr int kMailSlotWords = 256;   // 1 KB a slot: payload words, then the sequence word
+constexpr int kMailSeqWord = kMailSlotWords - 1;
+struct MailSlot {
+    int index = -1;         // -1: none held
+    uint32_t* h = nullptr;  // host view
+    uint32_t* d = nullptr;  // device view of the same memory
+    uint32_t seq = 0;       // the value the kernel writes to word kMailSeqWord when the payload is complete
+};
+bool mail_acquire(MailSlot* out);                  // false: none free (the caller then waits for its stream instead)
+void mail_release(MailSlot* slot);
+int mail_wait(const MailSlot& slot, hipStream_t s);  // blocks until the slot's payload has arrived
+
 // ---- hash table ---------------------------------------------------------------------------------------------
 struct HashTab {
     Buf slots;         // HashSlot [cap] (sp_hash.h): 16 bytes {key, first source row, row number}
@@ -68,23 +82,15 @@ struct HashTab {
     int zshift = 0;    // floor(log2(tensor stride)): see sp_hash.h
 };
 
-// ---- device-wide exclusive scans of int32 (sp_scan.hip) --------------------------------------------------------
-// In place: data[i] = sum_{j<i} data[j].  *total (device, may be null) = sum of all.  With koff set,
-// koff[i] = the exclusive prefix at element i*koff_stride for i < koff_n, and koff[koff_n] = the total.
-struct ScanJob {
-    int32_t* data = nullptr;
-    int64_t n = 0;
-    int32_t* total = nullptr;
-    int32_t* koff = nullptr;
-    int64_t koff_stride = 1;
-    int32_t koff_n = 0;
-};
-int exclusive_scan_jobs(const ScanJob* jobs, int njobs /* 1 or 2 */, hipStream_t s);
-
 // ---- coords (sp_coords.hip) ---------------------------------------------------------------------------------------
-// Builds a coordinate set from d_src rows; floor_step > 1 floors x,y,z to multiples of it first.
-int coords_build_impl(const int32_t* d_src, int64_t n_src, int32_t floor_step, int32_t tensor_stride, hipStream_t s,
-                      sp_coords_t** out);
+// Builds a coordinate set from d_src rows; floor_step > 1 floors x,y,z to multiples of it first.  n_src_ub is an
+// upper bound of the row count (sizes every allocation and grid); d_n_src, if not null, points at the true count
+// in device memory (a count that the host has not seen yet), else the count is n_src_ub.  Does not wait.
+int coords_build_impl(const int32_t* d_src, int64_t n_src_ub, const int32_t* d_n_src, int32_t floor_step,
+                      int32_t tensor_stride, hipStream_t s, sp_coords_t** out);
+// Waits (first call only) until the handle's row count has come back; reports device-detected errors.
+int coords_resolve(const sp_coords_t* c);
+int kmap_resolve(const sp_kmap_t* m);
 
 constexpr int kTileRows = 256;   // rows per tile of the tile lists (= map-build block size)
 constexpr int kSubTiles = 4;     // 64-row sub-tiles (one wavefront ballot each) per tile
@@ -92,13 +98,26 @@ constexpr int kHalves = 2;       // list offsets are kept per 32-row half of a s
 
 }  // namespace sp
 
+// Words of a coordinate set's device-side `meta` block (int32)
+enum { kMetaN = 0, kMetaErr = 1, kMetaWords = 4 };
+
 struct sp_coords {
     std::atomic<int> ref{1};
-    int64_t n = 0, n_raw = 0;
+    int64_t n_raw = 0;   // source rows (an upper bound of them when the set was derived from an unresolved one)
     int32_t ts = 1;
-    sp::Buf coords;   // int32 [n][4]
+    sp::Buf coords;   // int32 [n][4] (allocated for n_raw rows)
     sp::Buf inverse;  // int32 [n_raw]
+    sp::Buf meta;     // int32 [kMetaWords]: the row count n, error bits, ...: what kernels of later builds read
     sp::HashTab tab;
+    hipStream_t stream = nullptr;
+    // the host's copy of n arrives through a mail slot and is read on first demand (coords_resolve)
+    mutable std::mutex mu;
+    mutable bool resolved = false;
+    mutable int status = 0;       // SP_OK or the device-detected error, once resolved
+    mutable int64_t n = -1;
+    mutable sp::MailSlot mail;
+    sp_coords* src_of = nullptr;  // set on a coarser set derived from another: the set whose rows were its source rows (reference held)
+    ~sp_coords();
 };
 
 namespace sp {
@@ -124,16 +143,26 @@ struct MapSide {
 }  // namespace sp
 
 struct sp_kmap {
-    int64_t n_in = 0, n_out = 0, total = 0;
+    // Host copies of the sizes: valid once resolved (kmap_resolve); the kernels of the build read them from
+    // device memory instead.
+    mutable int64_t n_in = 0, n_out = 0, total = 0;
     int32_t K = 0, kvol = 0, stride = 1, dilation = 1;
-    sp::MapSide out_side;  // destinations = output rows, sources = input rows   (forward)
-    sp::MapSide in_side;   // destinations = input rows,  sources = output rows  (data gradient)
-    sp::Buf pair_in, pair_out;  // int32 [total], offset-major
-    std::vector<int64_t> counts;   // [kvol]
-    std::vector<int64_t> koff;     // [kvol+1] exclusive prefix of counts
+    mutable sp::MapSide out_side;  // destinations = output rows, sources = input rows   (forward)
+    mutable sp::MapSide in_side;   // destinations = input rows,  sources = output rows  (data gradient)
+    sp::Buf pair_in, pair_out;  // int32 [kvol][pair_stride]: offset k's pairs are the first counts[k] entries of row k
+    int64_t pair_stride = 0;
+    mutable std::vector<int64_t> counts;   // [kvol]
+    mutable std::vector<int64_t> koff;     // [kvol+1] exclusive prefix of counts
     sp::Buf d_koff;                // int32 [kvol+1], the same prefix on the device
     sp_coords* c_in = nullptr;     // references held
     sp_coords* c_out = nullptr;
+    hipStream_t stream = nullptr;
+    mutable std::mutex mu;
+    mutable bool resolved = false;
+    mutable int status = 0;
+    mutable sp::MailSlot mail;     // payload: n_in, n_out, error bits, koff[0..kvol]
+    void set_sizes(int64_t n_in_, int64_t n_out_, const uint32_t* koff_words) const;
+    ~sp_kmap() { sp::mail_release(&mail); }
     // filled on first use (average pooling's backward pass): links per output row, int32 [n_out]
     mutable std::mutex cache_mu;
     mutable sp::Buf out_link_cnt;

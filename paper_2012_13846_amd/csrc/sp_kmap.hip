@@ -1,6 +1,16 @@
 // Kernel maps (Sec. III-B step 2): for every kernel offset the (input row, output row) pairs it links,
 // found by probing the input coordinate set's hash table, then compacted with wavefront ballots and
-// prefix sums into (a) offset-major pair lists and (b) tile-major lists for the gather-GEMM kernels.
+// prefix sums into (a) per-offset pair lists and (b) tile-major lists for the gather-GEMM kernels.
+//
+// No host round trip and no scan launches: the build is (1) one reset launch, (2) the searches, which fill the
+// neighbour table(s), (3) per map side a count launch (links per 256-row tile and offset), a small prefix launch
+// (one workgroup per offset scans its counts over the tiles) and an emit launch (every tile writes its stretch
+// of the lists); the last tile delivers the per-offset totals
+// to device memory and to a mail slot, which the host reads when it first asks (kmap_resolve).  Row counts that
+// the host has not seen yet (the input set's N, the coarse set's N) are read from device memory by the kernels;
+// grids and allocations use upper bounds.  (A single-pass count + look-back + emit kernel was measured slower:
+// the look-back's device-coherent loads cost ~2 us a round trip and a tile near the end of a launch that starts
+// all at once needs several of them per offset.)
 #include <algorithm>
 
 #include "sp_hash.h"
@@ -10,168 +20,112 @@ namespace sp {
 namespace {
 
 constexpr int kThreads = kTileRows;  // one thread per row of a tile; 4 wavefronts = 4 sub-tiles
+constexpr int kMaxKvol = 125;
 
-__global__ __launch_bounds__(256) void fill_i32_kernel(int32_t* __restrict__ p, int64_t n, int32_t v) {
-    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < n) p[i] = v;
+// A row count: the host's value, or (d != null) a count in device memory that the host has not seen yet.
+struct Count {
+    const int32_t* d;
+    int64_t h;
+};
+__device__ __forceinline__ int64_t get(const Count& c) { return c.d ? (int64_t)*c.d : c.h; }
+
+// table[k][r] <- -1 for k in [k_lo, kvol), r < n (n may live on the device); a second such region
+struct NegRegion {
+    int32_t* table;
+    Count n;
+    int k_lo, kvol;
+};
+__global__ __launch_bounds__(256) void reset_kernel(NegRegion a, NegRegion b) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (a.table) {
+        const int64_t n = get(a.n);
+        if (i < n * (a.kvol - a.k_lo)) a.table[(int64_t)a.k_lo * n + i] = -1;
+    }
+    if (b.table) {
+        const int64_t n = get(b.n);
+        if (i < n * (b.kvol - b.k_lo)) b.table[(int64_t)b.k_lo * n + i] = -1;
+    }
 }
 
 // grid (tiles of n_out, K*K).  Thread (o, ax, ay) probes the K offsets (ax, ay, 0..K-1): the K searches of
 // one thread are independent, so their memory latencies overlap, and the row's coordinates are read once.
-// Writes nbr_out[k][o]; scatters nbr_in[k][i] = o when nbr_in is given; counts live links per 64-row
-// half sub-tile (sub_counts[((tile*4 + wave)*kvol + k)*2 + half]) and per tile (blk_counts[k*ntiles + tile]).
+// Writes nbr_out[k][o]; scatters nbr_in[k][i] = o when nbr_in is given.
 // identity_k >= 0 (stride 1, odd K; input and output rows are the same set): the centre offset is the
 // identity, and link (i, o) at offset k is link (o, i) at offset kvol-1-k, so only the offsets below the
 // centre are searched and each hit is also written to the mirrored entry nbr_out[kvol-1-k][i] = o.  The
-// entries above the centre that stay without a hit were set to -1 beforehand, and the counts come from a
-// separate pass over the table (count_kernel): sub_counts is null here.
+// entries above the centre that stay without a hit were set to -1 beforehand.
 template <int K>
-__global__ __launch_bounds__(kThreads) void probe_kernel(const int4* __restrict__ c_out, int64_t n_out,
+__global__ __launch_bounds__(kThreads) void probe_kernel(const int4* __restrict__ c_out, Count cn_out,
                                                          const HashSlot* __restrict__ tab, uint32_t cap, int zshift, int step,
                                                          int identity_k, int32_t* __restrict__ nbr_out,
-                                                         int32_t* __restrict__ nbr_in, int64_t n_in,
-                                                         int32_t* __restrict__ sub_counts,
-                                                         int32_t* __restrict__ blk_counts) {
-    __shared__ int s_cnt[K][kSubTiles];
+                                                         int32_t* __restrict__ nbr_in, Count cn_in) {
     constexpr int kvol = K * K * K;
+    const int64_t n_out = get(cn_out);
     const int ay = blockIdx.y % K, ax = blockIdx.y / K;
     const int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (o >= n_out) return;
+    const int64_t n_in = nbr_in ? get(cn_in) : 0;
     constexpr int centre = (K & 1) ? (K - 1) / 2 : 0;
     const int k0 = (ax * K + ay) * K;
     int32_t v[K];
 #pragma unroll
     for (int az = 0; az < K; ++az) v[az] = -1;
-    if (o < n_out) {
-        const int4 c = c_out[o];
-        uint64_t key[K];
-        bool ok[K];
+    const int4 c = c_out[o];
+    uint64_t key[K];
+    bool ok[K];
+#pragma unroll
+    for (int az = 0; az < K; ++az)
+        ok[az] = pack_key(c.x, c.y + (ax - centre) * step, c.z + (ay - centre) * step, c.w + (az - centre) * step, &key[az]);
+    // The K searches advance in lockstep: every turn issues the next slot's load of all searches still
+    // running and only then looks at the answers, so their memory latencies overlap (run one after the
+    // other, each search costs as many round trips as the longest probe sequence among the 64 lanes).
+    uint32_t slot[K];
+    bool run[K];
+    bool any = false;
+#pragma unroll
+    for (int az = 0; az < K; ++az) {
+        run[az] = false;
+        slot[az] = 0;
+        if (k0 + az == identity_k) {
+            v[az] = (int32_t)o;
+        } else if (ok[az] && (identity_k < 0 || k0 + az < identity_k)) {
+            uint32_t bucket, pos;
+            hash_home(key[az], cap, zshift, &bucket, &pos);
+            slot[az] = bucket * 4 + pos;
+            run[az] = true;
+            any = true;
+        }
+    }
+    for (uint32_t turn = 0; any && turn < cap; ++turn) {
+        uint4 raw[K];
 #pragma unroll
         for (int az = 0; az < K; ++az)
-            ok[az] = pack_key(c.x, c.y + (ax - centre) * step, c.z + (ay - centre) * step, c.w + (az - centre) * step,
-                              &key[az]);
-        // The K searches advance in lockstep: every turn issues the next slot's load of all searches still
-        // running and only then looks at the answers, so their memory latencies overlap (run one after the
-        // other, each search costs as many round trips as the longest probe sequence among the 64 lanes).
-        uint32_t slot[K];
-        bool run[K];
-        bool any = false;
+            if (run[az]) raw[az] = *reinterpret_cast<const uint4*>(&tab[slot[az]]);
+        any = false;
 #pragma unroll
         for (int az = 0; az < K; ++az) {
-            run[az] = false;
-            slot[az] = 0;
-            if (k0 + az == identity_k) {
-                v[az] = (int32_t)o;
-            } else if (ok[az] && (identity_k < 0 || k0 + az < identity_k)) {
-                uint32_t bucket, pos;
-                hash_home(key[az], cap, zshift, &bucket, &pos);
-                slot[az] = bucket * 4 + pos;
-                run[az] = true;
+            if (!run[az]) continue;
+            const unsigned long long cur = ((unsigned long long)raw[az].y << 32) | raw[az].x;
+            if (cur == key[az]) {
+                v[az] = (int32_t)raw[az].w;
+                run[az] = false;
+            } else if (cur == kEmptyKey) {
+                run[az] = false;
+            } else {
+                slot[az] = (slot[az] + 1) & (cap - 1);
                 any = true;
             }
         }
-        for (uint32_t turn = 0; any && turn < cap; ++turn) {
-            uint4 raw[K];
-#pragma unroll
-            for (int az = 0; az < K; ++az)
-                if (run[az]) raw[az] = *reinterpret_cast<const uint4*>(&tab[slot[az]]);
-            any = false;
-#pragma unroll
-            for (int az = 0; az < K; ++az) {
-                if (!run[az]) continue;
-                const unsigned long long cur = ((unsigned long long)raw[az].y << 32) | raw[az].x;
-                if (cur == key[az]) {
-                    v[az] = (int32_t)raw[az].w;
-                    run[az] = false;
-                } else if (cur == kEmptyKey) {
-                    run[az] = false;
-                } else {
-                    slot[az] = (slot[az] + 1) & (cap - 1);
-                    any = true;
-                }
-            }
-        }
-#pragma unroll
-        for (int az = 0; az < K; ++az) {
-            if (identity_k >= 0 && k0 + az > identity_k) continue;  // written by the mirrored offset's hits
-            nbr_out[(int64_t)(k0 + az) * n_out + o] = v[az];
-            if (nbr_in && v[az] >= 0) nbr_in[(int64_t)(k0 + az) * n_in + v[az]] = (int32_t)o;
-            if (identity_k >= 0 && k0 + az < identity_k && v[az] >= 0)
-                nbr_out[(int64_t)(kvol - 1 - (k0 + az)) * n_out + v[az]] = (int32_t)o;
-        }
     }
-    if (!sub_counts) return;  // uniform: the counts of a mirrored table are taken by count_kernel
-    const int w = threadIdx.x >> 6;
 #pragma unroll
     for (int az = 0; az < K; ++az) {
-        const unsigned long long live = __ballot(v[az] >= 0);
-        if ((threadIdx.x & 63) == 0) {
-            const int lo = __popc((unsigned)live), hi = __popc((unsigned)(live >> 32));
-            s_cnt[az][w] = lo + hi;
-            int32_t* dst = sub_counts + (((int64_t)blockIdx.x * kSubTiles + w) * kvol + k0 + az) * kHalves;
-            dst[0] = lo;
-            dst[1] = hi;
-        }
-    }
-    __syncthreads();
-    if (threadIdx.x < K && blk_counts)
-        blk_counts[(int64_t)(k0 + threadIdx.x) * gridDim.x + blockIdx.x] =
-            s_cnt[threadIdx.x][0] + s_cnt[threadIdx.x][1] + s_cnt[threadIdx.x][2] + s_cnt[threadIdx.x][3];
-}
-
-// Same counting from an existing table (the scattered input-side table of a strided map).
-__global__ __launch_bounds__(kThreads) void count_kernel(const int32_t* __restrict__ nbr, int64_t n_rows,
-                                                         int32_t* __restrict__ sub_counts,
-                                                         int32_t* __restrict__ blk_counts) {
-    __shared__ int s_cnt[kSubTiles];
-    const int k = blockIdx.y, kvol = gridDim.y;
-    const int64_t r = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    const int32_t v = r < n_rows ? nbr[(int64_t)k * n_rows + r] : -1;
-    const unsigned long long live = __ballot(v >= 0);
-    if ((threadIdx.x & 63) == 0) {
-        int32_t* dst = sub_counts + (((int64_t)blockIdx.x * kSubTiles + (threadIdx.x >> 6)) * kvol + k) * kHalves;
-        dst[0] = __popc((unsigned)live);
-        dst[1] = __popc((unsigned)(live >> 32));
-        s_cnt[threadIdx.x >> 6] = __popcll(live);
-    }
-    if (!blk_counts) return;  // uniform
-    __syncthreads();
-    if (threadIdx.x == 0) blk_counts[(int64_t)k * gridDim.x + blockIdx.x] = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
-}
-
-// Compaction: every live (row, k) writes its entry at offset + (number of live lanes below it).
-__global__ __launch_bounds__(kThreads) void emit_kernel(const int32_t* __restrict__ nbr, int64_t n_rows,
-                                                        const int32_t* __restrict__ tl_off,
-                                                        int32_t* __restrict__ tl_src, uint16_t* __restrict__ tl_row,
-                                                        const int32_t* __restrict__ blk_off,
-                                                        int32_t* __restrict__ pair_in, int32_t* __restrict__ pair_out) {
-    __shared__ int s_cnt[kSubTiles];
-    const int k = blockIdx.y, kvol = gridDim.y;
-    const int64_t r = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    const int32_t v = r < n_rows ? nbr[(int64_t)k * n_rows + r] : -1;
-    const unsigned long long live = __ballot(v >= 0);
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int pos = __popcll(live & ((1ull << lane) - 1ull));  // among the wavefront's 64 rows
-    if (v >= 0) {
-        // the two 32-row halves of a sub-tile are adjacent in the list, so the position inside the sub-tile's
-        // stretch is the plain 64-lane rank
-        const int64_t e = (int64_t)tl_off[(((int64_t)blockIdx.x * kSubTiles + w) * kvol + k) * kHalves] + pos;
-        tl_src[e] = v;
-        tl_row[e] = (uint16_t)threadIdx.x;
-    }
-    if (pair_in) {  // uniform branch
-        if (lane == 0) s_cnt[w] = __popcll(live);
-        __syncthreads();
-        int before = 0;
-        for (int j = 0; j < w; ++j) before += s_cnt[j];
-        if (v >= 0) {
-            const int64_t p = (int64_t)blk_off[(int64_t)k * gridDim.x + blockIdx.x] + before + pos;
-            pair_in[p] = v;
-            pair_out[p] = (int32_t)r;
-        }
+        if (identity_k >= 0 && k0 + az > identity_k) continue;  // written by the mirrored offset's hits
+        nbr_out[(int64_t)(k0 + az) * n_out + o] = v[az];
+        if (nbr_in && v[az] >= 0) nbr_in[(int64_t)(k0 + az) * n_in + v[az]] = (int32_t)o;
+        if (identity_k >= 0 && k0 + az < identity_k && v[az] >= 0)
+            nbr_out[(int64_t)(kvol - 1 - (k0 + az)) * n_out + v[az]] = (int32_t)o;
     }
 }
-
-inline unsigned blocks256(int64_t n) { return (unsigned)((n + 255) / 256); }
 
 // Position class of an input row inside its coarse cell: ((x/ts) mod s, (y/ts) mod s, (z/ts) mod s) as one number.
 __device__ __forceinline__ int cell_class(const int4& c, int ts, int stride) {
@@ -182,111 +136,16 @@ __device__ __forceinline__ int cell_class(const int4& c, int ts, int stride) {
 // Even kernel as wide as the stride (offsets 0 .. K-1 = the positions inside a coarse cell): every input row
 // has exactly one link, to its own coarse cell (parent[i], from the coarse coordinates' merge), at the offset
 // that is its position in the cell.  No searches.
-__global__ __launch_bounds__(kThreads) void child_map_kernel(const int4* __restrict__ c_in, int64_t n_in, int ts,
-                                                             int stride, const int32_t* __restrict__ parent,
-                                                             int64_t n_out, int32_t* __restrict__ nbr_out,
-                                                             int32_t* __restrict__ nbr_in) {
+__global__ __launch_bounds__(kThreads) void child_map_kernel(const int4* __restrict__ c_in, Count cn_in, int ts, int stride,
+                                                             const int32_t* __restrict__ parent, Count cn_out,
+                                                             int32_t* __restrict__ nbr_out, int32_t* __restrict__ nbr_in) {
+    const int64_t n_in = get(cn_in), n_out = get(cn_out);
     const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (i >= n_in) return;
     const int k = cell_class(c_in[i], ts, stride);
     const int32_t o = parent[i];
     nbr_in[(int64_t)k * n_in + i] = o;
     nbr_out[(int64_t)k * n_out + o] = (int32_t)i;
-}
-
-// cnt[cls * ntiles + tile] = rows of the tile in class cls (tiles of 256 rows in row order)
-__global__ __launch_bounds__(kThreads) void class_count_kernel(const int4* __restrict__ coords, int64_t n, int ts,
-                                                               int stride, int nclass, int32_t* __restrict__ cnt) {
-    __shared__ int s_cnt[32][kSubTiles];
-    const int64_t r = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    const int cls = r < n ? cell_class(coords[r], ts, stride) : -1;
-    const int w = threadIdx.x >> 6;
-    for (int c = 0; c < nclass; ++c) {
-        const unsigned long long m = __ballot(cls == c);
-        if ((threadIdx.x & 63) == 0) s_cnt[c][w] = __popcll(m);
-    }
-    __syncthreads();
-    if (threadIdx.x < nclass)
-        cnt[(int64_t)threadIdx.x * gridDim.x + blockIdx.x] =
-            s_cnt[threadIdx.x][0] + s_cnt[threadIdx.x][1] + s_cnt[threadIdx.x][2] + s_cnt[threadIdx.x][3];
-}
-
-// perm[off[cls * ntiles + tile] + rank of the row among the tile's rows of its class] = row
-__global__ __launch_bounds__(kThreads) void class_emit_kernel(const int4* __restrict__ coords, int64_t n, int ts,
-                                                              int stride, int nclass, const int32_t* __restrict__ off,
-                                                              int32_t* __restrict__ perm) {
-    __shared__ int s_cnt[32][kSubTiles];
-    const int64_t r = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    const int cls = r < n ? cell_class(coords[r], ts, stride) : -1;
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    int rank = 0;
-    for (int c = 0; c < nclass; ++c) {
-        const unsigned long long m = __ballot(cls == c);
-        if (lane == 0) s_cnt[c][w] = __popcll(m);
-        if (cls == c) rank = __popcll(m & ((1ull << lane) - 1ull));
-    }
-    __syncthreads();
-    if (cls >= 0) {
-        for (int j = 0; j < w; ++j) rank += s_cnt[cls][j];
-        perm[off[(int64_t)cls * gridDim.x + blockIdx.x] + rank] = (int32_t)r;
-    }
-}
-
-// mask[tile][k / 32] bit k % 32 = offset k can link a row of one of the position classes present in
-// perm[tile*256 .. +255].  Offset (ax, ay, az) links an input at class r to an output only if, per axis, the
-// offset's displacement is congruent to r modulo the stride (output coordinates are multiples of the stride).
-// One thread per tile; the classes' stretches of perm start at off[cls * ntiles].
-__global__ __launch_bounds__(kThreads) void tile_mask_kernel(const int32_t* __restrict__ off, int64_t n, int64_t ntiles,
-                                                             int K, int stride, uint32_t* __restrict__ mask) {
-    __shared__ uint32_t s_cm[32][4];   // offsets possible for each class
-    __shared__ int64_t s_beg[33];      // the classes' stretches of perm
-    const int nclass = stride * stride * stride, centre = (K & 1) ? (K - 1) / 2 : 0;
-    if (threadIdx.x < nclass) {
-        const int c = threadIdx.x;
-        const int r[3] = {c / (stride * stride), c / stride % stride, c % stride};
-        uint32_t m[4] = {0u, 0u, 0u, 0u};
-        for (int k = 0; k < K * K * K; ++k) {
-            const int d[3] = {k / (K * K) - centre, k / K % K - centre, k % K - centre};
-            bool ok = true;
-            for (int ax = 0; ax < 3; ++ax) ok = ok && ((d[ax] % stride + stride) % stride == r[ax]);
-            if (ok) m[k >> 5] |= 1u << (k & 31);
-        }
-        for (int i = 0; i < 4; ++i) s_cm[c][i] = m[i];
-        s_beg[c] = off[(int64_t)c * ntiles];
-        if (c == nclass - 1) s_beg[nclass] = n;
-    }
-    __syncthreads();
-    const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (t >= ntiles) return;
-    const int64_t lo = t * kTileRows, hi = lo + kTileRows < n ? lo + kTileRows : n;
-    uint32_t m[4] = {0u, 0u, 0u, 0u};
-    for (int c = 0; c < nclass; ++c)
-        if (s_beg[c] < hi && s_beg[c + 1] > lo)
-            for (int i = 0; i < 4; ++i) m[i] |= s_cm[c][i];
-    for (int i = 0; i < 4; ++i) mask[t * 4 + i] = m[i];
-}
-
-// Rows of a strided map's input side sorted by position class, and the per-tile offset masks.
-int build_classes(MapSide& side, const sp_coords* c, int stride, int K, hipStream_t s) {
-    const int nclass = stride * stride * stride;
-    const int64_t n = side.n_rows, ntiles = (n + kTileRows - 1) / kTileRows;
-    if (nclass > 32 || n == 0) return SP_OK;  // larger strides: no class order, the kernels take all offsets
-    Buf cnt = dev_alloc((size_t)(nclass * ntiles + 1) * 4, s);
-    side.perm = dev_alloc((size_t)n * 4, s);
-    side.tile_mask = dev_alloc((size_t)ntiles * 16, s);
-    if (!cnt || !side.perm || !side.tile_mask) return SP_ERR_ALLOC;
-    hipLaunchKernelGGL(class_count_kernel, dim3((unsigned)ntiles), dim3(kThreads), 0, s, ptr<int4>(c->coords), n, c->ts,
-                       stride, nclass, ptr<int32_t>(cnt));
-    ScanJob job;
-    job.data = ptr<int32_t>(cnt);
-    job.n = nclass * ntiles;
-    SP_TRY(exclusive_scan_jobs(&job, 1, s));
-    hipLaunchKernelGGL(class_emit_kernel, dim3((unsigned)ntiles), dim3(kThreads), 0, s, ptr<int4>(c->coords), n, c->ts,
-                       stride, nclass, ptr<int32_t>(cnt), ptr<int32_t>(side.perm));
-    hipLaunchKernelGGL(tile_mask_kernel, dim3(blocks256(ntiles)), dim3(kThreads), 0, s, ptr<int32_t>(cnt), n, ntiles, K,
-                       stride, ptr<uint32_t>(side.tile_mask));
-    SP_HIP(hipGetLastError());
-    return SP_OK;
 }
 
 // Generative transposed convolution.  Candidate (j, k) = input row j displaced by offset k times the output
@@ -309,8 +168,9 @@ __global__ __launch_bounds__(kThreads) void gen_candidates_kernel(const int4* __
 // where[j*kvol + k] = fine row of candidate (j, k).  As a stride-s convolution from the fine rows (inputs) to
 // the coarse rows (outputs) every candidate is one link: nbr_out[k][j] = that fine row, nbr_in[k][fine] = j.
 __global__ __launch_bounds__(kThreads) void gen_tables_kernel(const int32_t* __restrict__ where, int64_t n_coarse,
-                                                              int64_t n_fine, int kvol, int32_t* __restrict__ nbr_out,
+                                                              Count cn_fine, int kvol, int32_t* __restrict__ nbr_out,
                                                               int32_t* __restrict__ nbr_in) {
+    const int64_t n_fine = get(cn_fine);
     const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;   // = k * n_coarse + j: coalesced table writes
     if (t >= n_coarse * kvol) return;
     const int k = (int)(t / n_coarse);
@@ -320,102 +180,484 @@ __global__ __launch_bounds__(kThreads) void gen_tables_kernel(const int32_t* __r
     nbr_in[(int64_t)k * n_fine + f] = (int32_t)j;
 }
 
-// Turns sub-tile counts (already in side.tl_off) into offsets and fills the tile lists.
-// `total`: the number of links, or any upper bound of it (the lists are then allocated larger than needed).
-int finish_side(MapSide& side, int kvol, int64_t total, const int32_t* d_blk_off, int32_t* d_pair_in,
-                int32_t* d_pair_out, hipStream_t s) {
-    const int64_t ntiles = (side.n_rows + kTileRows - 1) / kTileRows;
-    side.tl_src = dev_alloc((size_t)(total ? total : 1) * 4, s);
-    side.tl_row = dev_alloc((size_t)(total ? total : 1) * 2, s);
-    if (!side.tl_src || !side.tl_row) return SP_ERR_ALLOC;
-    if (ntiles > 0 && total > 0)
-        hipLaunchKernelGGL(emit_kernel, dim3((unsigned)ntiles, kvol), dim3(kThreads), 0, s, ptr<int32_t>(side.nbr),
-                           side.n_rows, ptr<int32_t>(side.tl_off), ptr<int32_t>(side.tl_src),
-                           ptr<uint16_t>(side.tl_row), d_blk_off, d_pair_in, d_pair_out);
-    SP_HIP(hipGetLastError());
+// ---------------------------------------------------------------------------------------------------------------
+// One side of a map: neighbour table -> lists, in two launches.
+//
+// count_kernel: per tile (256 destination rows) the live entries per (sub-tile, offset, 32-row half) into cnt and
+// the tile's links per offset into agg[tile][*].  On a strided map's input side the rows per position class ride
+// along as extra sums (width = kvol + nclass).
+// prefix_kernel: one workgroup per sum scans it over the tiles: excl[tile][*].
+// emit_kernel: tile t writes
+//   tl_off  list offsets of its 4 sub-tiles: index ((t*4 + sub)*kvol + k)*2 + half, sub-tile-major stretches
+//   tl_src / tl_row  the tile lists (source row, destination row inside the tile), destination rows ascending
+//   pair_in / pair_out (output side only)  offset k's pairs at k*pair_stride + (links of earlier tiles at k) + rank
+//   cls_excl[t][*] (classes)  rows of each position class in earlier tiles, for class_emit_kernel
+// The last tile writes koff (prefix of the per-offset totals) to device memory and the mail slot, and the class
+// bases.
+// ---------------------------------------------------------------------------------------------------------------
+struct Sums {
+    int32_t* agg;   // [tile][width]: the tile's own sums (count_kernel)
+    int32_t* excl;  // [tile][width]: sums of all earlier tiles (prefix_kernel)
+    int width;      // kvol (+ nclass)
+};
+
+struct CountArgs {
+    const int32_t* nbr;
+    Count n_rows;
+    int kvol;
+    int32_t* cnt;   // [tile][sub][k][half]
+    Sums sums;
+    const int4* coords;  // classes (input side of a strided map), else nclass = 0
+    int ts, stride, nclass;
+};
+
+constexpr int kChunk = 9;  // offsets whose table entries a thread requests before it looks at any of them
+
+// grid (tiles, chunks of kChunk offsets): a workgroup counts one chunk of offsets of one tile (one table entry per
+// thread and offset, all requested before any is looked at); the chunk-0 workgroup also counts the classes.
+__global__ __launch_bounds__(kThreads) void count_kernel(CountArgs a) {
+    __shared__ int s_cnt[kSubTiles][kChunk][kHalves];
+    __shared__ int s_cls[32][kSubTiles];
+    const int kvol = a.kvol, width = a.sums.width;
+    const int n_ent = kSubTiles * kvol * kHalves;
+    const int64_t n = get(a.n_rows);
+    const int64_t t = blockIdx.x;
+    if (t * kTileRows >= n) return;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int64_t r = t * kTileRows + tid;
+    const int k0 = blockIdx.y * kChunk;
+    int32_t v[kChunk];
+#pragma unroll
+    for (int j = 0; j < kChunk; ++j) v[j] = (r < n && k0 + j < kvol) ? a.nbr[(int64_t)(k0 + j) * n + r] : -1;
+#pragma unroll
+    for (int j = 0; j < kChunk; ++j) {
+        const unsigned long long live = __ballot(v[j] >= 0);
+        if (lane == 0) {
+            s_cnt[w][j][0] = __popc((unsigned)live);
+            s_cnt[w][j][1] = __popc((unsigned)(live >> 32));
+        }
+    }
+    const bool classes = a.nclass && blockIdx.y == 0;
+    if (classes) {
+        const int cls = r < n ? cell_class(a.coords[r], a.ts, a.stride) : -1;
+        for (int c = 0; c < a.nclass; ++c) {
+            const unsigned long long m = __ballot(cls == c);
+            if (lane == 0) s_cls[c][w] = __popcll(m);
+        }
+    }
+    __syncthreads();
+    if (tid < kSubTiles * kChunk * kHalves) {
+        const int ww = tid / (kChunk * kHalves), j = tid / kHalves % kChunk, h = tid % kHalves;
+        if (k0 + j < kvol) a.cnt[t * n_ent + (ww * kvol + k0 + j) * kHalves + h] = s_cnt[ww][j][h];
+    }
+    if (tid < kChunk && k0 + tid < kvol) {
+        int sum = 0;
+        for (int ww = 0; ww < kSubTiles; ++ww) sum += s_cnt[ww][tid][0] + s_cnt[ww][tid][1];
+        a.sums.agg[t * width + k0 + tid] = sum;
+    }
+    if (classes && tid >= 64 && tid < 64 + a.nclass) {
+        int sum = 0;
+        for (int ww = 0; ww < kSubTiles; ++ww) sum += s_cls[tid - 64][ww];
+        a.sums.agg[t * width + kvol + tid - 64] = sum;
+    }
+}
+
+// Block i: excl[t][i] = sum of agg[t'][i] over t' < t, for all tiles (1024 tiles a round, running carry).
+__global__ __launch_bounds__(1024) void prefix_kernel(Sums sm, Count n_rows) {
+    __shared__ int s_wave[16];
+    __shared__ int s_carry;
+    const int i = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int64_t n = get(n_rows);
+    const int64_t ntiles = (n + kTileRows - 1) / kTileRows;
+    if (tid == 0) s_carry = 0;
+    __syncthreads();
+    for (int64_t t0 = 0; t0 < ntiles; t0 += 1024) {
+        const int64_t t = t0 + tid;
+        const int v = t < ntiles ? sm.agg[t * sm.width + i] : 0;
+        int inc = v;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int u = __shfl_up(inc, d, 64);
+            if (lane >= d) inc += u;
+        }
+        if (lane == 63) s_wave[w] = inc;
+        __syncthreads();
+        int before = s_carry;
+        for (int ww = 0; ww < w; ++ww) before += s_wave[ww];
+        if (t < ntiles) sm.excl[t * sm.width + i] = before + inc - v;
+        __syncthreads();
+        if (tid == 1023) s_carry = before + inc;
+        __syncthreads();
+    }
+}
+
+struct EmitArgs {
+    const int32_t* nbr;
+    Count n_rows;
+    int kvol;
+    const int32_t* cnt;  // count_kernel's counts (the workgroups that share a tile all read them: not tl_off itself)
+    int32_t* tl_off;
+    int32_t* tl_src;
+    uint16_t* tl_row;
+    int32_t* pair_in;   // null on the input side
+    int32_t* pair_out;
+    int64_t pair_stride;
+    Sums sums;
+    int nclass;
+    int32_t* cls_excl;  // [tile][nclass]: rows of class c in earlier tiles
+    int32_t* cls_base;  // [nclass + 1]: first position of class c in the class-sorted order (written by the last tile)
+    // results
+    int32_t* d_koff;    // [kvol + 1] (output side only)
+    uint32_t* mail;     // null or the mail slot: n_in, n_out, error bits, koff[0..kvol]
+    uint32_t mail_seq;
+    Count n_in, n_out;  // for the mail
+};
+
+__global__ __launch_bounds__(kThreads) void emit_kernel(EmitArgs a) {
+    __shared__ int s_cnt[kSubTiles * kMaxKvol * kHalves + 2];  // [sub][k][half]: counts, then list offsets
+    __shared__ int s_own[kMaxKvol + 32], s_excl[kMaxKvol + 32];
+    const int kvol = a.kvol, width = a.sums.width;
+    const int64_t n = get(a.n_rows);
+    const int64_t ntiles = (n + kTileRows - 1) / kTileRows;
+    const int64_t t = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    if (t >= ntiles && !(t == 0 && ntiles == 0)) return;
+    const bool empty = ntiles == 0;  // tile 0 of an empty side only delivers the (zero) results
+    const int64_t r = t * kTileRows + tid;
+    const int n_ent = kSubTiles * kvol * kHalves;
+
+    // ---- this tile's counts, and the sums of everything before it
+    if (!empty) {
+        for (int e = tid; e < n_ent; e += kThreads) s_cnt[e] = a.cnt[t * n_ent + e];
+        for (int i = tid; i < width; i += kThreads) {
+            s_excl[i] = a.sums.excl[t * width + i];
+            s_own[i] = a.sums.agg[t * width + i];
+        }
+    } else {
+        for (int i = tid; i < width; i += kThreads) s_own[i] = s_excl[i] = 0;
+    }
+    __syncthreads();
+
+    // ---- the last tile delivers the totals (gridDim.y workgroups share a tile: each emits a chunk of the offsets,
+    // the first one also writes what belongs to the tile as a whole)
+    const bool lead = blockIdx.y == 0;
+    if (lead && t == (empty ? 0 : ntiles - 1) && tid == 0) {
+        if (a.nclass) {
+            int run = 0;
+            for (int c = 0; c < a.nclass; ++c) {
+                a.cls_base[c] = run;
+                run += s_excl[kvol + c] + s_own[kvol + c];
+            }
+            a.cls_base[a.nclass] = run;
+        }
+        if (a.d_koff) {
+            int run = 0;
+            for (int k = 0; k < kvol; ++k) {
+                a.d_koff[k] = run;
+                if (a.mail) a.mail[3 + k] = (uint32_t)run;
+                run += s_excl[k] + s_own[k];
+            }
+            a.d_koff[kvol] = run;
+            if (a.mail) {
+                a.mail[3 + kvol] = (uint32_t)run;
+                a.mail[0] = (uint32_t)get(a.n_in);
+                a.mail[1] = (uint32_t)get(a.n_out);
+                a.mail[2] = 0u;
+                __threadfence_system();
+                __hip_atomic_store(a.mail + kMailSeqWord, a.mail_seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+            }
+        }
+    }
+    if (empty) {
+        if (lead && tid == 0) a.tl_off[0] = 0;
+        return;
+    }
+    if (lead && a.nclass)
+        for (int c = tid; c < a.nclass; c += kThreads) a.cls_excl[t * a.nclass + c] = s_excl[kvol + c];
+
+    // ---- list offsets of the tile: links of all earlier tiles + exclusive scan over (sub, k, half).
+    // Wavefront 0: lane l takes the entries [l*per, l*per + per).  s_cnt then holds offsets, with the end of the
+    // tile's stretch in the entry after the last.
+    if (w == 0) {
+        int before = 0;
+        for (int k = 0; k < kvol; ++k) before += s_excl[k];   // the same in every lane: links of all earlier tiles
+        const int per = (n_ent + 63) / 64;
+        int sum = 0;
+        for (int j = 0; j < per; ++j) {
+            const int e = lane * per + j;
+            if (e < n_ent) sum += s_cnt[e];
+        }
+        int inc = sum;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int u = __shfl_up(inc, d, 64);
+            if (lane >= d) inc += u;
+        }
+        int run = before + inc - sum;
+        for (int j = 0; j < per; ++j) {
+            const int e = lane * per + j;
+            if (e < n_ent) {
+                const int c = s_cnt[e];
+                s_cnt[e] = run;  // from here on: the entry's list offset
+                if (lead) a.tl_off[t * n_ent + e] = run;
+                run += c;
+            }
+        }
+        if (lane == 63) {
+            s_cnt[n_ent] = run;                                        // all lanes' entries precede: run = end of the tile
+            if (lead && t == ntiles - 1) a.tl_off[ntiles * n_ent] = run;  // end of the last stretch = all links
+        }
+    }
+    __syncthreads();
+
+    // ---- emit: every live (row, k) writes its entry at offset + (number of live lanes below it)
+    for (int k0 = blockIdx.y * kChunk; k0 < kvol; k0 += gridDim.y * kChunk) {
+      int32_t vv[kChunk];
+#pragma unroll
+      for (int j = 0; j < kChunk; ++j) vv[j] = (r < n && k0 + j < kvol) ? a.nbr[(int64_t)(k0 + j) * n + r] : -1;
+#pragma unroll
+      for (int j = 0; j < kChunk; ++j) {
+        const int k = k0 + j;
+        const int32_t v = vv[j];
+        const unsigned long long live = __ballot(v >= 0);
+        const int pos = __popcll(live & ((1ull << lane) - 1ull));  // among the wavefront's 64 rows
+        if (v >= 0) {
+            // the two 32-row halves of a sub-tile are adjacent in the list, so the position inside the sub-tile's
+            // stretch is the plain 64-lane rank
+            const int64_t e = (int64_t)s_cnt[(w * kvol + k) * kHalves] + pos;
+            a.tl_src[e] = v;
+            a.tl_row[e] = (uint16_t)tid;
+            if (a.pair_in) {
+                // links of this tile at offset k in the sub-tiles before this one, from the sizes of their stretches
+                int before = 0;
+                for (int ww = 0; ww < w; ++ww)
+                    before += s_cnt[(ww * kvol + k + 1) * kHalves] - s_cnt[(ww * kvol + k) * kHalves];
+                const int64_t p = (int64_t)k * a.pair_stride + s_excl[k] + before + pos;
+                a.pair_in[p] = v;
+                a.pair_out[p] = (int32_t)r;
+            }
+        }
+      }
+    }
+}
+
+// Rows of a strided map's input side in position-class order, and per 256 entries of that order the offsets
+// that can link them.  perm[cls_base[c] + (rows of class c in earlier tiles) + rank in the tile] = row.
+// mask[tile][k / 32] bit k % 32 = offset k can link a row of one of the position classes present in
+// perm[tile*256 .. +255]: offset (ax, ay, az) links an input at class r to an output only if, per axis, the
+// offset's displacement is congruent to r modulo the stride (output coordinates are multiples of the stride).
+__global__ __launch_bounds__(kThreads) void class_emit_kernel(const int4* __restrict__ coords, Count cn, int ts, int stride,
+                                                              int nclass, int K, const int32_t* __restrict__ cls_excl,
+                                                              const int32_t* __restrict__ cls_base,
+                                                              int32_t* __restrict__ perm, uint32_t* __restrict__ mask) {
+    __shared__ int s_cnt[32][kSubTiles];
+    __shared__ uint32_t s_cm[32][4];  // offsets possible for each class
+    const int64_t n = get(cn);
+    const int64_t t = blockIdx.x;
+    if (t * kTileRows >= n) return;
+    const int64_t r = t * kTileRows + threadIdx.x;
+    const int cls = r < n ? cell_class(coords[r], ts, stride) : -1;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int rank = 0;
+    for (int c = 0; c < nclass; ++c) {
+        const unsigned long long m = __ballot(cls == c);
+        if (lane == 0) s_cnt[c][w] = __popcll(m);
+        if (cls == c) rank = __popcll(m & ((1ull << lane) - 1ull));
+    }
+    const int centre = (K & 1) ? (K - 1) / 2 : 0;
+    if ((int)threadIdx.x < nclass) {
+        const int c = threadIdx.x;
+        const int rr[3] = {c / (stride * stride), c / stride % stride, c % stride};
+        uint32_t m[4] = {0u, 0u, 0u, 0u};
+        for (int k = 0; k < K * K * K; ++k) {
+            const int d[3] = {k / (K * K) - centre, k / K % K - centre, k % K - centre};
+            bool ok = true;
+            for (int ax = 0; ax < 3; ++ax) ok = ok && ((d[ax] % stride + stride) % stride == rr[ax]);
+            if (ok) m[k >> 5] |= 1u << (k & 31);
+        }
+        for (int i = 0; i < 4; ++i) s_cm[c][i] = m[i];
+    }
+    __syncthreads();
+    if (cls >= 0) {
+        for (int j = 0; j < w; ++j) rank += s_cnt[cls][j];
+        perm[cls_base[cls] + cls_excl[t * nclass + cls] + rank] = (int32_t)r;
+    }
+    if (threadIdx.x < 4) {  // the mask of tile t of the class-sorted order
+        const int64_t lo = t * kTileRows, hi = lo + kTileRows < n ? lo + kTileRows : n;
+        uint32_t m = 0u;
+        for (int c = 0; c < nclass; ++c)
+            if (cls_base[c] < hi && cls_base[c + 1] > lo) m |= s_cm[c][threadIdx.x];
+        mask[t * 4 + threadIdx.x] = m;
+    }
+}
+
+inline unsigned blocks256(int64_t n) { return (unsigned)((n + 255) / 256); }
+
+// Everything a build needs besides the tables: the tile counts and sums of both sides, the class prefixes of a
+// strided input side.
+struct Work {
+    Buf mem;
+    int32_t *cnt_out = nullptr, *cnt_in = nullptr;
+    Sums sums_out{}, sums_in{};
+    int32_t *cls_excl = nullptr, *cls_base = nullptr;
+};
+
+int make_work(Work& wk, int64_t nt_out, int64_t nt_in, int kvol, int nclass, bool two_sides, hipStream_t s) {
+    const int64_t no = nt_out ? nt_out : 1, ni = two_sides ? (nt_in ? nt_in : 1) : 0;
+    const int w_out = kvol, w_in = kvol + nclass;
+    const int64_t n_ent = (int64_t)kSubTiles * kvol * kHalves;
+    const int64_t words = 2 * no * w_out + 2 * ni * w_in + ni * nclass + nclass + 2 + (no + ni) * n_ent;
+    wk.mem = dev_alloc((size_t)words * 4, s);
+    if (!wk.mem) return SP_ERR_ALLOC;
+    int32_t* q = ptr<int32_t>(wk.mem);
+    wk.sums_out = Sums{q, q + no * w_out, w_out};
+    q += 2 * no * w_out;
+    wk.sums_in = Sums{q, q + ni * w_in, w_in};
+    q += 2 * ni * w_in;
+    wk.cls_excl = q;
+    wk.cls_base = q + ni * nclass;
+    q += ni * nclass + nclass + 2;
+    wk.cnt_out = q;
+    wk.cnt_in = q + no * n_ent;
     return SP_OK;
 }
 
-
 // Second half of a map build, shared by every way of filling the neighbour tables: on entry both tables are
-// complete, so.tl_off holds the output side's link counts per (sub-tile, offset, half) and blk those per
-// (offset, tile).  Scans them, reads the per-offset pair counts back, and compacts the tables into the pair
-// lists and the tile lists of both sides (a symmetric map shares one table and one set of lists).
-int finish_map(sp_kmap* m, bool symmetric, const Buf& blk, const Buf& small, hipStream_t s) {
+// complete (on the stream).  One launch per side turns them into lists; a strided input side also gets its
+// position-class order.  n_in_ub / n_out_ub: upper bounds of the row counts, cn_in / cn_out: where the kernels
+// find the true ones.
+int finish_map(sp_kmap* m, bool symmetric, Work& wk, int64_t n_in_ub, int64_t n_out_ub, Count cn_in, Count cn_out,
+               int nclass, hipStream_t s) {
     MapSide& so = m->out_side;
     MapSide& si = m->in_side;
-    sp_coords* cin = m->c_in;
-    const int kvol = m->kvol, stride = m->stride, kernel_size = m->K;
-    const int64_t n_in = m->n_in, n_out = m->n_out;
-    const int64_t nt_out = (n_out + kTileRows - 1) / kTileRows, nt_in = (n_in + kTileRows - 1) / kTileRows;
-    int32_t* d_koff = ptr<int32_t>(small);
-    // both scans in one launch pair: sub-tile-major list offsets, and offset-major pair-list offsets whose
-    // values at the start of each offset (every nt_out-th element) are the per-offset prefix koff[]
+    const int kvol = m->kvol;
+    const int64_t nt_out = (n_out_ub + kTileRows - 1) / kTileRows, nt_in = (n_in_ub + kTileRows - 1) / kTileRows;
+    const int64_t most = std::min(n_out_ub, n_in_ub) * kvol;  // links there can be
+    m->pair_stride = std::min(n_out_ub, n_in_ub);
+    m->pair_in = dev_alloc((size_t)(most ? most : 1) * 4, s);
+    m->pair_out = dev_alloc((size_t)(most ? most : 1) * 4, s);
+    m->d_koff = dev_alloc((size_t)(kvol + 1) * 4, s);
+    so.tl_src = dev_alloc((size_t)(most ? most : 1) * 4, s);
+    so.tl_row = dev_alloc((size_t)(most ? most : 1) * 2, s);
+    if (!m->pair_in || !m->pair_out || !m->d_koff || !so.tl_src || !so.tl_row) return SP_ERR_ALLOC;
+    const bool mailed = mail_acquire(&m->mail);
+    EmitArgs a{};
+    a.nbr = ptr<int32_t>(so.nbr);
+    a.n_rows = cn_out;
+    a.kvol = kvol;
+    a.tl_off = ptr<int32_t>(so.tl_off);
+    a.tl_src = ptr<int32_t>(so.tl_src);
+    a.tl_row = ptr<uint16_t>(so.tl_row);
+    a.pair_in = ptr<int32_t>(m->pair_in);
+    a.pair_out = ptr<int32_t>(m->pair_out);
+    a.pair_stride = m->pair_stride;
+    a.cnt = wk.cnt_out;
+    a.sums = wk.sums_out;
+    a.d_koff = ptr<int32_t>(m->d_koff);
+    a.mail = mailed ? m->mail.d : nullptr;
+    a.mail_seq = m->mail.seq;
+    a.n_in = cn_in;
+    a.n_out = cn_out;
     {
-        const int64_t n_sub = nt_out * kvol * kSubTiles * kHalves;
-        ScanJob jobs[2];
-        jobs[0].data = ptr<int32_t>(so.tl_off);
-        jobs[0].n = n_sub;
-        jobs[0].total = ptr<int32_t>(so.tl_off) + n_sub;
-        jobs[1].data = ptr<int32_t>(blk);
-        jobs[1].n = nt_out * kvol;
-        jobs[1].koff = d_koff;
-        jobs[1].koff_stride = nt_out > 0 ? nt_out : 1;
-        jobs[1].koff_n = kvol;
-        SP_TRY(exclusive_scan_jobs(jobs, 2, s));
+        CountArgs c{};
+        c.nbr = a.nbr;
+        c.n_rows = cn_out;
+        c.kvol = kvol;
+        c.cnt = wk.cnt_out;
+        c.sums = wk.sums_out;
+        hipLaunchKernelGGL(count_kernel, dim3((unsigned)(nt_out ? nt_out : 1), (unsigned)((kvol + kChunk - 1) / kChunk)), dim3(kThreads), 0, s, c);
+        hipLaunchKernelGGL(prefix_kernel, dim3((unsigned)c.sums.width), dim3(1024), 0, s, c.sums, cn_out);
     }
-    // The host needs the pair counts (for its own bookkeeping and the callers'), the device does not: unless
-    // the lists would be huge, they are allocated for the most links there can be and the compaction is
-    // enqueued behind the read-back, so the GPU does not idle while the host wakes up and launches.
-    const int64_t most = std::min(n_out, n_in) * kvol;
-    const bool early = most * 14 <= ((int64_t)512 << 20);
-    int early_rc = SP_OK;
-    auto emit_out_side = [&](int64_t total) {
-        m->pair_in = dev_alloc((size_t)(total ? total : 1) * 4, s);
-        m->pair_out = dev_alloc((size_t)(total ? total : 1) * 4, s);
-        if (!m->pair_in || !m->pair_out) return (int)SP_ERR_ALLOC;
-        return finish_side(so, kvol, total, ptr<int32_t>(blk), ptr<int32_t>(m->pair_in), ptr<int32_t>(m->pair_out), s);
-    };
-    // the input side of a map without the stride-1 symmetry: its own counts, list offsets, lists and classes
-    auto emit_in_side = [&](int64_t total) {
-        if (nt_in > 0)
-            hipLaunchKernelGGL(count_kernel, dim3((unsigned)nt_in, kvol), dim3(kThreads), 0, s, ptr<int32_t>(si.nbr),
-                               n_in, ptr<int32_t>(si.tl_off), (int32_t*)nullptr);
-        const int64_t n_sub_in = nt_in * kvol * kSubTiles * kHalves;
-        ScanJob job;
-        job.data = ptr<int32_t>(si.tl_off);
-        job.n = n_sub_in;
-        job.total = ptr<int32_t>(si.tl_off) + n_sub_in;
-        SP_TRY(exclusive_scan_jobs(&job, 1, s));
-        SP_TRY(finish_side(si, kvol, total, nullptr, nullptr, nullptr, s));
-        if (stride > 1) SP_TRY(build_classes(si, cin, stride, kernel_size, s));
-        return (int)SP_OK;
-    };
-    std::vector<int32_t> h_koff(kvol + 1);
-    SP_TRY(read_back(h_koff.data(), d_koff, (size_t)(kvol + 1) * 4, s, [&]() {
-        if (!early) return;
-        early_rc = emit_out_side(most);
-        if (early_rc == SP_OK && !symmetric) early_rc = emit_in_side(most);
-    }));
-    SP_TRY(early_rc);
-    m->koff.resize(kvol + 1);
-    m->counts.resize(kvol);
-    for (int k = 0; k <= kvol; ++k) m->koff[k] = h_koff[k];
-    for (int k = 0; k < kvol; ++k) m->counts[k] = m->koff[k + 1] - m->koff[k];
-    m->total = m->koff[kvol];
-    m->d_koff = small;
-    if (!early) SP_TRY(emit_out_side(m->total));
+    const unsigned chunks = (unsigned)((kvol + kChunk - 1) / kChunk);
+    hipLaunchKernelGGL(emit_kernel, dim3((unsigned)(nt_out ? nt_out : 1), chunks), dim3(kThreads), 0, s, a);
     if (symmetric) {
         si = so;  // same lists; the link (i, o) at offset k is the link (o, i) at offset kvol-1-k
         si.flip = true;
-    } else if (!early) {
-        SP_TRY(emit_in_side(m->total));
+    } else {
+        si.tl_src = dev_alloc((size_t)(most ? most : 1) * 4, s);
+        si.tl_row = dev_alloc((size_t)(most ? most : 1) * 2, s);
+        if (!si.tl_src || !si.tl_row) return SP_ERR_ALLOC;
+        EmitArgs b{};
+        b.nbr = ptr<int32_t>(si.nbr);
+        b.n_rows = cn_in;
+        b.kvol = kvol;
+        b.tl_off = ptr<int32_t>(si.tl_off);
+        b.tl_src = ptr<int32_t>(si.tl_src);
+        b.tl_row = ptr<uint16_t>(si.tl_row);
+        b.cnt = wk.cnt_in;
+        b.sums = wk.sums_in;
+        b.nclass = nclass;
+        b.cls_excl = wk.cls_excl;
+        b.cls_base = wk.cls_base;
+        CountArgs c{};
+        c.nbr = b.nbr;
+        c.n_rows = cn_in;
+        c.kvol = kvol;
+        c.cnt = wk.cnt_in;
+        c.sums = wk.sums_in;
+        c.coords = ptr<int4>(m->c_in->coords);
+        c.ts = m->c_in->ts;
+        c.stride = m->stride;
+        c.nclass = nclass;
+        hipLaunchKernelGGL(count_kernel, dim3((unsigned)(nt_in ? nt_in : 1), chunks), dim3(kThreads), 0, s, c);
+        hipLaunchKernelGGL(prefix_kernel, dim3((unsigned)c.sums.width), dim3(1024), 0, s, c.sums, cn_in);
+        hipLaunchKernelGGL(emit_kernel, dim3((unsigned)(nt_in ? nt_in : 1), chunks), dim3(kThreads), 0, s, b);
+        if (nclass && n_in_ub > 0) {
+            si.perm = dev_alloc((size_t)n_in_ub * 4, s);
+            si.tile_mask = dev_alloc((size_t)nt_in * 16, s);
+            if (!si.perm || !si.tile_mask) return SP_ERR_ALLOC;
+            hipLaunchKernelGGL(class_emit_kernel, dim3((unsigned)nt_in), dim3(kThreads), 0, s, ptr<int4>(m->c_in->coords), cn_in,
+                               m->c_in->ts, m->stride, nclass, m->K, wk.cls_excl, wk.cls_base, ptr<int32_t>(si.perm),
+                               ptr<uint32_t>(si.tile_mask));
+        }
+    }
+    SP_HIP(hipGetLastError());
+    if (!mailed) {  // no mail slot free: wait here
+        std::vector<uint32_t> h(kvol + 1);
+        SP_TRY(read_back(h.data(), ptr<int32_t>(m->d_koff), (size_t)(kvol + 1) * 4, s));
+        SP_TRY(coords_resolve(m->c_in));
+        SP_TRY(coords_resolve(m->c_out));
+        m->set_sizes(m->c_in->n, m->c_out->n, h.data());
+        m->status = SP_OK;
+        m->resolved = true;
     }
     return SP_OK;
 }
 
 }  // namespace
+
+int kmap_resolve(const sp_kmap_t* m) {
+    std::lock_guard<std::mutex> lk(m->mu);
+    if (!m->resolved) {
+        SP_TRY(mail_wait(m->mail, m->stream));
+        const uint32_t* h = m->mail.h;
+        m->set_sizes((int64_t)h[0], (int64_t)h[1], h + 3);
+        m->status = SP_OK;
+        m->resolved = true;
+        mail_release(&m->mail);
+    }
+    // an error found while the coordinate sets were built (a coordinate out of range) makes the map invalid too
+    if (m->c_in) SP_TRY(coords_resolve(m->c_in));
+    if (m->c_out && m->c_out != m->c_in) SP_TRY(coords_resolve(m->c_out));
+    return SP_OK;
+}
+
 }  // namespace sp
+
+// host copies of the sizes, once they have arrived: koff = kvol + 1 prefix values
+void sp_kmap::set_sizes(int64_t ni, int64_t no, const uint32_t* koff_words) const {
+    n_in = ni;
+    n_out = no;
+    koff.resize(kvol + 1);
+    counts.resize(kvol);
+    for (int k = 0; k <= kvol; ++k) koff[k] = koff_words[k];
+    for (int k = 0; k < kvol; ++k) counts[k] = koff[k + 1] - koff[k];
+    total = koff[kvol];
+    out_side.n_rows = no;
+    out_side.n_src = ni;
+    in_side.n_rows = ni;
+    in_side.n_src = no;
+}
 
 using namespace sp;
 
@@ -433,76 +675,96 @@ int sp_kmap_build(const sp_coords_t* in, int32_t kernel_size, int32_t stride, in
         return fail(SP_ERR_RANGE, "tensor stride * stride / dilation leaves the packable coordinate range");
     hipStream_t s = (hipStream_t)stream;
     const int kvol = kernel_size * kernel_size * kernel_size;
-    if (in->n * (int64_t)kvol >= ((int64_t)1 << 31) - 4096)
+    // Sizes: the input set's row count may not have reached the host yet.  Then its source row count bounds it;
+    // when that bound would make the tables and lists much larger than they can need to be (many duplicates in
+    // a large input), waiting for the count is the cheaper choice.
+    bool known;
+    {
+        std::lock_guard<std::mutex> lk(in->mu);
+        known = in->resolved;
+    }
+    if (!known && in->n_raw * (int64_t)kvol * 18 > ((int64_t)1 << 30)) {
+        SP_TRY(coords_resolve(in));
+        known = true;
+    }
+    if (known) SP_TRY(coords_resolve(in));  // reports an error found while it was built
+    const int64_t n_in_ub = known ? in->n : in->n_raw;
+    if (n_in_ub * (int64_t)kvol >= ((int64_t)1 << 31) - 4096)
         return fail(SP_ERR_INVALID_ARG, "n * kernel volume exceeds 32-bit list offsets");
+    const Count cn_in{known ? nullptr : ptr<int32_t>(in->meta) + kMetaN, known ? in->n : 0};
 
     std::unique_ptr<sp_kmap, int (*)(sp_kmap*)> m(new sp_kmap, sp_kmap_destroy);
     m->K = kernel_size;
     m->kvol = kvol;
     m->stride = stride;
     m->dilation = dilation;
+    m->stream = s;
     sp_coords* cin = const_cast<sp_coords*>(in);
     cin->ref.fetch_add(1);
     m->c_in = cin;
+    Count cn_out = cn_in;
+    int64_t n_out_ub = n_in_ub;
     if (stride == 1) {
         cin->ref.fetch_add(1);
         m->c_out = cin;
     } else {
         sp_coords* co = nullptr;
-        SP_TRY(coords_build_impl(ptr<int32_t>(in->coords), in->n, in->ts * stride, in->ts * stride, s, &co));
+        SP_TRY(coords_build_impl(ptr<int32_t>(in->coords), n_in_ub, cn_in.d, in->ts * stride, in->ts * stride, s, &co));
+        cin->ref.fetch_add(1);
+        co->src_of = cin;  // its inverse array has one entry per row of `in`
         m->c_out = co;
+        cn_out = co->resolved ? Count{nullptr, co->n} : Count{ptr<int32_t>(co->meta) + kMetaN, 0};
+        if (co->resolved) n_out_ub = co->n;
     }
-    const int64_t n_in = in->n, n_out = m->c_out->n;
-    m->n_in = n_in;
-    m->n_out = n_out;
     const bool symmetric = (stride == 1) && (kernel_size & 1);
-    const int64_t nt_out = (n_out + kTileRows - 1) / kTileRows, nt_in = (n_in + kTileRows - 1) / kTileRows;
+    const int64_t nt_out = (n_out_ub + kTileRows - 1) / kTileRows, nt_in = (n_in_ub + kTileRows - 1) / kTileRows;
     const int step = dilation * in->ts;
+    const int nclass = (stride > 1 && stride * stride * stride <= 32) ? stride * stride * stride : 0;
 
     MapSide& so = m->out_side;
-    so.n_rows = n_out;
-    so.n_src = n_in;
-    so.nbr = dev_alloc((size_t)(n_out ? n_out : 1) * kvol * 4, s);
-    so.tl_off = dev_alloc((size_t)(nt_out * kvol * kSubTiles * kHalves + 1) * 4, s);
-    Buf blk = dev_alloc((size_t)(nt_out * kvol + 1) * 4, s);
-    Buf small = dev_alloc((size_t)(kvol + 2) * 4, s);  // [0..kvol] koff, [kvol+1] scratch total
-    if (!so.nbr || !so.tl_off || !blk || !small) return SP_ERR_ALLOC;
     MapSide& si = m->in_side;
+    so.nbr = dev_alloc((size_t)(n_out_ub ? n_out_ub : 1) * kvol * 4, s);
+    so.tl_off = dev_alloc((size_t)(nt_out * kvol * kSubTiles * kHalves + 1) * 4, s);
+    Work wk;
+    SP_TRY(make_work(wk, nt_out, nt_in, kvol, nclass, !symmetric, s));
+    if (!so.nbr || !so.tl_off) return SP_ERR_ALLOC;
     if (!symmetric) {
-        si.n_rows = n_in;
-        si.n_src = n_out;
-        si.nbr = dev_alloc((size_t)(n_in ? n_in : 1) * kvol * 4, s);
+        si.nbr = dev_alloc((size_t)(n_in_ub ? n_in_ub : 1) * kvol * 4, s);
         si.tl_off = dev_alloc((size_t)(nt_in * kvol * kSubTiles * kHalves + 1) * 4, s);
         if (!si.nbr || !si.tl_off) return SP_ERR_ALLOC;
-        if (n_in > 0)
-            hipLaunchKernelGGL(fill_i32_kernel, dim3(blocks256(n_in * kvol)), dim3(256), 0, s, ptr<int32_t>(si.nbr),
-                               n_in * kvol, -1);
     }
     const bool children = stride > 1 && kernel_size == stride && kernel_size % 2 == 0;
+    const int identity_k = symmetric ? (kvol - 1) / 2 : -1;
+    // one reset launch: "no link" where the searches will not write, zeros in the bookkeeping words
+    {
+        NegRegion ra{nullptr, cn_out, 0, kvol}, rb{nullptr, cn_in, 0, kvol};
+        int64_t cover = 0;
+        if (symmetric && kvol > 1) {
+            ra = NegRegion{ptr<int32_t>(so.nbr), cn_out, identity_k + 1, kvol};
+            cover = std::max(cover, n_out_ub * (int64_t)(kvol - 1 - identity_k));
+        }
+        if (!symmetric) {
+            rb = NegRegion{ptr<int32_t>(si.nbr), cn_in, 0, kvol};
+            cover = std::max(cover, n_in_ub * (int64_t)kvol);
+            if (children) {
+                ra = NegRegion{ptr<int32_t>(so.nbr), cn_out, 0, kvol};
+                cover = std::max(cover, n_out_ub * (int64_t)kvol);
+            }
+        }
+        if (cover > 0) hipLaunchKernelGGL(reset_kernel, dim3(blocks256(cover)), dim3(256), 0, s, ra, rb);
+    }
     if (nt_out > 0 && children) {
-        hipLaunchKernelGGL(fill_i32_kernel, dim3(blocks256(n_out * (int64_t)kvol)), dim3(256), 0, s, ptr<int32_t>(so.nbr),
-                           n_out * (int64_t)kvol, -1);
-        hipLaunchKernelGGL(child_map_kernel, dim3(blocks256(n_in)), dim3(kThreads), 0, s, ptr<int4>(in->coords), n_in,
-                           in->ts, stride, ptr<int32_t>(m->c_out->inverse), n_out, ptr<int32_t>(so.nbr),
-                           ptr<int32_t>(si.nbr));
-        hipLaunchKernelGGL(count_kernel, dim3((unsigned)nt_out, kvol), dim3(kThreads), 0, s, ptr<int32_t>(so.nbr), n_out,
-                           ptr<int32_t>(so.tl_off), ptr<int32_t>(blk));
+        hipLaunchKernelGGL(child_map_kernel, dim3(blocks256(n_in_ub)), dim3(kThreads), 0, s, ptr<int4>(in->coords), cn_in,
+                           in->ts, stride, ptr<int32_t>(m->c_out->inverse), cn_out, ptr<int32_t>(so.nbr), ptr<int32_t>(si.nbr));
     } else if (nt_out > 0) {
-        const int identity_k = symmetric ? (kvol - 1) / 2 : -1;
-        // mirrored table: only the (ax, ay) pairs that hold an offset up to the centre are launched, and the
-        // entries above the centre start as "no link"
+        // mirrored table: only the (ax, ay) pairs that hold an offset up to the centre are launched
         const int pairs_xy = symmetric ? identity_k / kernel_size + 1 : kernel_size * kernel_size;
         const dim3 grid((unsigned)nt_out, (unsigned)pairs_xy);
-        if (symmetric && kvol > 1)
-            hipLaunchKernelGGL(fill_i32_kernel, dim3(blocks256(n_out * (int64_t)(kvol - 1 - identity_k))), dim3(256), 0, s,
-                               ptr<int32_t>(so.nbr) + (int64_t)(identity_k + 1) * n_out,
-                               n_out * (int64_t)(kvol - 1 - identity_k), -1);
         int32_t* nbr_in_arg = symmetric ? (int32_t*)nullptr : ptr<int32_t>(si.nbr);
-        int32_t* sub_arg = symmetric ? (int32_t*)nullptr : ptr<int32_t>(so.tl_off);
-#define SP_LAUNCH_PROBE(KS)                                                                                     \
-    hipLaunchKernelGGL(probe_kernel<KS>, grid, dim3(kThreads), 0, s, ptr<int4>(m->c_out->coords), n_out,          \
-                       ptr<HashSlot>(in->tab.slots), in->tab.cap, in->tab.zshift, step, identity_k, ptr<int32_t>(so.nbr), nbr_in_arg, \
-                       n_in, sub_arg, ptr<int32_t>(blk))
+#define SP_LAUNCH_PROBE(KS)                                                                                          \
+    hipLaunchKernelGGL(probe_kernel<KS>, grid, dim3(kThreads), 0, s, ptr<int4>(m->c_out->coords), cn_out,              \
+                       ptr<HashSlot>(in->tab.slots), in->tab.cap, in->tab.zshift, step, identity_k, ptr<int32_t>(so.nbr), \
+                       nbr_in_arg, cn_in)
         switch (kernel_size) {
             case 1: SP_LAUNCH_PROBE(1); break;
             case 2: SP_LAUNCH_PROBE(2); break;
@@ -511,12 +773,9 @@ int sp_kmap_build(const sp_coords_t* in, int32_t kernel_size, int32_t stride, in
             default: SP_LAUNCH_PROBE(5); break;
         }
 #undef SP_LAUNCH_PROBE
-        if (symmetric)
-            hipLaunchKernelGGL(count_kernel, dim3((unsigned)nt_out, kvol), dim3(kThreads), 0, s, ptr<int32_t>(so.nbr),
-                               n_out, ptr<int32_t>(so.tl_off), ptr<int32_t>(blk));
     }
     SP_HIP(hipGetLastError());
-    SP_TRY(finish_map(m.get(), symmetric, blk, small, s));
+    SP_TRY(finish_map(m.get(), symmetric, wk, n_in_ub, n_out_ub, cn_in, cn_out, nclass, s));
     if (out_coords) {
         m->c_out->ref.fetch_add(1);
         *out_coords = m->c_out;
@@ -536,6 +795,7 @@ int sp_kmap_build_generative(const sp_coords_t* in, int32_t kernel_size, int32_t
         return fail(SP_ERR_INVALID_ARG, "the tensor stride (%d) must be a multiple of the layer stride (%d)", in->ts, stride);
     hipStream_t s = (hipStream_t)stream;
     const int kvol = kernel_size * kernel_size * kernel_size;
+    SP_TRY(coords_resolve(in));  // the candidate count sizes everything
     const int64_t n_coarse = in->n, n_cand = n_coarse * kvol;
     if (n_cand >= ((int64_t)1 << 30)) return fail(SP_ERR_INVALID_ARG, "n * kernel volume exceeds 2^30 candidates");
     const int ts_out = in->ts / stride;
@@ -548,7 +808,7 @@ int sp_kmap_build_generative(const sp_coords_t* in, int32_t kernel_size, int32_t
                            n_coarse, kernel_size, ts_out, ptr<int4>(cand));
     SP_HIP(hipGetLastError());
     sp_coords* fine = nullptr;
-    SP_TRY(coords_build_impl(ptr<int32_t>(cand), n_cand, 1, ts_out, s, &fine));
+    SP_TRY(coords_build_impl(ptr<int32_t>(cand), n_cand, nullptr, 1, ts_out, s, &fine));
 
     // the stride-s convolution's map from the fine rows (inputs) to the coarse rows (outputs) ...
     std::unique_ptr<sp_kmap, int (*)(sp_kmap*)> m(new sp_kmap, sp_kmap_destroy);
@@ -556,39 +816,37 @@ int sp_kmap_build_generative(const sp_coords_t* in, int32_t kernel_size, int32_t
     m->kvol = kvol;
     m->stride = stride;
     m->dilation = 1;
+    m->stream = s;
     m->c_in = fine;  // takes over the reference
     sp_coords* coarse = const_cast<sp_coords*>(in);
     coarse->ref.fetch_add(1);
     m->c_out = coarse;
+    SP_TRY(coords_resolve(fine));  // the created rows' count: the lists are sized from it, not from the candidates
     const int64_t n_fine = fine->n;
-    m->n_in = n_fine;
-    m->n_out = n_coarse;
+    const Count cn_fine{nullptr, n_fine}, cn_coarse{nullptr, n_coarse};
     if (n_fine * (int64_t)kvol >= ((int64_t)1 << 31) - 4096)
         return fail(SP_ERR_INVALID_ARG, "n * kernel volume exceeds 32-bit list offsets");
     const int64_t nt_out = (n_coarse + kTileRows - 1) / kTileRows, nt_in = (n_fine + kTileRows - 1) / kTileRows;
+    const int nclass = (stride > 1 && stride * stride * stride <= 32) ? stride * stride * stride : 0;
     MapSide& so = m->out_side;
     MapSide& si = m->in_side;
-    so.n_rows = n_coarse;
-    so.n_src = n_fine;
-    si.n_rows = n_fine;
-    si.n_src = n_coarse;
     so.nbr = dev_alloc((size_t)(n_cand ? n_cand : 1) * 4, s);
     so.tl_off = dev_alloc((size_t)(nt_out * kvol * kSubTiles * kHalves + 1) * 4, s);
     si.nbr = dev_alloc((size_t)(n_fine ? n_fine : 1) * kvol * 4, s);
     si.tl_off = dev_alloc((size_t)(nt_in * kvol * kSubTiles * kHalves + 1) * 4, s);
-    Buf blk = dev_alloc((size_t)(nt_out * kvol + 1) * 4, s);
-    Buf small = dev_alloc((size_t)(kvol + 2) * 4, s);
-    if (!so.nbr || !so.tl_off || !si.nbr || !si.tl_off || !blk || !small) return SP_ERR_ALLOC;
-    if (n_cand > 0) {
-        hipLaunchKernelGGL(fill_i32_kernel, dim3(blocks256(n_fine * kvol)), dim3(256), 0, s, ptr<int32_t>(si.nbr),
-                           n_fine * kvol, -1);
-        hipLaunchKernelGGL(gen_tables_kernel, dim3(blocks256(n_cand)), dim3(kThreads), 0, s, ptr<int32_t>(fine->inverse),
-                           n_coarse, n_fine, kvol, ptr<int32_t>(so.nbr), ptr<int32_t>(si.nbr));
-        hipLaunchKernelGGL(count_kernel, dim3((unsigned)nt_out, kvol), dim3(kThreads), 0, s, ptr<int32_t>(so.nbr), n_coarse,
-                           ptr<int32_t>(so.tl_off), ptr<int32_t>(blk));
+    Work wk;
+    SP_TRY(make_work(wk, nt_out, nt_in, kvol, nclass, true, s));
+    if (!so.nbr || !so.tl_off || !si.nbr || !si.tl_off) return SP_ERR_ALLOC;
+    {
+        NegRegion ra{nullptr, cn_coarse, 0, kvol}, rb{ptr<int32_t>(si.nbr), cn_fine, 0, kvol};
+        const int64_t cover = n_fine * (int64_t)kvol;
+        if (cover > 0) hipLaunchKernelGGL(reset_kernel, dim3(blocks256(cover)), dim3(256), 0, s, ra, rb);
     }
+    if (n_cand > 0)
+        hipLaunchKernelGGL(gen_tables_kernel, dim3(blocks256(n_cand)), dim3(kThreads), 0, s, ptr<int32_t>(fine->inverse),
+                           n_coarse, cn_fine, kvol, ptr<int32_t>(so.nbr), ptr<int32_t>(si.nbr));
     SP_HIP(hipGetLastError());
-    SP_TRY(finish_map(m.get(), false, blk, small, s));
+    SP_TRY(finish_map(m.get(), false, wk, n_fine, n_coarse, cn_fine, cn_coarse, nclass, s));
     // ... handed out with the roles swapped: inputs = the given (coarse) rows, outputs = the created rows
     sp_kmap_t* t = nullptr;
     SP_TRY(sp_kmap_transpose(m.get(), &t));
@@ -603,6 +861,7 @@ int sp_kmap_build_generative(const sp_coords_t* in, int32_t kernel_size, int32_t
 int sp_kmap_transpose(const sp_kmap_t* f, sp_kmap_t** transposed) {
     if (transposed) *transposed = nullptr;
     if (!f || !transposed) return fail(SP_ERR_INVALID_ARG, "kmap handle or out pointer is NULL");
+    SP_TRY(kmap_resolve(f));
     sp_kmap* t = new sp_kmap;
     t->n_in = f->n_out;
     t->n_out = f->n_in;
@@ -615,11 +874,15 @@ int sp_kmap_transpose(const sp_kmap_t* f, sp_kmap_t** transposed) {
     t->in_side = f->out_side;
     t->pair_in = f->pair_out;
     t->pair_out = f->pair_in;
+    t->pair_stride = f->pair_stride;
     t->counts = f->counts;
     t->koff = f->koff;
     t->d_koff = f->d_koff;
     t->c_in = f->c_out;
     t->c_out = f->c_in;
+    t->stream = f->stream;
+    t->resolved = true;
+    t->status = SP_OK;
     if (t->c_in) t->c_in->ref.fetch_add(1);
     if (t->c_out) t->c_out->ref.fetch_add(1);
     *transposed = t;
@@ -629,19 +892,21 @@ int sp_kmap_transpose(const sp_kmap_t* f, sp_kmap_t** transposed) {
 int sp_kmap_info(const sp_kmap_t* m, int64_t* n_in, int64_t* n_out, int32_t* kvol, int64_t* total_pairs,
                  int64_t* h_counts) {
     if (!m) return fail(SP_ERR_INVALID_ARG, "kmap handle is NULL");
+    if (kvol) *kvol = m->kvol;
+    if (n_in || n_out || total_pairs || h_counts) SP_TRY(kmap_resolve(m));
     if (n_in) *n_in = m->n_in;
     if (n_out) *n_out = m->n_out;
-    if (kvol) *kvol = m->kvol;
     if (total_pairs) *total_pairs = m->total;
     if (h_counts)
         for (int k = 0; k < m->kvol; ++k) h_counts[k] = m->counts[k];
     return SP_OK;
 }
 
-int sp_kmap_pairs(const sp_kmap_t* m, const int32_t** d_pair_in, const int32_t** d_pair_out) {
+int sp_kmap_pairs(const sp_kmap_t* m, const int32_t** d_pair_in, const int32_t** d_pair_out, int64_t* pair_stride) {
     if (!m) return fail(SP_ERR_INVALID_ARG, "kmap handle is NULL");
     if (d_pair_in) *d_pair_in = ptr<int32_t>(m->pair_in);
     if (d_pair_out) *d_pair_out = ptr<int32_t>(m->pair_out);
+    if (pair_stride) *pair_stride = m->pair_stride;
     return SP_OK;
 }
 

@@ -217,7 +217,9 @@ extern "C" {
 
 int sp_pool_fwd(const sp_kmap_t* m, const void* d_x, void* d_y, uint8_t* d_arg, int32_t c, sp_pool_mode mode, sp_dtype dt,
                 void* stream) {
-    SP_TRY(check_pool_args(m, d_x, m ? m->n_in : 0, d_y, m ? m->n_out : 0, c, mode, dt));
+    if (!m) return fail(SP_ERR_INVALID_ARG, "kmap handle is NULL");
+    SP_TRY(kmap_resolve(m));
+    SP_TRY(check_pool_args(m, d_x, m->n_in, d_y, m->n_out, c, mode, dt));
     hipStream_t s = (hipStream_t)stream;
     const MapSide& side = m->out_side;
     if (vector_ok(d_x, d_y, c, dt))
@@ -229,7 +231,9 @@ int sp_pool_fwd(const sp_kmap_t* m, const void* d_x, void* d_y, uint8_t* d_arg, 
 
 int sp_pool_bwd(const sp_kmap_t* m, const void* d_dy, const uint8_t* d_arg, void* d_dx, int32_t c, sp_pool_mode mode,
                 sp_dtype dt, void* stream) {
-    SP_TRY(check_pool_args(m, d_dy, m ? m->n_out : 0, d_dx, m ? m->n_in : 0, c, mode, dt));
+    if (!m) return fail(SP_ERR_INVALID_ARG, "kmap handle is NULL");
+    SP_TRY(kmap_resolve(m));
+    SP_TRY(check_pool_args(m, d_dy, m->n_out, d_dx, m->n_in, c, mode, dt));
     if (mode == SP_POOL_MAX && !d_arg && m->n_out > 0) return fail(SP_ERR_INVALID_ARG, "max pooling backward needs d_arg");
     hipStream_t s = (hipStream_t)stream;
     const MapSide& side = m->in_side;

@@ -253,6 +253,81 @@ __global__ __launch_bounds__(256) void mailbox_kernel(const uint32_t* __restrict
 }
 }  // namespace
 
+
+// ---- mail slots: small results that a build's last kernel writes straight into pinned host memory ----------------
+// The builds do not wait for their row and pair counts: the kernel that computes them writes them into a slot of
+// coherent pinned host memory (payload first, then a sequence word with system-scope release), and the host
+// reads the slot only when somebody asks for the numbers (mail_wait polls the sequence word).
+namespace {
+struct MailPool {
+    std::mutex mu;
+    uint32_t* h = nullptr;  // kMailSlots slots of kMailSlotWords words, as the host sees them
+    uint32_t* d = nullptr;  // the same memory as the device sees it
+    std::vector<int> free_slots;
+    uint32_t next_seq = 1;
+    bool tried = false;
+};
+MailPool& mail_pool() {
+    static MailPool* m = new MailPool;
+    return *m;
+}
+}  // namespace
+
+bool mail_acquire(MailSlot* out) {
+    MailPool& mp = mail_pool();
+    std::lock_guard<std::mutex> lk(mp.mu);
+    if (!mp.tried) {
+        mp.tried = true;
+        void* h = nullptr;
+        const size_t bytes = (size_t)kMailSlots * kMailSlotWords * 4;
+        if (hipHostMalloc(&h, bytes, hipHostMallocMapped | hipHostMallocCoherent) == hipSuccess) {
+            void* d = nullptr;
+            if (hipHostGetDevicePointer(&d, h, 0) == hipSuccess) {
+                memset(h, 0, bytes);
+                mp.h = static_cast<uint32_t*>(h);
+                mp.d = static_cast<uint32_t*>(d);
+                for (int i = kMailSlots - 1; i >= 0; --i) mp.free_slots.push_back(i);
+            } else {
+                (void)hipHostFree(h);
+            }
+        }
+        (void)hipGetLastError();
+    }
+    if (!mp.h || mp.free_slots.empty()) return false;
+    const int i = mp.free_slots.back();
+    mp.free_slots.pop_back();
+    out->index = i;
+    out->h = mp.h + (size_t)i * kMailSlotWords;
+    out->d = mp.d + (size_t)i * kMailSlotWords;
+    out->seq = mp.next_seq++;
+    if (mp.next_seq == 0) mp.next_seq = 1;
+    return true;
+}
+
+void mail_release(MailSlot* slot) {
+    if (slot->index < 0) return;
+    MailPool& mp = mail_pool();
+    std::lock_guard<std::mutex> lk(mp.mu);
+    mp.free_slots.push_back(slot->index);
+    slot->index = -1;
+}
+
+int mail_wait(const MailSlot& slot, hipStream_t s) {
+    volatile uint32_t* flag = slot.h + kMailSeqWord;
+    // poll; every ~50 us of silence ask the runtime whether the stream has failed or finished
+    for (uint64_t spins = 0;; ++spins) {
+        if (__atomic_load_n(flag, __ATOMIC_ACQUIRE) == slot.seq) return SP_OK;
+        if ((spins & 0x3fff) == 0x3fff) {
+            const hipError_t q = hipStreamQuery(s);
+            if (q == hipSuccess) {  // everything enqueued has run: the stores are visible by now
+                if (__atomic_load_n(flag, __ATOMIC_ACQUIRE) == slot.seq) return SP_OK;
+                return fail(SP_ERR_HIP, "a build finished without delivering its counts");
+            }
+            if (q != hipErrorNotReady) return fail(SP_ERR_HIP, "hipStreamQuery: %s", hipGetErrorString(q));
+        }
+    }
+}
+
 int read_back(void* h_dst, const void* d_src, size_t bytes, hipStream_t s, const std::function<void()>& then_enqueue) {
     if (bytes == 0) {
         if (then_enqueue) then_enqueue();

@@ -39,12 +39,13 @@ __device__ __forceinline__ float load_f32(const bf16_t* p) { return __uint_as_fl
 // not a multiple of C): every chunk start and every such stretch start begins exactly one piece.
 struct PlanArgs {
     int kvol, S8, nc, C, tiles;
+    int pair_stride;      // offset k's pairs start at k * pair_stride in the pair arrays
     int slots_per_strip;  // nc + kvol: more than the largest piece number of a strip
     int32_t koff[130];    // exclusive prefix of the offsets' link counts
 };
 // stretch of offset k in strip s: links [lo, lo + len), lo = koff[k] + floor(cnt * s / S8) in 32-bit steps
 __device__ __forceinline__ void strip_stretch(const PlanArgs& pa, int k, int s, int* lo, int* len) {
-    const uint32_t k0 = (uint32_t)pa.koff[k], cnt = (uint32_t)pa.koff[k + 1] - k0, n = (uint32_t)pa.S8;
+    const uint32_t k0 = (uint32_t)k * (uint32_t)pa.pair_stride, cnt = (uint32_t)(pa.koff[k + 1] - pa.koff[k]), n = (uint32_t)pa.S8;
     const uint32_t q = cnt / n, r = cnt % n;  // r * s < 2^20
     const uint32_t b0 = q * (uint32_t)s + r * (uint32_t)s / n, b1 = q * (uint32_t)(s + 1) + r * (uint32_t)(s + 1) / n;
     *lo = (int)(k0 + b0);
@@ -475,15 +476,16 @@ __global__ __launch_bounds__(64 * WCO * WCI * WK) void wgrad_staged_kernel(Stage
 template <typename T>
 __global__ __launch_bounds__(256) void wgrad_plain_kernel(const int32_t* __restrict__ pair_in,
                                                           const int32_t* __restrict__ pair_out,
-                                                          const int32_t* __restrict__ koff, const T* __restrict__ X,
-                                                          const T* __restrict__ dY, int cin, int cout,
-                                                          float* __restrict__ dw) {
+                                                          const int32_t* __restrict__ koff, int64_t pair_stride,
+                                                          const T* __restrict__ X, const T* __restrict__ dY, int cin,
+                                                          int cout, float* __restrict__ dw) {
     const int k = blockIdx.y;
     const int e = blockIdx.x * 256 + threadIdx.x;
     if (e >= cin * cout) return;
     const int co = e / cin, ci = e % cin;
     float s = 0.f;
-    for (int p = koff[k]; p < koff[k + 1]; ++p)
+    const int64_t p0 = (int64_t)k * pair_stride;
+    for (int64_t p = p0; p < p0 + (koff[k + 1] - koff[k]); ++p)
         s = fmaf(load_f32(dY + (size_t)pair_out[p] * cout + co), load_f32(X + (size_t)pair_in[p] * cin + ci), s);
     dw[(size_t)k * cin * cout + e] = s;
 }
@@ -512,6 +514,7 @@ int launch_staged(const sp_kmap* m, const void* x, const void* dy, int cin, int 
     StagedArgs a;
     PlanArgs& pa = a.plan;
     pa.kvol = kvol;
+    pa.pair_stride = (int)m->pair_stride;
     pa.tiles = (cout / COB) * (cin / CIB);
     for (int k = 0; k <= kvol; ++k) pa.koff[k] = (int32_t)m->koff[k];
     // Strips: about 1.5 MB of rows (both operands) each, but long enough that an offset's stretch in a strip
@@ -552,7 +555,7 @@ int launch_staged(const sp_kmap* m, const void* x, const void* dy, int cin, int 
     a.cout = cout;
     a.x_bytes = (uint32_t)((uint64_t)m->n_in * cin * sizeof(T));
     a.dy_bytes = (uint32_t)((uint64_t)m->n_out * cout * sizeof(T));
-    a.pair_bytes = (uint32_t)((uint64_t)m->total * 4);
+    a.pair_bytes = (uint32_t)((uint64_t)kvol * m->pair_stride * 4);
     hipLaunchKernelGGL(wgrad_plan_kernel, dim3(pa.S8), dim3(64), 0, s, pa, d_lo, d_len, d_first, d_count,
                        d_cstart);
     const int64_t wgs = (int64_t)pa.S8 * nc * pa.tiles;
@@ -575,10 +578,10 @@ int wgrad_typed(const sp_kmap* m, const void* x, const void* dy, float* dw, int 
     const int kvol = m->kvol;
     const uint64_t lim = 0x7fffffffull;  // the staged kernel addresses its buffers with 32-bit offsets
     const bool small = (uint64_t)m->n_in * cin * sizeof(T) < lim && (uint64_t)m->n_out * cout * sizeof(T) < lim &&
-                       (uint64_t)m->total * 4 < lim;
+                       (uint64_t)kvol * m->pair_stride * 4 < lim;
     if (cin % 16 || cout % 16 || !small || m->total == 0 || kvol > 128) {
         hipLaunchKernelGGL(wgrad_plain_kernel<T>, dim3((cin * cout + 255) / 256, kvol), dim3(256), 0, s,
-                           ptr<int32_t>(m->pair_in), ptr<int32_t>(m->pair_out), ptr<int32_t>(m->d_koff),
+                           ptr<int32_t>(m->pair_in), ptr<int32_t>(m->pair_out), ptr<int32_t>(m->d_koff), m->pair_stride,
                            static_cast<const T*>(x), static_cast<const T*>(dy), cin, cout, dw);
         SP_HIP(hipGetLastError());
         return SP_OK;
@@ -623,6 +626,7 @@ extern "C" int sp_conv_bwd_weight(const sp_kmap_t* m, const void* d_x, const voi
                                   int32_t cout, sp_dtype dt, void* stream) {
     using namespace sp;
     if (!m) return fail(SP_ERR_INVALID_ARG, "kmap handle is NULL");
+    SP_TRY(kmap_resolve(m));  // sizes of a map whose build has not reported yet
     if (cin < 1 || cout < 1 || cin > 4096 || cout > 4096) return fail(SP_ERR_INVALID_ARG, "bad channel count");
     if (dt != SP_F32 && dt != SP_BF16) return fail(SP_ERR_INVALID_ARG, "bad dtype");
     if ((!d_x && m->n_in > 0) || (!d_dy && m->n_out > 0) || !d_dw)

@@ -53,8 +53,8 @@ def test_coords_build_matches_oracle(sp, name, raw):
 
 
 def test_coords_build_more_than_4M_rows_few_distinct(sp):
-    """4.5 M raw rows drawn from ~50 k distinct coordinates: more than 4096 numbering blocks, so the block counts
-    are scanned by an extra launch instead of every block adding up its predecessors."""
+    """4.5 M raw rows drawn from ~50 k distinct coordinates: 4395 numbering blocks, i.e. look-back chains that
+    span dozens of 64-block windows."""
     rng = np.random.default_rng(21)
     distinct = random_coords(22, 50000, 60, batches=4, lo=-30)
     raw = distinct[rng.integers(0, len(distinct), 4_500_000)]
@@ -63,28 +63,6 @@ def test_coords_build_more_than_4M_rows_few_distinct(sp):
     assert c.n == len(want_c)
     assert np.array_equal(c.coords().cpu().numpy(), want_c)
     assert np.array_equal(c.inverse().cpu().numpy(), want_inv)
-
-
-def test_map_build_with_scanned_block_sums(sp):
-    """The scans' "too many blocks for every block to add up its predecessors" path, forced on a small input
-    through the library's test hook, against the oracle's pair lists."""
-    import ctypes
-    hook = sp.lib().sp_debug_scan_self_base_max
-    hook.restype, hook.argtypes = ctypes.c_int64, [ctypes.c_int64]
-    old = hook(1)
-    try:
-        for K, stride in ((3, 1), (3, 2), (2, 2)):
-            raw = spgen.coords_config(1, 0.5)
-            want = oracle_steps(raw, K, stride, 1, 1)
-            c = sp.sp_coords_build(dev(raw), 1)
-            km, co = sp.sp_kmap_build(c, K, stride, 1)
-            assert np.array_equal(co.coords().cpu().numpy(), want["c_out"])
-            check_map(sp, km, want, len(want["c_in"]), len(want["c_out"]))
-            kt = sp.sp_kmap_transpose(km)
-            tin, tout, tcounts = oracle.transpose_map(want["pair_in"], want["pair_out"], want["counts"])
-            check_map(sp, kt, dict(pair_in=tin, pair_out=tout, counts=tcounts), len(want["c_out"]), len(want["c_in"]))
-    finally:
-        hook(old)
 
 
 def test_coords_build_empty(sp):
@@ -101,8 +79,14 @@ def test_coords_build_empty(sp):
 
 def test_coords_out_of_range_is_an_error(sp):
     for bad in ([[0, 40000, 0, 0]], [[70000, 0, 0, 0]], [[-1, 0, 0, 0]], [[0, 0, 0, -32769]]):
+        c = sp.sp_coords_build(dev(np.array(bad, np.int32)), 1)      # found on the device ...
         with pytest.raises(sp.SpError) as e:
-            sp.sp_coords_build(dev(np.array(bad, np.int32)), 1)
+            c.n                                                      # ... reported when the count is asked for
+        assert e.value.code == -2
+        c = sp.sp_coords_build(dev(np.array(bad, np.int32)), 1)
+        km, _ = sp.sp_kmap_build(c, 3, 1, 1)                         # a map built on it reports it as well
+        with pytest.raises(sp.SpError) as e:
+            km.n_in
         assert e.value.code == -2
 
 
