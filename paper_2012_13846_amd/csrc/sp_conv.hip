@@ -191,8 +191,8 @@ __global__ __launch_bounds__(256) void gather_mma_kernel(GatherArgs a) {
 //  - The wavefront first cuts its links into blocks of up to 16 links of one offset and writes one packed
 //    descriptor per block into LDS, so that block b+n is addressable without walking a cursor.
 //  - Everything a block needs is requested well ahead of its use and kept in registers: link entries
-//    (source row, destination row) 2*kDepth blocks ahead, the gathered source rows kDepth blocks ahead,
-//    the next offset's weight matrix while the current one is in use.
+//    (source row, destination row) 2*kDX blocks ahead, the gathered source rows kDX blocks ahead (6 for
+//    rows of up to 128 bytes, else 3), the weight matrix two blocks ahead.
 //  - Source rows are gathered with coalesced 16-byte loads (adjacent lanes = adjacent pieces of one row; a
 //    fragment-shaped global load would cost one L1 tag lookup per lane) and pass through a small
 //    wavefront-private LDS buffer to be re-read as MFMA fragments, one block ahead of the MFMAs using them.
@@ -235,7 +235,13 @@ __global__ __launch_bounds__(64) void gather_wave_kernel(GatherArgs a) {
     using Frag = typename std::conditional<kIsF32, f32x4, bf16x8>::type;  // 16 bytes
     static_assert(CC % Cfg::kGroup == 0, "contraction channels must fill whole fragment groups");
     static_assert(kPieces % 4 == 0, "a source row must be a multiple of 64 bytes");
-    constexpr int kDepth = 3;  // blocks whose gathers are in flight
+    // Blocks whose gathers are in flight, and blocks whose weights are.  A gather is two dependent trips to
+    // memory behind the entry loads and mostly misses the L2; the weights are one trip that mostly hits.  Rows
+    // cost few registers per block and weights many, so narrow rows are fetched deep and weights shallow.
+    constexpr int kDX = 3;  // loads return in order: a deeper ring for the rows alone would still wait for the weights issued after it
+    constexpr int kDW = 2;
+    constexpr int kTurn = 6;  // bodies per loop turn: a multiple of kDX, kDW and the two result sets
+    static_assert(kTurn % kDX == 0 && kTurn % kDW == 0 && kTurn % 2 == 0, "ring sizes must divide the turn");
 
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x & 63;
@@ -322,15 +328,19 @@ __global__ __launch_bounds__(64) void gather_wave_kernel(GatherArgs a) {
     // clamped to the last one and their results dropped): the compiler can then count outstanding loads
     // exactly and wait only for the oldest, instead of draining the whole prefetch queue at every branch.
     struct Slot {
-        int dc;                   // descriptor of the block whose gathered rows / weights are in x / w
+        int dc;                   // descriptor of the block whose gathered rows are in x
         int drow;                 // destination row of that block's link n16
         int de;                   // descriptor of the block whose entries are in esrc / erow
         int esrc[kXLoads];        // source row of the link this lane gathers a piece of, per load
         int erow;                 // destination row of link n16
         u32x4 x[kXLoads];         // gathered pieces, coalesced layout: piece (t*64 + lane) of the block
-        Frag w[kNCT][kGroups];    // the block's weight matrix
+    };
+    struct WSlot {
+        Frag w[kNCT][kGroups];    // a block's weight matrix
     };
     const int last = nblk - 1;
+    // (Starting each wavefront at a block of its own, so that the wavefronts of a compute unit do not ask for
+    // the same weight lines at the same moment, was measured and is slower: in step, they share the lines in L1.)
     auto load_entries = [&](Slot& sl, int b) __attribute__((always_inline)) {
         sl.de = s_blk[min(b, last)];
         const int cnt = ((sl.de >> 7) & 15) + 1, e0 = off0 + (sl.de >> 13);
@@ -345,7 +355,9 @@ __global__ __launch_bounds__(64) void gather_wave_kernel(GatherArgs a) {
 #pragma unroll
         for (int t = 0; t < kXLoads; ++t)
             sl.x[t] = __builtin_amdgcn_raw_buffer_load_b128(rF, sl.esrc[t] * Cfg::kRowBytes + ((t * 64 + lane) % kPieces) * 16, 0, 0);
-        load_weights(sl.dc & 127, sl.w);
+    };
+    auto issue_weights = [&](WSlot& ws, int b) __attribute__((always_inline)) {
+        load_weights(s_blk[min(b, last)] & 127, ws.w);
     };
     auto stage = [&](const Slot& sl) __attribute__((always_inline)) {  // gathered rows -> LDS, row-major, padded
 #pragma unroll
@@ -360,20 +372,19 @@ __global__ __launch_bounds__(64) void gather_wave_kernel(GatherArgs a) {
             xf[s] = *reinterpret_cast<const Frag*>(xbuf + n16 * Cfg::kXStride + s * 64 + g * 16);
     };
 
-    static_assert(kDepth == 3, "three named slots");
     if (nblk > 0) {
-        Slot slot0 = {}, slot1 = {}, slot2 = {};
-        load_entries(slot0, 0);
-        load_entries(slot1, 1);
-        load_entries(slot2, 2);
-        issue_gather(slot0);
-        issue_gather(slot1);
-        issue_gather(slot2);
-        load_entries(slot0, 3);
-        load_entries(slot1, 4);
-        load_entries(slot2, 5);
+        Slot xs[kDX] = {};
+        WSlot ws[kDW] = {};
+#pragma unroll
+        for (int j = 0; j < kDX; ++j) load_entries(xs[j], j);
+#pragma unroll
+        for (int j = 0; j < kDW; ++j) issue_weights(ws[j], j);
+#pragma unroll
+        for (int j = 0; j < kDX; ++j) issue_gather(xs[j]);
+#pragma unroll
+        for (int j = 0; j < kDX; ++j) load_entries(xs[j], kDX + j);
         Frag xf_c[kGroups];
-        stage(slot0);
+        stage(xs[0]);
         wave_sync();
         read_frags(xf_c);
         wave_sync();
@@ -381,16 +392,16 @@ __global__ __launch_bounds__(64) void gather_wave_kernel(GatherArgs a) {
         // One block: sl holds block b, sn holds block b + 1.  A wavefront issues in order, so the block's
         // MFMAs only overlap with its other work if that work does not depend on them and is interleaved
         // with them: the accumulator update of block b-1, the staging of block b+1 and the loads for
-        // blocks b+3 / b+6 are therefore issued between the MFMAs of block b.
-        // Three result sets rotate with the three slots, so a block's products stay where the MFMAs left
-        // them until the next block's turn adds them to the accumulator.
+        // later blocks are therefore issued between the MFMAs of block b.
+        // Two result sets alternate, so a block's products stay where the MFMAs left them until the next
+        // block's turn adds them to the accumulator.
         struct Result {
             f32x4 d[kNCT];  // d[ct][i] = channel ct*16 + 4*g + i of link n16 of the block
             float* dst;     // accumulator row of that link (+ 4*g)
             bool valid;     // this lane's link exists
         };
-        Result res0 = {}, res1 = {}, res2 = {};
-        res0.dst = res1.dst = res2.dst = acc + g * 4;
+        Result res[2] = {};
+        res[0].dst = res[1].dst = acc + g * 4;
         // the accumulator rows are read at the start of a turn and written back at its end, so the LDS
         // latency is paid once, under the turn's MFMAs
         auto flush_read = [&](const Result& r, f32x4 (&av)[kNCT]) __attribute__((always_inline)) {
@@ -403,7 +414,7 @@ __global__ __launch_bounds__(64) void gather_wave_kernel(GatherArgs a) {
                 for (int ct = 0; ct < kNCT; ++ct) *reinterpret_cast<f32x4*>(r.dst + ct * 16) = av[ct] + r.d[ct];
             }
         };
-        auto body = [&](int b, Slot& sl, const Slot& sn, Result& cur, const Result& prev) __attribute__((always_inline)) {
+        auto body = [&](int b, Slot& sl, const Slot& sn, WSlot& wl, Result& cur, const Result& prev) __attribute__((always_inline)) {
             const int cnt = ((sl.dc >> 7) & 15) + 1;
             cur.valid = n16 < cnt;
             cur.dst = acc + sl.drow * Cfg::kStride + g * 4;
@@ -421,16 +432,17 @@ __global__ __launch_bounds__(64) void gather_wave_kernel(GatherArgs a) {
 #pragma unroll
                 for (int ct = 0; ct < kNCT; ++ct) {
                     if constexpr (kIsF32) {
-                        cur.d[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(sl.w[ct][s][0], xf_c[s][0], cur.d[ct], 0, 0, 0);
-                        cur.d[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(sl.w[ct][s][1], xf_c[s][1], cur.d[ct], 0, 0, 0);
-                        cur.d[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(sl.w[ct][s][2], xf_c[s][2], cur.d[ct], 0, 0, 0);
-                        cur.d[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(sl.w[ct][s][3], xf_c[s][3], cur.d[ct], 0, 0, 0);
+                        cur.d[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(wl.w[ct][s][0], xf_c[s][0], cur.d[ct], 0, 0, 0);
+                        cur.d[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(wl.w[ct][s][1], xf_c[s][1], cur.d[ct], 0, 0, 0);
+                        cur.d[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(wl.w[ct][s][2], xf_c[s][2], cur.d[ct], 0, 0, 0);
+                        cur.d[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(wl.w[ct][s][3], xf_c[s][3], cur.d[ct], 0, 0, 0);
                     } else {
-                        cur.d[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sl.w[ct][s], xf_c[s], cur.d[ct], 0, 0, 0);
+                        cur.d[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wl.w[ct][s], xf_c[s], cur.d[ct], 0, 0, 0);
                     }
                 }
-            issue_gather(sl);               // block b + kDepth: its entries arrived a turn ago
-            load_entries(sl, b + 2 * kDepth);
+            issue_gather(sl);               // block b + kDX: its entries arrived kDX turns ago
+            load_entries(sl, b + 2 * kDX);
+            issue_weights(wl, b + kDW);
             flush_write(prev, av);
 #pragma unroll
             for (int s = 0; s < kGroups; ++s) xf_c[s] = xf_n[s];
@@ -454,21 +466,20 @@ __global__ __launch_bounds__(64) void gather_wave_kernel(GatherArgs a) {
             }
         };
         int done = 0;  // number of blocks computed; the last one's result is still to be added
-        for (int b = 0; b < nblk; b += 3) {
-            body(b, slot0, slot1, res0, res2);
-            done = b + 1;
-            if (b + 1 >= nblk) break;
-            body(b + 1, slot1, slot2, res1, res0);
-            done = b + 2;
-            if (b + 2 >= nblk) break;
-            body(b + 2, slot2, slot0, res2, res1);
-            done = b + 3;
+        for (int b = 0; b < nblk; b += kTurn) {
+            bool stop = false;
+#pragma unroll
+            for (int j = 0; j < kTurn; ++j) {
+                if (!stop) {
+                    body(b + j, xs[j % kDX], xs[(j + 1) % kDX], ws[j % kDW], res[j % 2], res[(j + 1) % 2]);
+                    done = b + j + 1;
+                    stop = b + j + 1 >= nblk;
+                }
+            }
         }
-        const int last_set = (done + 2) % 3;  // set of block done-1
         f32x4 av[kNCT];
-        if (last_set == 0) { flush_read(res0, av); flush_write(res0, av); }
-        else if (last_set == 1) { flush_read(res1, av); flush_write(res1, av); }
-        else { flush_read(res2, av); flush_write(res2, av); }
+        if ((done + 1) % 2 == 0) { flush_read(res[0], av); flush_write(res[0], av); }  // the set of block done-1
+        else { flush_read(res[1], av); flush_write(res[1], av); }
     }
     wave_sync();
     const int co0 = blockIdx.y * COT;
