@@ -65,6 +65,31 @@ def test_coords_build_more_than_4M_rows_few_distinct(sp):
     assert np.array_equal(c.inverse().cpu().numpy(), want_inv)
 
 
+def test_more_unresolved_builds_than_mail_slots(sp):
+    """2048 builds may have their counts waiting in pinned host memory; the builds beyond that fall back to a
+    blocking read-back.  2200 handles are built before any count is asked for; all must be right, and the slots
+    must come back when the handles are destroyed."""
+    rng = np.random.default_rng(5)
+    raws = [rng.integers(0, 6, size=(int(rng.integers(1, 40)), 4)).astype(np.int32) for _ in range(2200)]
+    big = dev(np.concatenate(raws))
+    hs, at = [], 0
+    for r in raws:
+        hs.append(sp.sp_coords_build(big[at:at + len(r)], 1))
+        at += len(r)
+    for i in (0, 1, 2047, 2048, 2049, 2199, 1000):
+        want_c, want_inv = oracle.unique_coords(raws[i])
+        assert hs[i].n == len(want_c)
+        assert np.array_equal(hs[i].coords().cpu().numpy(), want_c)
+        assert np.array_equal(hs[i].inverse().cpu().numpy(), want_inv)
+    assert [h.n for h in hs] == [len(np.unique(r, axis=0)) for r in raws]
+    for h in hs:
+        h.close()
+    want = oracle_steps(raws[0], 3, 1, 1, 1)     # slots are free again: builds work as before
+    c = sp.sp_coords_build(dev(raws[0]), 1)
+    km, co = sp.sp_kmap_build(c, 3, 1, 1)
+    check_map(sp, km, want, len(want["c_in"]), len(want["c_out"]))
+
+
 def test_coords_build_empty(sp):
     c = sp.sp_coords_build(torch.empty((0, 4), dtype=torch.int32, device="cuda"), 1)
     assert c.n == 0
