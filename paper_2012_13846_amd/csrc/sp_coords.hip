@@ -215,6 +215,8 @@ int coords_build_impl(const int32_t* d_src, int64_t n_src, const int32_t* d_n_sr
     hipLaunchKernelGGL(number_kernel, dim3((unsigned)(nb ? nb : 1)), dim3(kThreads), 0, s, src, n_src, d_n_src, floor_step, tab,
                        ptr<int32_t>(slot_of), chain, meta, ptr<int4>(c->coords), mailed ? c->mail.d : (uint32_t*)nullptr,
                        c->mail.seq);
+    c->mail.armed = mailed;
+    c->mail.stream = s;
     if (n_src > 0)
         hipLaunchKernelGGL(inverse_kernel, dim3(blocks_for(n_src, kThreads)), dim3(kThreads), 0, s, tab, ptr<int32_t>(slot_of),
                            n_src, d_n_src, ptr<int32_t>(c->inverse));

@@ -70,8 +70,13 @@ struct MailSlot {
     uint32_t* h = nullptr;  // host view
     uint32_t* d = nullptr;  // device view of the same memory
     uint32_t seq = 0;       // the value the kernel writes to word kMailSeqWord when the payload is complete
+    bool armed = false;     // the kernel that will write the slot has been enqueued (on `stream`)
+    hipStream_t stream = nullptr;
 };
 bool mail_acquire(MailSlot* out);                  // false: none free (the caller then waits for its stream instead)
+// Gives the slot back.  A slot whose kernel is enqueued but has not delivered yet (a handle destroyed before its
+// counts were asked for) is parked and only reused once the delivery, or the end of its stream's work, is seen:
+// a late write must not land in a slot that another build already owns.
 void mail_release(MailSlot* slot);
 int mail_wait(const MailSlot& slot, hipStream_t s);  // blocks until the slot's payload has arrived
 

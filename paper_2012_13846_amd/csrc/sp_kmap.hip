@@ -570,6 +570,8 @@ int finish_map(sp_kmap* m, bool symmetric, Work& wk, int64_t n_in_ub, int64_t n_
     }
     const unsigned chunks = (unsigned)((kvol + kChunk - 1) / kChunk);
     hipLaunchKernelGGL(emit_kernel, dim3((unsigned)(nt_out ? nt_out : 1), chunks), dim3(kThreads), 0, s, a);
+    m->mail.armed = mailed;
+    m->mail.stream = s;
     if (symmetric) {
         si = so;  // same lists; the link (i, o) at offset k is the link (o, i) at offset kvol-1-k
         si.flip = true;

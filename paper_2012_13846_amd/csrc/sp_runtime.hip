@@ -264,6 +264,12 @@ struct MailPool {
     uint32_t* h = nullptr;  // kMailSlots slots of kMailSlotWords words, as the host sees them
     uint32_t* d = nullptr;  // the same memory as the device sees it
     std::vector<int> free_slots;
+    struct Parked {
+        int index;
+        uint32_t seq;
+        hipStream_t stream;
+    };
+    std::vector<Parked> parked;  // released before their kernel delivered
     uint32_t next_seq = 1;
     bool tried = false;
 };
@@ -293,13 +299,31 @@ bool mail_acquire(MailSlot* out) {
         }
         (void)hipGetLastError();
     }
-    if (!mp.h || mp.free_slots.empty()) return false;
+    if (!mp.h) return false;
+    if (!mp.parked.empty() && mp.free_slots.size() < 64) {  // look whether parked slots have been delivered meanwhile
+        size_t keep = 0;
+        for (size_t j = 0; j < mp.parked.size(); ++j) {
+            const MailPool::Parked& pk = mp.parked[j];
+            const uint32_t got = __atomic_load_n(mp.h + (size_t)pk.index * kMailSlotWords + kMailSeqWord, __ATOMIC_ACQUIRE);
+            bool done = got == pk.seq;
+            if (!done) {
+                done = hipStreamQuery(pk.stream) != hipErrorNotReady;  // nothing left that could still write it
+                (void)hipGetLastError();
+            }
+            if (done) mp.free_slots.push_back(pk.index);
+            else mp.parked[keep++] = pk;
+        }
+        mp.parked.resize(keep);
+    }
+    if (mp.free_slots.empty()) return false;
     const int i = mp.free_slots.back();
     mp.free_slots.pop_back();
     out->index = i;
     out->h = mp.h + (size_t)i * kMailSlotWords;
     out->d = mp.d + (size_t)i * kMailSlotWords;
     out->seq = mp.next_seq++;
+    out->armed = false;
+    out->stream = nullptr;
     if (mp.next_seq == 0) mp.next_seq = 1;
     return true;
 }
@@ -308,7 +332,9 @@ void mail_release(MailSlot* slot) {
     if (slot->index < 0) return;
     MailPool& mp = mail_pool();
     std::lock_guard<std::mutex> lk(mp.mu);
-    mp.free_slots.push_back(slot->index);
+    const bool delivered = __atomic_load_n(slot->h + kMailSeqWord, __ATOMIC_ACQUIRE) == slot->seq;
+    if (slot->armed && !delivered) mp.parked.push_back({slot->index, slot->seq, slot->stream});
+    else mp.free_slots.push_back(slot->index);
     slot->index = -1;
 }
 

@@ -84,6 +84,22 @@ def test_more_unresolved_builds_than_mail_slots(sp):
     assert [h.n for h in hs] == [len(np.unique(r, axis=0)) for r in raws]
     for h in hs:
         h.close()
+    # handles dropped before anybody asked for their counts: their slots are parked until the kernels have
+    # delivered, then reused; builds on another stream meanwhile must not see a late delivery
+    side = torch.cuda.Stream()
+    for rnd in range(3):
+        hs, at = [], 0
+        for r in raws[:900]:
+            hs.append(sp.sp_coords_build(big[at:at + len(r)], 1))
+            at += len(r)
+        for h in hs:
+            h.close()
+        with torch.cuda.stream(side):
+            side.wait_stream(torch.cuda.current_stream())
+            c2 = sp.sp_coords_build(big[:len(raws[0])], 1)
+            assert c2.n == len(np.unique(raws[0], axis=0))
+            c2.close()
+    torch.cuda.synchronize()
     want = oracle_steps(raws[0], 3, 1, 1, 1)     # slots are free again: builds work as before
     c = sp.sp_coords_build(dev(raws[0]), 1)
     km, co = sp.sp_kmap_build(c, 3, 1, 1)
