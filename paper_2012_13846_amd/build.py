@@ -14,6 +14,7 @@ LIB = os.path.join(HERE, "libsp_conv.so")
 SOURCES = ["sp_runtime.hip", "sp_coords.hip", "sp_kmap.hip", "sp_conv.hip", "sp_conv_dense.hip", "sp_wgrad.hip", "sp_glue.hip", "sp_pool.hip", "sp_pack.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function", "-Wno-pass-failed",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 code generation
+         "-mllvm", "-amdgpu-mfma-vgpr-form",   # MFMA results in VGPRs: no v_accvgpr_read before every use of a product
          "-I", INCLUDE, "-I", CSRC]
 
 

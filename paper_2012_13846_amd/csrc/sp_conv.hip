@@ -408,8 +408,9 @@ __global__ __launch_bounds__(64) void gather_wave_kernel(GatherArgs a) {
 #pragma unroll
             for (int ct = 0; ct < kNCT; ++ct) av[ct] = *reinterpret_cast<const f32x4*>(r.dst + ct * 16);
         };
-        // (Letting lanes without a link update a spare row instead, which makes a turn one basic block, was
-        // measured: 73 us against 63, the same-address LDS writes of those lanes cost more than the branch.)
+        // (Letting lanes without a link update spare LDS bytes instead, one row for all or 16 bytes per lane, makes
+        // a turn one basic block in which the compiler deals the update and the loads out between the MFMAs;
+        // both were measured at 73-76 us against 62 with this branch.)
         auto flush_write = [&](const Result& r, const f32x4 (&av)[kNCT]) __attribute__((always_inline)) {
             if (r.valid) {
 #pragma unroll
