@@ -196,6 +196,27 @@ def cpu_baseline(raw, K, stride, dil, cin, cout, bf16, seed, all_cores=True):
 # ---------------------------------------------------------------------------------------------------------
 # one layer: coords + map + fwd + dgrad + wgrad
 # ---------------------------------------------------------------------------------------------------------
+def measured_roofs(sp, torch):
+    """What this GPU reaches on the two roofs' own microbenchmarks (the fractions in this file are against the
+    published peaks, these are for context): a plain 256 MiB device copy, and a register-resident MFMA loop."""
+    src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 10 * 2 * src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src, dst
+    return {"hbm_copy_GBps": round(copy_gbs, 1), "hbm_peak_GBps": PEAK_HBM_GBS,
+            "mfma_f32_TFLOPs": round(sp.sp_measure_mfma_peak(torch.float32), 1), "mfma_f32_peak_TFLOPs": PEAK_F32_MFMA_TFLOPS,
+            "mfma_bf16_TFLOPs": round(sp.sp_measure_mfma_peak(torch.bfloat16), 1), "mfma_bf16_peak_TFLOPs": PEAK_BF16_MFMA_TFLOPS,
+            "note": "copy counts bytes read + written; MFMA loop: 2 wavefronts per SIMD, operands in registers"}
+
+
 def profile_traffic(workload, kernel):
     """HBM bytes per launch of `kernel` from the committed rocprofv3 summary of this workload, if it has one: a line
     `roofline_traffic_bytes <kernel name> <bytes>` in profiles/step_<workload>.txt."""
@@ -266,7 +287,8 @@ def run_layer(name, steps, warmup, sp, spgen, torch, with_roofline):
         step(ev[i])
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    stage_ms = {n: float(np.mean([ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(steps)])) for j, n in enumerate(names)}
+    per_step = {n: [ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(steps)] for j, n in enumerate(names)}
+    stage_ms = {n: float(np.mean(v)) for n, v in per_step.items()}
     ms_per_step = elapsed / steps * 1e3
     flops_conv = 2.0 * pairs * cin * cout
     n_conv = 4 if up else 3
@@ -277,6 +299,9 @@ def run_layer(name, steps, warmup, sp, spgen, torch, with_roofline):
         stages[n] = conv_stage_entry(n, stage_ms[n], n_in, n_out, pairs, kvol, cin, cout, bf16)
     if up:   # transposed layer: sources = coarse rows (n_out), destinations = fine rows (n_in), cout -> cin channels
         stages["up_fwd"] = conv_stage_entry("conv_fwd", stage_ms["up_fwd"], n_out, n_in, pairs, kvol, cout, cin, bf16)
+    for n, v in per_step.items():   # "ms" above is the mean over the timed steps
+        stages[n]["median_ms"] = round(float(np.median(v)), 4)
+        stages[n]["min_ms"] = round(float(np.min(v)), 4)
     entry = {
         "workload": name, "dtype": "bf16" if bf16 else "f32", "n_raw": int(raw.shape[0]), "n_in": n_in, "n_out": n_out,
         "pairs": pairs, "kernel": K, "stride": stride, "dilation": dil, "cin": cin, "cout": cout,
@@ -516,6 +541,7 @@ def main():
                           "bytes_written_per_launch": src.numel() * 4, "launches": 10}))
         return
 
+    measured = measured_roofs(sp, torch)
     out = {"metric": METRIC, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "data": "synthetic"}
     if args.workload == "cfg3_stack_bf16":
@@ -530,7 +556,7 @@ def main():
         out["coords_mpoints_per_s"] = entry["stages"]["coords_build"]["mpoints_per_s"]
         out["map_build_ms"] = entry["map_build_ms"]
     out.update({"value": entry["tflops_step"], "ms_per_step": entry["ms_per_step"], "dtype": entry["dtype"],
-                "stages": entry["stages"], "roofline": roofline})
+                "stages": entry["stages"], "roofline": roofline, "measured_roofs": measured})
     if not args.only_headline:
         configs = []
         for name in DEFAULT_EXTRA:

@@ -419,6 +419,15 @@ def sp_conv_kernel_name(kmap: KMap, cin: int, cout: int, dtype: torch.dtype, dir
     return l.sp_conv_kernel_name(kmap._h, cin, cout, SP_F32 if dtype == torch.float32 else SP_BF16, direction).decode()
 
 
+def sp_measure_mfma_peak(dtype: torch.dtype) -> float:
+    """Measured matrix-core rate (TFLOP/s) of a register-resident MFMA loop in this dtype, on the current stream."""
+    out = C.c_double(0.0)
+    l = lib()
+    l.sp_measure_mfma_peak.argtypes = [C.c_int32, _vp, C.POINTER(C.c_double)]
+    _check(l.sp_measure_mfma_peak(SP_F32 if dtype == torch.float32 else SP_BF16, _stream(), C.byref(out)))
+    return float(out.value)
+
+
 def sp_version() -> str:
     return lib().sp_version().decode()
 

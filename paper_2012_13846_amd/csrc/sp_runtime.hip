@@ -424,6 +424,41 @@ int read_back(void* h_dst, const void* d_src, size_t bytes, hipStream_t s, const
 
 }  // namespace sp
 
+namespace sp {
+// iters x 8 independent MFMAs per wavefront, operands and accumulators in registers
+template <bool kF32>
+__global__ __launch_bounds__(256) void mfma_loop_kernel(int iters, float* __restrict__ sink) {
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+    f32x4 acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const float a = 1.0f + (float)(threadIdx.x & 3) * 0.25f, b = 0.5f;
+    bf16x8 ah, bh;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        ah[j] = (__bf16)a;
+        bh[j] = (__bf16)b;
+    }
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            // (a different first operand per chain: identical chains would be merged into one)
+            if constexpr (kF32) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a + (float)j, b, acc[j], 0, 0, 0);
+            else {
+                bf16x8 aj = ah;
+                aj[0] = (__bf16)(float)j;
+                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aj, bh, acc[j], 0, 0, 0);
+            }
+        }
+    }
+    float t = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) t += acc[j][0] + acc[j][1] + acc[j][2] + acc[j][3];
+    if (t == 123.456f) sink[threadIdx.x] = t;  // never true: keeps the loop alive without a store in the way
+}
+}  // namespace sp
+
 extern "C" {
 
 const char* sp_last_error(void) { return sp::g_err.c_str(); }
@@ -438,6 +473,31 @@ int sp_set_allocator(sp_alloc_fn alloc, sp_free_fn free_, void* ctx) {
     e.ctx = ctx;
     return SP_OK;
 }
+int sp_measure_mfma_peak(sp_dtype dt, void* stream, double* tflops) {
+    if (!tflops || (dt != SP_F32 && dt != SP_BF16)) return sp::fail(SP_ERR_INVALID_ARG, "sp_measure_mfma_peak: bad argument");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    sp::Buf sink = sp::dev_alloc(4096, s);
+    if (!sink) return SP_ERR_ALLOC;
+    const int iters = 20000, blocks = 256 * 4 * 2 / 4;  // 8 wavefronts per CU = 2 per SIMD, 4 per workgroup
+    hipEvent_t e0, e1;
+    SP_HIP(hipEventCreate(&e0));
+    SP_HIP(hipEventCreate(&e1));
+    for (int rep = 0; rep < 2; ++rep) {  // the first launch warms up
+        SP_HIP(hipEventRecord(e0, s));
+        if (dt == SP_F32) hipLaunchKernelGGL(sp::mfma_loop_kernel<true>, dim3(blocks), dim3(256), 0, s, iters, sp::ptr<float>(sink));
+        else hipLaunchKernelGGL(sp::mfma_loop_kernel<false>, dim3(blocks), dim3(256), 0, s, iters, sp::ptr<float>(sink));
+        SP_HIP(hipEventRecord(e1, s));
+        SP_HIP(hipEventSynchronize(e1));
+    }
+    float ms = 0.f;
+    SP_HIP(hipEventElapsedTime(&ms, e0, e1));
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    const double flop_per_mfma = dt == SP_F32 ? 2.0 * 16 * 16 * 4 : 2.0 * 16 * 16 * 32;
+    *tflops = (double)blocks * 4 * iters * 8 * flop_per_mfma / (ms * 1e-3) / 1e12;
+    return SP_OK;
+}
+
 int64_t sp_pool_cross_stream(void) { return sp::pool_cross_stream(); }
 int sp_pool_trim(void) { return sp::pool_trim(); }
 int64_t sp_pool_bytes(void) { return sp::pool_bytes(); }

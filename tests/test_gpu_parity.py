@@ -131,6 +131,15 @@ def test_coords_out_of_range_is_an_error(sp):
         assert e.value.code == -2
 
 
+def test_measured_mfma_roof_is_plausible(sp):
+    """The register-resident MFMA loop must land between a third of the published dense peaks and just above them
+    (157.3 TFLOP/s fp32, 2.5 PFLOP/s bf16 on this GPU): it is what bench.py prints as the measured roof."""
+    f32 = sp.sp_measure_mfma_peak(torch.float32)
+    bf16 = sp.sp_measure_mfma_peak(torch.bfloat16)
+    assert 50.0 < f32 < 170.0, f32
+    assert 800.0 < bf16 < 2700.0, bf16
+
+
 def test_bad_arguments(sp):
     c = sp.sp_coords_build(dev(spgen.coords_config(0)), 1)
     for args, code in (((0, 1, 1), -1), ((6, 1, 1), -1), ((3, 0, 1), -1), ((3, 1, 0), -1), ((3, 2, 2), -5)):
