@@ -358,6 +358,49 @@ def test_generated_occupancy_is_surface_like():
     assert 4.0 < counts.sum() / len(c) < 12.0
 
 
+def _paper_values():
+    vals = {}
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "paper_values.txt")):
+        line = line.split("#")[0].split()
+        if line:
+            vals[line[0]] = [float(v) for v in line[1:]]
+    return vals
+
+
+def test_offsets_match_the_set_the_paper_prints():
+    # Sec. III-B gives V^1(3) = {-1, 0, 1}; the 3-D offsets of a 3x3x3 kernel are its cube, z fastest
+    want = _paper_values()["offsets_1d_k3"]
+    # recover offset k from the map of one output voxel inside a full 3x3x3 cube of inputs: its only pair at k
+    # is the input at c_out + i_k
+    cube = np.array([[0, x, y, z] for x in (-1, 0, 1) for y in (-1, 0, 1) for z in (-1, 0, 1)], np.int32)
+    rng = np.random.default_rng(3)
+    cube = cube[rng.permutation(27)]
+    pin, pout, counts = oracle.kernel_map(cube, np.zeros((1, 4), np.int32), 3, 1)
+    assert counts.tolist() == [1] * 27
+    off = cube[pin][:, 1:]
+    assert sorted(set(off[:, 0].tolist())) == sorted(set(off[:, 1].tolist())) == sorted(set(off[:, 2].tolist())) == want
+    assert len(off) == 27 and len({tuple(o) for o in off.tolist()}) == 27
+    assert off[:3].tolist() == [[-1, -1, -1], [-1, -1, 0], [-1, -1, 1]]
+
+
+def test_sweep_clouds_have_the_occupancy_and_dropout_the_paper_reports():
+    """The sparsity-sweep stand-ins (Sec. IV-C, Table II): full shapes of 4096 points occupy about 7.6 % of the 32^3
+    grid and 2.6 % of the 50^3 grid; with dropout setting p a shape keeps a fraction U[p, 1] of its points, so the
+    mean kept fraction is (1 + p) / 2, the ratio Table II's epoch times follow at fixed batch size."""
+    pv = _paper_values()
+    assert spgen.SWEEP_POINTS == int(pv["points_per_shape"][0]) and list(spgen.SWEEP_P) == pv["sweep_p"]
+    for grid, key in ((32, "occupancy_32"), (50, "occupancy_50")):
+        occ = [len(oracle.unique_coords(spgen.sweep_cloud(spgen.seed_for(5, c, 3), grid, 1.0))[0]) / grid ** 3 for c in range(48)]
+        assert abs(np.mean(occ) - pv[key][0]) < 0.15 * pv[key][0], (grid, np.mean(occ))
+    for p in spgen.SWEEP_P:   # kept fraction of the shape's own points (a few of the 4096 fall outside the grid's cube)
+        kept = [len(spgen.sweep_cloud(spgen.seed_for(5, c, 4), 32, p)) / len(spgen.sweep_cloud(spgen.seed_for(5, c, 4), 32, 1.0))
+                for c in range(400)]
+        assert abs(np.mean(kept) - (1 + p) / 2) < 0.03 and min(kept) >= p - 1e-3
+    t = pv["epoch_time_sparse_32"]            # batch 256: p = 1, 0.5, 0.25
+    for p, ratio in zip((0.5, 0.25), (t[2] / t[1], t[3] / t[1])):
+        assert abs(ratio - (1 + p) / 2) < 0.08, (p, ratio)
+
+
 # ------------------------------------------------------------------ layers between the convolutions
 def test_glue_layers_match_torch_library_routines():
     from oracle import glue
