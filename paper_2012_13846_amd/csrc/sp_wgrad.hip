@@ -517,20 +517,22 @@ int launch_staged(const sp_kmap* m, const void* x, const void* dy, int cin, int 
     pa.pair_stride = (int)m->pair_stride;
     pa.tiles = (cout / COB) * (cin / CIB);
     for (int k = 0; k <= kvol; ++k) pa.koff[k] = (int32_t)m->koff[k];
-    // Strips: about 1.5 MB of rows (both operands) each, but long enough that an offset's stretch in a strip
-    // (which costs a partial block of per * 4 bytes) has at least ~1024 links or per / 32 of them.
-    const int64_t rows_bytes = (m->n_in * (int64_t)cin + m->n_out * (int64_t)cout) * (int64_t)sizeof(T);
-    const int64_t stretch = std::max<int64_t>(1024, per / 32);
-    int64_t M = std::min<int64_t>((rows_bytes / 8 + (3 << 18)) / (3 << 19), m->total / (8 * kvol * stretch));
-    M = M < 1 ? 1 : (M > 128 ? 128 : M);  // the reduction keeps a strip table of 1024 entries in LDS
-    pa.S8 = (int)(8 * M);
-    // Chunks: when everything fits the GPU at once, exactly as many workgroups as are resident together
-    // (one round, equal chunks); otherwise about 2048 links each (more for wide layers).
+    // Strips: one per XCD.  (More strips, sized so that a strip's rows fit an XCD's L2, were measured slower on
+    // every workload, 4-19 %: each strip adds one partial block per offset, and the rows' L2 hits did not pay for
+    // that traffic.)
+    pa.S8 = 8;
+    // Chunks (one workgroup each): when the links fit the GPU at once with at most 8192 per chunk, exactly as many
+    // chunks as workgroups are resident together (one round, equal chunks); otherwise whole rounds of about
+    // 4096-link chunks (a chunk costs a partial block of per * 4 or 8 bytes written and read again; rounds that
+    // are not whole leave most of the GPU idle during the last one).
     const int64_t strip_links = (m->total + pa.S8 - 1) / pa.S8 + kvol;  // upper bound of a strip's sequence
-    const int64_t resident = (int64_t)256 * occ / pa.tiles;
-    int64_t nc = resident / pa.S8;
-    const int64_t links = std::max<int64_t>(2048, per / 16);  // a chunk's partial block costs per * 8 bytes of traffic
-    if (nc < 1 || strip_links > nc * links) nc = (strip_links + links - 1) / links;
+    const int64_t resident = std::max<int64_t>(pa.S8, (int64_t)256 * occ / pa.tiles);
+    const int64_t per_strip = resident / pa.S8;  // chunks per strip in one round
+    int64_t nc = per_strip;
+    if (strip_links > nc * 8192) {
+        const int64_t rounds = (strip_links + per_strip * 4096 - 1) / (per_strip * 4096);
+        nc = rounds * per_strip;
+    }
     int64_t C = (strip_links + nc - 1) / nc;
     C = (C + Cfg::kS - 1) / Cfg::kS * Cfg::kS;
     pa.nc = (int)nc;
