@@ -27,12 +27,11 @@ __device__ __forceinline__ float load_f32(const bf16_t* p) { return __uint_as_fl
 
 // Work decomposition.  Offset k's links are sorted by row on one side, so the j-th fraction of every
 // offset's list covers about the same rows (and, on the other side, their spatial neighbours).  The lists are
-// cut into S8 = 8*M "strips": strip s is, for every offset in turn, the s-th 1/S8 of its list; the
-// concatenation of these stretches is the strip's link sequence.  Workgroup i runs on XCD i % 8: strips are
-// dealt to the XCDs round-robin and run in order, so the rows a strip touches 27 times cross the fabric once
-// and are then served by that XCD's L2.  A strip's sequence is cut into nc chunks of C links, one workgroup
-// each (times the channel tiles): equal work whatever the offsets' densities.  A chunk that spans several
-// offsets produces one partial block per offset ("piece").
+// cut into S8 "strips" (the host uses 8, one per XCD): strip s is, for every offset in turn, the s-th 1/S8 of
+// its list; the concatenation of these stretches is the strip's link sequence.  Workgroup i runs on XCD i % 8,
+// so a strip's rows, touched by up to 27 offsets, are fetched by one XCD.  A strip's sequence is cut into nc
+// chunks of C links, one workgroup each (times the channel tiles): equal work whatever the offsets'
+// densities.  A chunk that spans several offsets produces one partial block per offset ("piece").
 //
 // Partial blocks are numbered strip by strip in sequence order: within a strip, the piece that starts at
 // sequence position p has number ceil(p / C) + (offset stretches starting before p at a position that is
@@ -521,18 +520,13 @@ int launch_staged(const sp_kmap* m, const void* x, const void* dy, int cin, int 
     // every workload, 4-19 %: each strip adds one partial block per offset, and the rows' L2 hits did not pay for
     // that traffic.)
     pa.S8 = 8;
-    // Chunks (one workgroup each): when the links fit the GPU at once with at most 8192 per chunk, exactly as many
-    // chunks as workgroups are resident together (one round, equal chunks); otherwise whole rounds of about
-    // 4096-link chunks (a chunk costs a partial block of per * 4 or 8 bytes written and read again; rounds that
-    // are not whole leave most of the GPU idle during the last one).
+    // Chunks (one workgroup each): exactly as many as workgroups are resident together, so the launch is one
+    // round of equal chunks whatever the size of the map.  A chunk costs a partial block (per * 4 or 8 bytes written
+    // and read again) and a pipeline fill; shorter chunks in several rounds were measured slower throughout
+    // (2048-link chunks: +10 % on 11.5 M links, +30 % on 5 M links of 64 -> 64 fp32).
     const int64_t strip_links = (m->total + pa.S8 - 1) / pa.S8 + kvol;  // upper bound of a strip's sequence
     const int64_t resident = std::max<int64_t>(pa.S8, (int64_t)256 * occ / pa.tiles);
-    const int64_t per_strip = resident / pa.S8;  // chunks per strip in one round
-    int64_t nc = per_strip;
-    if (strip_links > nc * 8192) {
-        const int64_t rounds = (strip_links + per_strip * 4096 - 1) / (per_strip * 4096);
-        nc = rounds * per_strip;
-    }
+    const int64_t nc = resident / pa.S8;  // chunks per strip
     int64_t C = (strip_links + nc - 1) / nc;
     C = (C + Cfg::kS - 1) / Cfg::kS * Cfg::kS;
     pa.nc = (int)nc;
