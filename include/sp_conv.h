@@ -268,8 +268,8 @@ const char* sp_version(void);
  * kernel they time; the choice itself is the library's and may change between versions. */
 const char* sp_conv_kernel_name(const sp_kmap_t* m, int32_t cin, int32_t cout, sp_dtype dt, int32_t direction);
 /* Measured matrix-core roof of this GPU, for benchmarks that quote a fraction of it: runs a loop of independent
- * register-resident MFMAs (SP_F32: v_mfma_f32_16x16x4_f32; SP_BF16: v_mfma_f32_16x16x32_bf16) on every SIMD for a few
- * milliseconds on `stream`, waits for it, and writes the rate in TFLOP/s to *tflops (host pointer).  No operands
+ * register-resident MFMAs (SP_F32: v_mfma_f32_16x16x4_f32; SP_BF16: v_mfma_f32_16x16x32_bf16) on every SIMD for about a
+ * millisecond on `stream`, waits for it, and writes the rate in TFLOP/s to *tflops (host pointer).  No operands
  * come from memory.  Allocates 4 KB from the pool. */
 int sp_measure_mfma_peak(sp_dtype dt, void* stream, double* tflops);
 

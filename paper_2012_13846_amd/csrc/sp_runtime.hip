@@ -478,7 +478,7 @@ int sp_measure_mfma_peak(sp_dtype dt, void* stream, double* tflops) {
     hipStream_t s = static_cast<hipStream_t>(stream);
     sp::Buf sink = sp::dev_alloc(4096, s);
     if (!sink) return SP_ERR_ALLOC;
-    const int iters = 20000, blocks = 256 * 4 * 2 / 4;  // 8 wavefronts per CU = 2 per SIMD, 4 per workgroup
+    const int iters = 4000, blocks = 256 * 4 * 2 / 4;  // 8 wavefronts per CU = 2 per SIMD, 4 per workgroup
     hipEvent_t e0, e1;
     SP_HIP(hipEventCreate(&e0));
     SP_HIP(hipEventCreate(&e1));
