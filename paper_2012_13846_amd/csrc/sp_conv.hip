@@ -570,7 +570,8 @@ int launch_wave(GatherArgs a, hipStream_t s) {
     // run in several rounds, where splitting would only add padding.
     const int64_t resident_tiles = 256 * (160 * 1024 / (int64_t)a.lds_per_wave);
     a.split_blocks = (nwt * (a.co_total / COT) * 5 / 4 <= resident_tiles) ? 48 : 0x7fffffff;
-    dim3 grid((unsigned)(2 * nwt), (unsigned)(a.co_total / COT));
+    // two wavefronts per sub-tile only where sub-tiles may be split (the second one leaves at once otherwise)
+    dim3 grid((unsigned)((a.split_blocks == 0x7fffffff ? 1 : 2) * nwt), (unsigned)(a.co_total / COT));
     hipLaunchKernelGGL(kern, grid, dim3(64), lds, s, a);
     SP_HIP(hipGetLastError());
     return SP_OK;  // wf goes back to the pool; later users are ordered behind this launch on the stream
