@@ -518,7 +518,7 @@ int launch_staged(const sp_kmap* m, const void* x, const void* dy, int cin, int 
     for (int k = 0; k <= kvol; ++k) pa.koff[k] = (int32_t)m->koff[k];
     // Strips: one per XCD.  (More strips, sized so that a strip's rows fit an XCD's L2, were measured slower on
     // every workload, 4-19 %: each strip adds one partial block per offset, and the rows' L2 hits did not pay for
-    // that traffic.)
+    // that traffic.  Fewer than one per XCD, with the chunks dealt to the XCDs in turn, were 1-12 % slower too.)
     pa.S8 = 8;
     // Chunks (one workgroup each): exactly as many as workgroups are resident together, so the launch is one
     // round of equal chunks whatever the size of the map.  A chunk costs a partial block (per * 4 or 8 bytes written
