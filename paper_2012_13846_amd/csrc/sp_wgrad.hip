@@ -51,19 +51,25 @@ __device__ __forceinline__ void strip_stretch(const PlanArgs& pa, int k, int s, 
     *len = (int)(b1 - b0);
 }
 
-// Plan tables, one wavefront per strip (lane = offset):
-//   lo/len [S8][kvol]     offset k's stretch in strip s
-//   first/count [S8][kvol] number of its first partial block, how many it has
-//   cstart [S8][nc][3]    for chunk c: the offset whose stretch holds the chunk's first position, that
-//                         stretch's start position, and the number of stretches before it that start off a
-//                         chunk boundary; offset = kvol for chunks past the strip's end
-__global__ __launch_bounds__(64) void wgrad_plan_kernel(PlanArgs pa, int32_t* __restrict__ lo_tab, int32_t* __restrict__ len_tab,
-                                                        int32_t* __restrict__ first, int32_t* __restrict__ count,
-                                                        int32_t* __restrict__ cstart) {
-    const int s = blockIdx.x, lane = threadIdx.x;
+// The plan of one strip, computed by every wavefront for itself (lane = offset; registers only): lo/len of the
+// stretches of offsets lane and lane + 64, and for chunk `chunk` of the strip (positions [chunk*C, chunk*C + C)
+// of the strip's sequence): the offset whose stretch holds the chunk's first position (kvol: the chunk lies past
+// the strip's end), that stretch's start position, and the number of stretches before it that start off a chunk
+// boundary.
+struct StripPlan {
+    int lo[2], len[2];      // this lane's offsets
+    int k0, pos0, nb0;      // the chunk's start (the same in every lane)
+};
+__device__ __forceinline__ StripPlan strip_plan(const PlanArgs& pa, int s, int chunk, int lane) {
+    StripPlan sp;
+    const int cb = chunk * pa.C;
+    sp.k0 = pa.kvol;
+    sp.pos0 = 0;
+    sp.nb0 = 0;
     int pos_base = 0, nb_base = 0;
-    for (int kb = 0; kb < pa.kvol; kb += 64) {
-        const int k = kb + lane;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int k = h * 64 + lane;
         int lo = 0, len = 0;
         if (k < pa.kvol) strip_stretch(pa, k, s, &lo, &len);
         int inc = len;
@@ -76,35 +82,34 @@ __global__ __launch_bounds__(64) void wgrad_plan_kernel(PlanArgs pa, int32_t* __
         const bool real = len > 0 && pos % pa.C != 0;
         const unsigned long long mask = __ballot(real);
         const int nb = nb_base + __popcll(mask & ((1ull << lane) - 1ull));
-        if (k < pa.kvol) {
-            lo_tab[s * pa.kvol + k] = lo;
-            len_tab[s * pa.kvol + k] = len;
-            first[s * pa.kvol + k] = len > 0 ? s * pa.slots_per_strip + (pos + pa.C - 1) / pa.C + nb : 0;
-            count[s * pa.kvol + k] = len > 0 ? (pos + len + pa.C - 1) / pa.C - pos / pa.C : 0;
-            for (int c = (pos + pa.C - 1) / pa.C; c < pa.nc && (int64_t)c * pa.C < pos + len; ++c) {
-                int32_t* cs = cstart + ((size_t)s * pa.nc + c) * 3;
-                cs[0] = k;
-                cs[1] = pos;
-                cs[2] = nb;
-            }
+        sp.lo[h] = lo;
+        sp.len[h] = len;
+        const unsigned long long here = __ballot(len > 0 && pos <= cb && cb < pos + len);
+        if (here) {  // exactly one lane
+            const int src = __builtin_ctzll(here);
+            sp.k0 = h * 64 + src;
+            sp.pos0 = __shfl(pos, src, 64);
+            sp.nb0 = __shfl(nb, src, 64);
         }
         pos_base += __shfl(inc, 63, 64);
         nb_base += __popcll(mask);
     }
-    for (int c = (pos_base + pa.C - 1) / pa.C + lane; c < pa.nc; c += 64) cstart[((size_t)s * pa.nc + c) * 3] = pa.kvol;
+    return sp;
 }
 
 // dW[k][e] = sum of offset k's partial blocks, strip by strip, in a fixed order: 16 interleaved running sums
 // per element, each over every 16th block, then added in order 0..15.  grid (per/64, kvol); block = 16 lanes
 // x 4 elements each x 16 block slices.
 // P: type of the partial blocks and of the sums (double on the fp32 path, see wgrad_staged_kernel).
+// first / count [S8][kvol]: number of offset k's first partial block in strip s and how many it has (written by
+// the staged kernel).
 template <typename P>
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const P* __restrict__ part,
                                                            const int32_t* __restrict__ first,
                                                            const int32_t* __restrict__ count, int S8, int kvol, int per,
                                                            float* __restrict__ dw) {
     typedef P Px4 __attribute__((ext_vector_type(4)));
-    constexpr int kMaxStrips = 1024;
+    constexpr int kMaxStrips = 64;
     __shared__ int s_first[kMaxStrips], s_count[kMaxStrips];
     __shared__ Px4 red[16][16];
     const int k = blockIdx.y;
@@ -176,9 +181,8 @@ struct StagedArgs {
     int cin, cout;
     uint32_t x_bytes, dy_bytes, pair_bytes;  // buffer sizes (< 2 GiB each)
     PlanArgs plan;
-    const int32_t* lo_tab;   // plan tables, see wgrad_plan_kernel
-    const int32_t* len_tab;
-    const int32_t* cstart;
+    int32_t* first;   // [S8][kvol], for the reduction: written here by the workgroup in whose chunk a stretch starts
+    int32_t* count;
 };
 
 template <typename T, int COB, int CIB, int WCO, int WCI, int WK, int kD>
@@ -348,17 +352,33 @@ __global__ __launch_bounds__(64 * WCO * WCI * WK) void wgrad_staged_kernel(Stage
     // requested in step s-kD, and the row numbers of step s+2*kD are requested.  The step count is rounded up
     // to a multiple of kD (steps past the piece's end load zeros) to keep the loop body branch-free.
     Regs r[kD];
+    // the strip's plan (a few hundred cycles of integer arithmetic per wavefront: cheaper than a launch that
+    // writes it to memory and the loads that read it back)
+    const StripPlan plan = strip_plan(pa, strip, chunk, lane);
+    if (chunk == 0 && tile == 0 && wave == 0) {  // offsets without links in this strip: no partial blocks
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int k = h * 64 + lane;
+            if (k < pa.kvol && plan.len[h] == 0) {
+                a.first[strip * pa.kvol + k] = 0;
+                a.count[strip * pa.kvol + k] = 0;
+            }
+        }
+    }
     // the chunk's pieces: walk the strip's stretches, offset by offset
-    const int32_t* cs = a.cstart + ((size_t)strip * pa.nc + chunk) * 3;
-    int pos = cs[1], nb = cs[2];
-    for (int k = cs[0]; k < pa.kvol && pos < ce; ++k) {
-        const int lo = a.lo_tab[strip * pa.kvol + k];
-        const int slen = a.len_tab[strip * pa.kvol + k];
+    int pos = plan.pos0, nb = plan.nb0;
+    for (int k = plan.k0; k < pa.kvol && pos < ce; ++k) {
+        const int lo = __shfl(k < 64 ? plan.lo[0] : plan.lo[1], k & 63, 64);
+        const int slen = __shfl(k < 64 ? plan.len[0] : plan.len[1], k & 63, 64);
         if (slen == 0) continue;
         const int s0 = pos, p0 = max(s0, cb), p1 = min(s0 + slen, ce);
         const bool real = s0 % pa.C != 0;
         pos += slen;
         const int nb_here = nb + ((real && s0 < p0) ? 1 : 0);
+        if (s0 >= cb && tile == 0 && tid == 0) {  // the stretch starts in this chunk: tell the reduction where its blocks are
+            a.first[strip * pa.kvol + k] = strip * pa.slots_per_strip + (s0 + pa.C - 1) / pa.C + nb;
+            a.count[strip * pa.kvol + k] = (s0 + slen + pa.C - 1) / pa.C - s0 / pa.C;
+        }
         nb += real ? 1 : 0;
         if (p0 >= p1) continue;
         beg4 = (uint32_t)(lo + (p0 - s0)) * 4u;
@@ -534,14 +554,10 @@ int launch_staged(const sp_kmap* m, const void* x, const void* dy, int cin, int 
     pa.slots_per_strip = (int)nc + kvol;
     const int64_t slots = (int64_t)pa.S8 * pa.slots_per_strip;
     Buf part = dev_alloc((size_t)slots * per * Cfg::kPartElt, s);
-    const size_t nsk = (size_t)pa.S8 * kvol;
-    Buf plan = dev_alloc((nsk * 4 + (size_t)pa.S8 * nc * 3) * 4, s);
-    if (!part || !plan) return SP_ERR_ALLOC;
-    int32_t* d_lo = ptr<int32_t>(plan);
-    int32_t *d_len = d_lo + nsk, *d_first = d_len + nsk, *d_count = d_first + nsk, *d_cstart = d_count + nsk;
-    a.lo_tab = d_lo;
-    a.len_tab = d_len;
-    a.cstart = d_cstart;
+    Buf tabs = dev_alloc((size_t)2 * pa.S8 * kvol * 4, s);
+    if (!part || !tabs) return SP_ERR_ALLOC;
+    a.first = ptr<int32_t>(tabs);
+    a.count = a.first + (size_t)pa.S8 * kvol;
     a.pair_in = ptr<int32_t>(m->pair_in);
     a.pair_out = ptr<int32_t>(m->pair_out);
     a.x = x;
@@ -552,16 +568,14 @@ int launch_staged(const sp_kmap* m, const void* x, const void* dy, int cin, int 
     a.x_bytes = (uint32_t)((uint64_t)m->n_in * cin * sizeof(T));
     a.dy_bytes = (uint32_t)((uint64_t)m->n_out * cout * sizeof(T));
     a.pair_bytes = (uint32_t)((uint64_t)kvol * m->pair_stride * 4);
-    hipLaunchKernelGGL(wgrad_plan_kernel, dim3(pa.S8), dim3(64), 0, s, pa, d_lo, d_len, d_first, d_count,
-                       d_cstart);
     const int64_t wgs = (int64_t)pa.S8 * nc * pa.tiles;
     hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(Cfg::kThreads), Cfg::kLds, s, a);
     if constexpr (Cfg::kIsF32)
-        hipLaunchKernelGGL(wgrad_reduce_kernel<double>, dim3(per / 64, kvol), dim3(256), 0, s, ptr<double>(part), d_first,
-                           d_count, pa.S8, kvol, per, dw);
+        hipLaunchKernelGGL(wgrad_reduce_kernel<double>, dim3(per / 64, kvol), dim3(256), 0, s, ptr<double>(part), a.first,
+                           a.count, pa.S8, kvol, per, dw);
     else
-        hipLaunchKernelGGL(wgrad_reduce_kernel<float>, dim3(per / 64, kvol), dim3(256), 0, s, ptr<float>(part), d_first,
-                           d_count, pa.S8, kvol, per, dw);
+        hipLaunchKernelGGL(wgrad_reduce_kernel<float>, dim3(per / 64, kvol), dim3(256), 0, s, ptr<float>(part), a.first,
+                           a.count, pa.S8, kvol, per, dw);
     SP_HIP(hipGetLastError());
     return SP_OK;
 }
