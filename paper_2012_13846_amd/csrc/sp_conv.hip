@@ -242,6 +242,13 @@ __global__ __launch_bounds__(64) void gather_wave_kernel(GatherArgs a) {
     // cost few registers per block and weights many, so narrow rows are fetched deep and weights shallow.
     constexpr int kDX = 3;  // loads return in order: a deeper ring for the rows alone would still wait for the weights issued after it
     constexpr int kDW = 2;
+    // A weight matrix of more than 32 fragment registers (e.g. fp32 64 x 64) does not fit a ring of two whole
+    // matrices.  Then the two weight slots hold the two halves (channel tiles 0..kNCT/2-1 and the rest) of ONE
+    // block's matrix: a half is re-requested for the next block as soon as this block's MFMAs on it are issued,
+    // i.e. half a block ahead of its next use, which is enough for a matrix that lives in L2.
+    constexpr bool kHalfW = kNCT * kGroups > 8;
+    constexpr int kWT = kHalfW ? kNCT / 2 : kNCT;  // channel tiles per weight slot
+    static_assert(!kHalfW || kNCT % 2 == 0, "halves");
     constexpr int kTurn = 6;  // bodies per loop turn: a multiple of kDX, kDW and the two result sets
     static_assert(kTurn % kDX == 0 && kTurn % kDW == 0 && kTurn % 2 == 0, "ring sizes must divide the turn");
 
@@ -314,16 +321,16 @@ __global__ __launch_bounds__(64) void gather_wave_kernel(GatherArgs a) {
     const uint32_t w_tile_off = (uint32_t)(blockIdx.y * Cfg::kWFragBytesPerOffsetTile);
     const uint32_t w_offset_stride = (uint32_t)((a.co_total / COT) * Cfg::kWFragBytesPerOffsetTile);
 
-    auto load_weights = [&](int k, Frag (&wf)[kNCT][kGroups]) __attribute__((always_inline)) {
+    auto load_weights = [&](int k, Frag (&wf)[kWT][kGroups], int ct0) __attribute__((always_inline)) {
         const int wk = a.flip ? kvol - 1 - k : k;
         // the offset index is the same in every lane, but it came through LDS: tell the compiler
         const int soff = __builtin_amdgcn_readfirstlane((int)(w_tile_off + (uint32_t)wk * w_offset_stride));
 #pragma unroll
-        for (int ct = 0; ct < kNCT; ++ct)
+        for (int ct = 0; ct < kWT; ++ct)
 #pragma unroll
             for (int s = 0; s < kGroups; ++s)
                 wf[ct][s] = __builtin_bit_cast(
-                    Frag, __builtin_amdgcn_raw_buffer_load_b128(rW, lane * 16 + (ct * kGroups + s) * 1024, soff, 0));
+                    Frag, __builtin_amdgcn_raw_buffer_load_b128(rW, lane * 16 + ((ct0 + ct) * kGroups + s) * 1024, soff, 0));
     };
 
     // The main loop is straight-line code with the same loads in every turn (blocks past the end are
@@ -338,7 +345,7 @@ __global__ __launch_bounds__(64) void gather_wave_kernel(GatherArgs a) {
         u32x4 x[kXLoads];         // gathered pieces, coalesced layout: piece (t*64 + lane) of the block
     };
     struct WSlot {
-        Frag w[kNCT][kGroups];    // a block's weight matrix
+        Frag w[kWT][kGroups];     // a block's weight matrix (kHalfW: one half of it)
     };
     const int last = nblk - 1;
     // (Starting each wavefront at a block of its own, so that the wavefronts of a compute unit do not ask for
@@ -358,8 +365,8 @@ __global__ __launch_bounds__(64) void gather_wave_kernel(GatherArgs a) {
         for (int t = 0; t < kXLoads; ++t)
             sl.x[t] = __builtin_amdgcn_raw_buffer_load_b128(rF, sl.esrc[t] * Cfg::kRowBytes + ((t * 64 + lane) % kPieces) * 16, 0, 0);
     };
-    auto issue_weights = [&](WSlot& ws, int b) __attribute__((always_inline)) {
-        load_weights(s_blk[min(b, last)] & 127, ws.w);
+    auto issue_weights = [&](WSlot& ws, int b, int ct0 = 0) __attribute__((always_inline)) {
+        load_weights(s_blk[min(b, last)] & 127, ws.w, ct0);
     };
     auto stage = [&](const Slot& sl) __attribute__((always_inline)) {  // gathered rows -> LDS, row-major, padded
 #pragma unroll
@@ -380,7 +387,10 @@ __global__ __launch_bounds__(64) void gather_wave_kernel(GatherArgs a) {
 #pragma unroll
         for (int j = 0; j < kDX; ++j) load_entries(xs[j], j);
 #pragma unroll
-        for (int j = 0; j < kDW; ++j) issue_weights(ws[j], j);
+        for (int j = 0; j < kDW; ++j) {
+            if constexpr (kHalfW) issue_weights(ws[j], 0, j * kWT);  // both halves of block 0
+            else issue_weights(ws[j], j);
+        }
 #pragma unroll
         for (int j = 0; j < kDX; ++j) issue_gather(xs[j]);
 #pragma unroll
@@ -419,7 +429,23 @@ __global__ __launch_bounds__(64) void gather_wave_kernel(GatherArgs a) {
                 for (int ct = 0; ct < kNCT; ++ct) *reinterpret_cast<f32x4*>(r.dst + ct * 16) = av[ct] + r.d[ct];
             }
         };
-        auto body = [&](int b, Slot& sl, const Slot& sn, WSlot& wl, Result& cur, const Result& prev) __attribute__((always_inline)) {
+        auto mfmas = [&](Result& cur, const WSlot& wl, int ct0, const Frag (&xf)[kGroups]) __attribute__((always_inline)) {
+#pragma unroll
+            for (int s = 0; s < kGroups; ++s)
+#pragma unroll
+                for (int c = 0; c < kWT; ++c) {
+                    const int ct = ct0 + c;
+                    if constexpr (kIsF32) {
+                        cur.d[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(wl.w[c][s][0], xf[s][0], cur.d[ct], 0, 0, 0);
+                        cur.d[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(wl.w[c][s][1], xf[s][1], cur.d[ct], 0, 0, 0);
+                        cur.d[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(wl.w[c][s][2], xf[s][2], cur.d[ct], 0, 0, 0);
+                        cur.d[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(wl.w[c][s][3], xf[s][3], cur.d[ct], 0, 0, 0);
+                    } else {
+                        cur.d[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wl.w[c][s], xf[s], cur.d[ct], 0, 0, 0);
+                    }
+                }
+        };
+        auto body = [&](int b, Slot& sl, const Slot& sn, WSlot& wl, WSlot& wl2, Result& cur, const Result& prev) __attribute__((always_inline)) {
             const int cnt = ((sl.dc >> 7) & 15) + 1;
             cur.valid = n16 < cnt;
             cur.dst = acc + sl.drow * Cfg::kStride + g * 4;
@@ -432,22 +458,19 @@ __global__ __launch_bounds__(64) void gather_wave_kernel(GatherArgs a) {
 
 #pragma unroll
             for (int ct = 0; ct < kNCT; ++ct) cur.d[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int s = 0; s < kGroups; ++s)
-#pragma unroll
-                for (int ct = 0; ct < kNCT; ++ct) {
-                    if constexpr (kIsF32) {
-                        cur.d[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(wl.w[ct][s][0], xf_c[s][0], cur.d[ct], 0, 0, 0);
-                        cur.d[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(wl.w[ct][s][1], xf_c[s][1], cur.d[ct], 0, 0, 0);
-                        cur.d[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(wl.w[ct][s][2], xf_c[s][2], cur.d[ct], 0, 0, 0);
-                        cur.d[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(wl.w[ct][s][3], xf_c[s][3], cur.d[ct], 0, 0, 0);
-                    } else {
-                        cur.d[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wl.w[ct][s], xf_c[s], cur.d[ct], 0, 0, 0);
-                    }
-                }
-            issue_gather(sl);               // block b + kDX: its entries arrived kDX turns ago
-            load_entries(sl, b + 2 * kDX);
-            issue_weights(wl, b + kDW);
+            if constexpr (kHalfW) {
+                mfmas(cur, wl, 0, xf_c);
+                issue_weights(wl, b + 1, 0);        // first half of the next block's matrix
+                mfmas(cur, wl2, kWT, xf_c);
+                issue_gather(sl);
+                load_entries(sl, b + 2 * kDX);
+                issue_weights(wl2, b + 1, kWT);     // its second half
+            } else {
+                mfmas(cur, wl, 0, xf_c);
+                issue_gather(sl);               // block b + kDX: its entries arrived kDX turns ago
+                load_entries(sl, b + 2 * kDX);
+                issue_weights(wl, b + kDW);
+            }
             flush_write(prev, av);
 #pragma unroll
             for (int s = 0; s < kGroups; ++s) xf_c[s] = xf_n[s];
@@ -476,7 +499,7 @@ __global__ __launch_bounds__(64) void gather_wave_kernel(GatherArgs a) {
 #pragma unroll
             for (int j = 0; j < kTurn; ++j) {
                 if (!stop) {
-                    body(b + j, xs[j % kDX], xs[(j + 1) % kDX], ws[j % kDW], res[j % 2], res[(j + 1) % 2]);
+                    body(b + j, xs[j % kDX], xs[(j + 1) % kDX], ws[kHalfW ? 0 : j % kDW], ws[1], res[j % 2], res[(j + 1) % 2]);
                     done = b + j + 1;
                     stop = b + j + 1 >= nblk;
                 }
@@ -657,7 +680,7 @@ int launch_gather(GatherArgs a, hipStream_t s) {
 int wave_tile(int cc, int co, bool is_f32, bool wave_ok) {
     const int groups = cc / (is_f32 ? 16 : 32);
     if (!wave_ok) return 0;
-    if (groups * 4 <= 8 && co % 64 == 0) return 64;
+    if (groups * 4 <= 16 && co % 64 == 0) return 64;  // more than 8 fragments per lane: the matrix is held in two halves
     if (groups * 2 <= 8 && co % 32 == 0) return 32;
     if (groups <= 2 && (co == 16 || co == 48)) return 16;
     return 0;
@@ -667,7 +690,7 @@ template <typename T, int CC>
 int dispatch_co(const GatherArgs& a, hipStream_t s) {
     constexpr int kGroups = CC / (std::is_same<T, float>::value ? 16 : 32);
     const int cot = wave_tile(CC, a.co_total, std::is_same<T, float>::value, a.wave_ok != 0);
-    if constexpr (kGroups * 4 <= 8)
+    if constexpr (kGroups * 4 <= 16)
         if (cot == 64) return launch_wave<T, CC, 64>(a, s);
     if constexpr (kGroups * 2 <= 8)
         if (cot == 32) return launch_wave<T, CC, 32>(a, s);

@@ -280,6 +280,9 @@ CONV_CASES = [
     ("cfg1_f32_d2", 1, 0.25, 1, 3, 1, 2, 32, 64, False, False),
     ("cfg1_f32_k3s2", 1, 0.25, 1, 3, 2, 1, 32, 32, False, False),
     ("cfg1_f32_64x16", 1, 0.1, 1, 3, 1, 1, 64, 16, False, False),
+    ("cfg1_f32_64x64", 1, 0.25, 1, 3, 1, 1, 64, 64, False, False),      # weight matrix held in two halves
+    ("cfg1_f32_64x128", 1, 0.1, 1, 3, 1, 1, 64, 128, False, False),
+    ("cfg1_bf16_128x64_sparse", 1, 0.25, 1, 3, 1, 1, 128, 64, True, False),
     ("cfg1_f32_128x128", 1, 0.05, 1, 3, 1, 1, 128, 128, False, False),
     ("cfg1_f32_256x48", 1, 0.02, 1, 3, 1, 1, 256, 48, False, False),
     ("cfg0_f32_3x5_plain", 0, 1.0, 1, 3, 1, 1, 3, 5, False, False),
