@@ -191,8 +191,8 @@ __global__ __launch_bounds__(256) void gather_mma_kernel(GatherArgs a) {
 //  - The wavefront first cuts its links into blocks of up to 16 links of one offset and writes one packed
 //    descriptor per block into LDS, so that block b+n is addressable without walking a cursor.
 //  - Everything a block needs is requested well ahead of its use and kept in registers: link entries
-//    (source row, destination row) 2*kDX blocks ahead, the gathered source rows kDX blocks ahead (6 for
-//    rows of up to 128 bytes, else 3), the weight matrix two blocks ahead.
+//    (source row, destination row) 2*kDX = 6 blocks ahead, the gathered source rows kDX = 3 blocks ahead, the
+//    weight matrix two blocks ahead (a matrix too large for two register copies: in halves, half a block ahead).
 //  - Source rows are gathered with coalesced 16-byte loads (adjacent lanes = adjacent pieces of one row; a
 //    fragment-shaped global load would cost one L1 tag lookup per lane) and pass through a small
 //    wavefront-private LDS buffer to be re-read as MFMA fragments, one block ahead of the MFMAs using them.
