@@ -618,12 +618,16 @@ __global__ __launch_bounds__(256) void gather_plain_kernel(const int32_t* __rest
         const int wk = flip ? kvol - 1 - kk : kk;
         const T* wp = W + (size_t)wk * cc * co + (size_t)c * w_co;
         const T* fp = F + (size_t)src * cc;
+        // one link's dot product first, then added: a single chain over all kvol * cc terms (6000 for a 5x5x5
+        // kernel on 48 channels) measured 8e-6 against the fp64 definition, this 1e-6
+        float dot = 0.f;
         for (int j = 0; j < cc; ++j) {
             if constexpr (std::is_same<T, float>::value)
-                acc = fmaf(wp[(size_t)j * w_cc], fp[j], acc);
+                dot = fmaf(wp[(size_t)j * w_cc], fp[j], dot);
             else
-                acc = fmaf(bf16_to_f32(wp[(size_t)j * w_cc]), bf16_to_f32(fp[j]), acc);
+                dot = fmaf(bf16_to_f32(wp[(size_t)j * w_cc]), bf16_to_f32(fp[j]), dot);
         }
+        acc += dot;
     }
     if constexpr (std::is_same<T, float>::value)
         G[idx] = acc;

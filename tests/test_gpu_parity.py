@@ -305,6 +305,12 @@ def test_conv_matches_oracle(sp, case):
     conv_case(sp, raw, ts, K, stride, dil, cin, cout, bf16, seed=1000 + len(name), transposed=transposed)
 
 
+def test_plain_kernel_long_sums_stay_within_tolerance(sp):
+    """5x5x5 kernel on a full cube, 48 -> 48 fp32 (a shape the plain one-thread-per-output kernel takes): up to 6000
+    terms per output.  Summed as one chain this measured 8e-6; per-link dot products first, it is 1.3e-6."""
+    conv_case(sp, full_cubes(10, 1), 1, 5, 1, 1, 48, 48, False, seed=4848)
+
+
 def full_cubes(side, batches):
     """Every voxel of a side^3 cube per cloud, rows shuffled: interior rows have all 27 neighbours, so the map is
     dense enough for the row-stationary wide-layer kernel to be chosen."""
