@@ -168,6 +168,14 @@ MAP_CASES = [
     ("ts2_k2s2", random_coords(8, 20000, 20, batches=2, lo=-10) * np.array([1, 2, 2, 2], np.int32), 2, 2, 2, 1),
     ("tail_257", random_coords(9, 257, 7, batches=1)[:257], 1, 3, 1, 1),
     ("one_voxel", np.array([[0, 0, 0, 0]], np.int32), 1, 3, 1, 1),
+    # voxels on the faces of the packable range: a neighbour beyond it is absent, never a wrapped-around key
+    ("range_faces_k3", np.array([[65535, 32767, 32767, 32767], [65535, 32766, 32767, 32767], [0, -32768, -32768, -32768],
+                                 [0, -32768, -32768, -32767], [65534, -32768, 32767, 0], [65535, -32768, 32767, 0],
+                                 [0, 32767, -32768, 5], [1, -32768, -32768, 5]], np.int32), 1, 3, 1, 1),
+    ("range_faces_k5_d2", np.array([[65535, 32767, 32767, 32767], [65535, 32763, 32767, 32767], [0, -32768, -32768, -32768],
+                                    [0, -32768, -32764, -32768], [1, 32767, 32767, 32767]], np.int32), 1, 5, 1, 2),
+    ("range_faces_k2s2", np.array([[65535, 32767, 32767, 32767], [65535, 32766, 32766, 32766], [0, -32768, -32768, -32768],
+                                   [0, -32767, -32768, -32767]], np.int32), 1, 2, 2, 1),
 ]
 
 

@@ -171,3 +171,17 @@ def test_generative_bad_arguments_and_empty(sp):
     c0 = sp.sp_coords_build(torch.empty((0, 4), dtype=torch.int32, device="cuda"), 2)
     km, fine = sp.sp_kmap_build_generative(c0, 2, 2)
     assert km.total == 0 and fine.n == 0 and fine.tensor_stride == 1
+
+
+def test_generative_rows_beyond_the_packable_range_are_an_error(sp):
+    """A created row is a coordinate like any other: one past the range is reported, not wrapped."""
+    c = sp.sp_coords_build(dev(np.array([[0, 32767, 0, 0], [0, 5, 5, 5]], np.int32)), 1)
+    with pytest.raises(sp.SpError) as e:
+        sp.sp_kmap_build_generative(c, 3, 1)          # 32767 + 1 has no key
+    assert e.value.code == -2
+    c = sp.sp_coords_build(dev(np.array([[0, -32768, 0, 0]], np.int32)), 2)
+    with pytest.raises(sp.SpError) as e:
+        sp.sp_kmap_build_generative(c, 3, 2)          # -32768 - 1
+    assert e.value.code == -2
+    km, fine = sp.sp_kmap_build_generative(c, 2, 2)   # even kernel: offsets 0 and +1 only, all rows fit
+    assert fine.n == 8 and km.total == 8
