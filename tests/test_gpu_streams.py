@@ -116,3 +116,43 @@ def test_callers_allocator(sp):
     # and the pool works again
     c2 = sp.sp_coords_build(dev(raw), 1)
     assert c2.n == case["n_in"]
+
+
+def test_steady_state_steps_hold_the_pool_and_host_memory_still(sp):
+    """The same step over and over: after the first few the pool holds what it held (no HIP allocation per
+    step), the process's resident memory does not creep (handles, mail slots and plans are given back), results
+    stay identical, and once every handle is closed a trim leaves nothing in the pool."""
+    import gc
+    import psutil
+    raw = dev(spgen.coords_config(1, 0.2))
+    kvol, cin, cout = 27, 32, 64
+    w = torch.randn(kvol, cout, cin, device="cuda") * 0.1
+
+    def step(stride):
+        c = sp.sp_coords_build(raw, 1)
+        km, co = sp.sp_kmap_build(c, 3, stride, 1)
+        x = torch.ones(km.n_in, cin, device="cuda")
+        dy = torch.ones(km.n_out, cout, device="cuda")
+        y = sp.sp_conv_fwd(km, x, w)
+        dx = sp.sp_conv_bwd_data(km, dy, w)
+        dw = sp.sp_conv_bwd_weight(km, x, dy)
+        out = (float(y.sum()), float(dx.sum()), float(dw.sum()))
+        km.close(), co.close(), c.close()
+        return out
+
+    ref = {}
+    for i in range(10):
+        ref[1 + i % 2] = step(1 + i % 2)
+    torch.cuda.synchronize()
+    gc.collect()
+    held = sp.sp_pool_bytes()
+    rss = psutil.Process().memory_info().rss
+    for i in range(300):
+        assert step(1 + i % 2) == ref[1 + i % 2]
+    torch.cuda.synchronize()
+    gc.collect()
+    assert sp.sp_pool_bytes() == held, "the pool grew in steady state"
+    grown = psutil.Process().memory_info().rss - rss
+    assert grown < 32 << 20, f"resident memory grew by {grown >> 20} MiB over 300 steps"
+    sp.sp_pool_trim()
+    assert sp.sp_pool_bytes() == 0 or sp.sp_pool_bytes() < held   # only blocks of still-open handles remain
