@@ -156,3 +156,56 @@ def test_steady_state_steps_hold_the_pool_and_host_memory_still(sp):
     assert grown < 32 << 20, f"resident memory grew by {grown >> 20} MiB over 300 steps"
     sp.sp_pool_trim()
     assert sp.sp_pool_bytes() == 0 or sp.sp_pool_bytes() < held   # only blocks of still-open handles remain
+
+
+def test_host_threads_with_their_own_streams(sp):
+    """Four host threads, each with a stream of its own, build maps and run the three convolutions at the same
+    time (ctypes drops the interpreter lock inside the library): every thread gets, every time, bit for bit
+    what the same work gave when it ran alone."""
+    import threading
+    jobs = []
+    for t in range(4):
+        raw = dev(spgen.coords_config(1, 0.1 + 0.05 * t))
+        stride = 1 + t % 2
+        cin, cout = (32, 64) if t < 2 else (64, 32)
+        g = torch.Generator(device="cuda").manual_seed(100 + t)
+        w = torch.randn(27, cout, cin, device="cuda", generator=g) * 0.1
+        jobs.append((raw, stride, cin, cout, w))
+
+    def work(job):
+        raw, stride, cin, cout, w = job
+        c = sp.sp_coords_build(raw, 1)
+        km, co = sp.sp_kmap_build(c, 3, stride, 1)
+        g = torch.Generator(device="cuda").manual_seed(7)
+        x = torch.randn(km.n_in, cin, device="cuda", generator=g)
+        dy = torch.randn(km.n_out, cout, device="cuda", generator=g)
+        y = sp.sp_conv_fwd(km, x, w)
+        dx = sp.sp_conv_bwd_data(km, dy, w)
+        dw = sp.sp_conv_bwd_weight(km, x, dy)
+        gin, gout = km.pairs()
+        out = [t.clone() for t in (c.coords(), co.coords(), gin, gout, y, dx, dw)]
+        torch.cuda.current_stream().synchronize()
+        km.close(), co.close(), c.close()
+        return out
+
+    alone = [work(j) for j in jobs]
+    errors = []
+
+    def run(t):
+        try:
+            with torch.cuda.stream(torch.cuda.Stream()):
+                for _ in range(25):
+                    got = work(jobs[t])
+                    for a, b in zip(got, alone[t]):
+                        if not torch.equal(a, b):
+                            raise AssertionError(f"thread {t}: a result differs from the single-threaded one")
+        except Exception as e:   # reported by the main thread
+            errors.append(e)
+
+    threads = [threading.Thread(target=run, args=(t,)) for t in range(4)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
