@@ -57,6 +57,9 @@ CASES = [
     ("cfg3_l1_k3_bf16_128x128", 3, 1, 3, 1, 1, 128, 128, True, False, 2048),
     ("cfg3_l1_k3s2_bf16_128x256", 3, 1, 3, 2, 1, 128, 256, True, False, 2048),
     ("cfg3_l2_k3_bf16_256x256", 3, 2, 3, 1, 1, 256, 256, True, False, 1024),
+    # the sparsity sweep's batches as bench.py times them (fp32, 64 -> 64): the largest batch of each grid
+    ("sweep32_p0.25_b512_f32_64x64", ("sweep", 32, 0.25, 512), 0, 3, 1, 1, 64, 64, False, False, N_SAMPLE),
+    ("sweep50_p0.25_b256_f32_64x64", ("sweep", 50, 0.25, 256), 0, 3, 1, 1, 64, 64, False, False, N_SAMPLE),
 ]
 
 
@@ -81,8 +84,12 @@ def links_of_rows(pair_in, pair_out, counts, rows, side):
 def test_full_size(sp, case):
     name, cfg, level, K, stride, dil, cin, cout, bf16, transposed, n_sample = case
     kvol = K ** 3
+    if isinstance(cfg, tuple):   # ("sweep", grid, p, clouds)
+        raw = spgen.coords_sweep(cfg[1], cfg[2], cfg[3])
+        cfg = 5
+    else:
+        raw = spgen.coords_config(cfg)
     rng = np.random.default_rng(spgen.seed_for(cfg, 0, stream=7))
-    raw = spgen.coords_config(cfg)
 
     # ---- coordinates of every level, in full
     c_in, inverse = oracle.unique_coords(raw)
