@@ -60,6 +60,9 @@ CASES = [
     # the sparsity sweep's batches as bench.py times them (fp32, 64 -> 64): the largest batch of each grid
     ("sweep32_p0.25_b512_f32_64x64", ("sweep", 32, 0.25, 512), 0, 3, 1, 1, 64, 64, False, False, N_SAMPLE),
     ("sweep50_p0.25_b256_f32_64x64", ("sweep", 50, 0.25, 256), 0, 3, 1, 1, 64, 64, False, False, N_SAMPLE),
+    # the two literal readings bench.py also times: 2048 points per cloud, and the room at 5 cm voxels
+    ("cfg2lit_2048pt_k2s2_bf16_64x128", ("literal", "cfg2_2048pt"), 0, 2, 2, 1, 64, 128, True, False, N_SAMPLE),
+    ("cfg4lit_5cm_k3_bf16_64x64", ("literal", "cfg4_5cm"), 0, 3, 1, 1, 64, 64, True, False, N_SAMPLE),
 ]
 
 
@@ -84,8 +87,8 @@ def links_of_rows(pair_in, pair_out, counts, rows, side):
 def test_full_size(sp, case):
     name, cfg, level, K, stride, dil, cin, cout, bf16, transposed, n_sample = case
     kvol = K ** 3
-    if isinstance(cfg, tuple):   # ("sweep", grid, p, clouds)
-        raw = spgen.coords_sweep(cfg[1], cfg[2], cfg[3])
+    if isinstance(cfg, tuple):   # ("sweep", grid, p, clouds) or ("literal", name)
+        raw = spgen.coords_sweep(cfg[1], cfg[2], cfg[3]) if cfg[0] == "sweep" else spgen.coords_literal(cfg[1])
         cfg = 5
     else:
         raw = spgen.coords_config(cfg)
