@@ -65,6 +65,10 @@ struct DenseCfg {
     static constexpr int kXLoads = kTR / kRP;        // 16-byte pieces per thread and step
     static constexpr int kWLoads = COT / kRP;
     static constexpr int kWDepth = kWaves > 4 ? 1 : 2;  // register stages of the weight slices (the rows always have 2)
+    // Weight fragments in flight per wavefront.  With 8 wavefronts and four slices per offset (CC = 256) a third one
+    // makes the compiler spill, and a reload inside the loop waits for every gather in flight (loads return in
+    // order), which undoes the rows' second register stage.
+    static constexpr int kWF = (kWaves > 4 && CC == 256) ? 2 : 3;
     static constexpr int kOutPitch = COT * 2 + 16;   // output staging row (bf16)
     static constexpr int kLds = 2 * kBuf > kTR * kOutPitch ? 2 * kBuf : kTR * kOutPitch;
     static constexpr int kMI = 4;                    // 16-row groups per wavefront: 64 rows
@@ -161,7 +165,6 @@ __global__ __launch_bounds__(kDenseThreads<COT>, (KS == 32 ? 2 : 1)) void gather
     auto store_w = [&](const u32x4 (&w)[kWLoads], int j, unsigned char* buf) __attribute__((always_inline)) {
         *reinterpret_cast<u32x4*>(buf + Cfg::kXBytes + st_off + j * kRP * kRowBytes) = w[j];
     };
-
     // acc[ni][mi][i]: destination channel co0 + ch*128 + ni*16 + 4*g + i, tile row rq*64 + mi*16 + n16
     // (weights are the MFMA A operand, the gathered rows the B operand: a lane ends up with 4 adjacent channels
     // of one row, which pack into one 8-byte store)
@@ -178,14 +181,15 @@ __global__ __launch_bounds__(kDenseThreads<COT>, (KS == 32 ? 2 : 1)) void gather
                            Cfg::kXBytes + (ch * 128 + n16) * kRowBytes + swz<kP>(n16, (4 + g) % kP)};
     // One step = kKSteps k-steps x kNI channel tiles = kGroups groups of kMI MFMAs.  A wavefront issues in order
     // and an MFMA runs for 16 cycles once issued, so everything else the step has to do is dealt out over the
-    // groups and issued in the shadow of their MFMAs: the LDS fragment reads (two groups ahead of their
-    // use: 3 rotating weight fragments; the second k-step's row fragments during the first k-step), the
+    // groups and issued in the shadow of their MFMAs: the LDS fragment reads (kWF - 1 groups ahead of their
+    // use: kWF rotating weight fragments; the second k-step's row fragments during the first k-step), the
     // global loads of later steps and the LDS stores of the next step's stage, kPerGroup of each per group.
     constexpr int kGroups = kKSteps * kNI;
     constexpr int kLoads = kXLoads + kWLoads;
     constexpr int kPerGroup = (kLoads + kGroups - 1) / kGroups;
     auto compute = [&](const unsigned char* buf, auto&& extra) __attribute__((always_inline)) {
-        bf16x8 xf[kKSteps][kMI], wf[3];
+        constexpr int kWF = Cfg::kWF;
+        bf16x8 xf[kKSteps][kMI], wf[kWF];
         auto read_w = [&](int grp) __attribute__((always_inline)) {
             return *reinterpret_cast<const bf16x8*>(buf + frag_w[grp / kNI] + (grp % kNI) * 16 * kRowBytes);
         };
@@ -194,17 +198,17 @@ __global__ __launch_bounds__(kDenseThreads<COT>, (KS == 32 ? 2 : 1)) void gather
         };
 #pragma unroll
         for (int mi = 0; mi < kMI; ++mi) xf[0][mi] = read_x(0, mi);
-        wf[0] = read_w(0);
-        wf[1] = read_w(1);
+#pragma unroll
+        for (int i = 0; i < kWF - 1; ++i) wf[i] = read_w(i);
 #pragma unroll
         for (int grp = 0; grp < kGroups; ++grp) {
-            if (grp + 2 < kGroups) wf[(grp + 2) % 3] = read_w(grp + 2);
+            if (grp + kWF - 1 < kGroups) wf[(grp + kWF - 1) % kWF] = read_w(grp + kWF - 1);
             if (kKSteps == 2 && grp >= 1 && grp <= kMI) xf[kKSteps - 1][grp - 1] = read_x(1, grp - 1);
 #pragma unroll
             for (int e = 0; e < kPerGroup; ++e) extra(grp * kPerGroup + e);
             __builtin_amdgcn_sched_barrier(0);  // keeps this group's other work ahead of the MFMAs that hide it
 #pragma unroll
-            for (int mi = 0; mi < kMI; ++mi) mfma_acc(acc[grp % kNI][mi], wf[grp % 3], xf[grp / kNI][mi]);
+            for (int mi = 0; mi < kMI; ++mi) mfma_acc(acc[grp % kNI][mi], wf[grp % kWF], xf[grp / kNI][mi]);
         }
     };
 
@@ -221,23 +225,27 @@ __global__ __launch_bounds__(kDenseThreads<COT>, (KS == 32 ? 2 : 1)) void gather
     static_assert(kRS % 2 == 0, "the register stage and LDS buffer of a step are its index in the turn % 2");
     // The offsets to visit, ascending: all of them, or those of the tile's mask.  next_offset() hands them out
     // one by one and then kvol (for which every load reads zeros) for ever.
-    uint32_t todo[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int lo = 32 * i, n = a.kvol - lo;
+    // (Four named words, not an array: an array here ends up in scratch memory, and each read of it then makes
+    // the wavefront wait for every gather it has in flight.)
+    auto mask_word = [&](int i) __attribute__((always_inline)) {
+        const int n = a.kvol - 32 * i;
         uint32_t all = n >= 32 ? 0xffffffffu : (n > 0 ? (1u << n) - 1u : 0u);
         if (a.tile_mask) all &= a.tile_mask[tile * 4 + i];
-        todo[i] = __builtin_amdgcn_readfirstlane(all);
-    }
+        return (uint32_t)__builtin_amdgcn_readfirstlane(all);
+    };
+    uint32_t todo0 = mask_word(0), todo1 = mask_word(1), todo2 = mask_word(2), todo3 = mask_word(3);
     auto next_offset = [&]() __attribute__((always_inline)) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            if (todo[i]) {
-                const int b = __builtin_ctz(todo[i]);
-                todo[i] &= todo[i] - 1;
-                return 32 * i + b;
-            }
-        return a.kvol;
+        // every word is assigned on every call (a store under a condition would bring the memory form back)
+        const bool u0 = todo0 != 0, u1 = !u0 && todo1 != 0, u2 = !u0 && !u1 && todo2 != 0,
+                   u3 = !u0 && !u1 && !u2 && todo3 != 0;
+        const int k = u0 ? __builtin_ctz(todo0)
+                         : (u1 ? 32 + __builtin_ctz(todo1)
+                               : (u2 ? 64 + __builtin_ctz(todo2) : (u3 ? 96 + __builtin_ctz(todo3) : a.kvol)));
+        todo0 = u0 ? (todo0 & (todo0 - 1)) : todo0;
+        todo1 = u1 ? (todo1 & (todo1 - 1)) : todo1;
+        todo2 = u2 ? (todo2 & (todo2 - 1)) : todo2;
+        todo3 = u3 ? (todo3 & (todo3 - 1)) : todo3;
+        return k;
     };
     Where cur[kOPR], nxt[kOPR];  // the offsets of this turn and of the next
     int k_cur[kOPR];             // this turn's offsets (kvol: none left)
@@ -261,9 +269,20 @@ __global__ __launch_bounds__(kDenseThreads<COT>, (KS == 32 ? 2 : 1)) void gather
         k_raw[o] = next_offset();
         load_nbr(k_raw[o], raw[o]);
     }
-    u32x4 sx[2][kXLoads], sw[kWDepth][kWLoads];
     // step j of this turn (j < kRS) or of the next (j >= kRS): its offset's addresses and its slice
     auto where_of = [&](int j) -> const Where& { return j < kRS ? cur[j / kSPO] : nxt[(j - kRS) / kSPO]; };
+    auto advance_turn = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int o = 0; o < kOPR; ++o) {
+            cur[o] = nxt[o];
+            k_cur[o] = k_nxt[o];
+            k_nxt[o] = k_raw[o];
+            locate(k_nxt[o], raw[o], nxt[o]);
+            k_raw[o] = next_offset();
+            load_nbr(k_raw[o], raw[o]);
+        }
+    };
+    u32x4 sx[2][kXLoads], sw[kWDepth][kWLoads];
 #pragma unroll
     for (int j = 0; j < kXLoads; ++j) load_x(sx[0], j, 0, where_of(0));
 #pragma unroll
@@ -299,15 +318,7 @@ __global__ __launch_bounds__(kDenseThreads<COT>, (KS == 32 ? 2 : 1)) void gather
             });
             __syncthreads();
         }
-#pragma unroll
-        for (int o = 0; o < kOPR; ++o) {
-            cur[o] = nxt[o];
-            k_cur[o] = k_nxt[o];
-            k_nxt[o] = k_raw[o];
-            locate(k_nxt[o], raw[o], nxt[o]);
-            k_raw[o] = next_offset();
-            load_nbr(k_raw[o], raw[o]);
-        }
+        advance_turn();
     }
 
     // the accumulators are read below by ordinary instructions: the MFMAs were written as opaque instructions,

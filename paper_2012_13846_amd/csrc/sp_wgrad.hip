@@ -457,6 +457,14 @@ __global__ __launch_bounds__(64 * WCO * WCI * WK) void wgrad_staged_kernel(Stage
         auto chan = [&](int t, int m, int kt) { return kIsF32 ? m * kt + t : t * 16 + m; };
         typedef Part Partx4 __attribute__((ext_vector_type(4)));
         Part* dst = static_cast<Part*>(a.part) + (size_t)slot * a.cout * a.cin;
+        // Large tiles: the lane's position is made opaque here, or the store addresses below are computed before the
+        // main loop, where the registers that hold them get spilled and reloaded between the gathers (a reload waits
+        // for every load issued before it; 256 x 256) or cost two thirds of the wavefronts per SIMD (128 x 128).
+        auto opaque = [](int v) __attribute__((always_inline)) {
+            if constexpr (COB * CIB >= 128 * 128) asm volatile("" : "+v"(v));
+            return v;
+        };
+        const int g_here = opaque(g), n16_here = opaque(n16);
         if constexpr (WK > 1) {
             Part* red = reinterpret_cast<Part*>(smem);
             for (int w = 0; w < WK; ++w) {
@@ -467,7 +475,7 @@ __global__ __launch_bounds__(64 * WCO * WCI * WK) void wgrad_staged_kernel(Stage
                         for (int tb = 0; tb < kTB; ++tb)
 #pragma unroll
                             for (int j = 0; j < 4; ++j) {
-                                const int e = (wco * kTA * 16 + chan(ta, g * 4 + j, kTA)) * CIB + wci * kTB * 16 + chan(tb, n16, kTB);
+                                const int e = (wco * kTA * 16 + chan(ta, g_here * 4 + j, kTA)) * CIB + wci * kTB * 16 + chan(tb, n16_here, kTB);
                                 red[e] = (w == 0 ? (Part)0 : red[e]) + piece_val(ta, tb, j);
                             }
                 }
@@ -484,8 +492,8 @@ __global__ __launch_bounds__(64 * WCO * WCI * WK) void wgrad_staged_kernel(Stage
                 for (int tb = 0; tb < kTB; ++tb)
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
-                        dst[(size_t)(co0 + wco * kTA * 16 + chan(ta, g * 4 + j, kTA)) * a.cin + ci0 + wci * kTB * 16 +
-                            chan(tb, n16, kTB)] = piece_val(ta, tb, j);
+                        dst[(size_t)(co0 + wco * kTA * 16 + chan(ta, g_here * 4 + j, kTA)) * a.cin + ci0 + wci * kTB * 16 +
+                            chan(tb, n16_here, kTB)] = piece_val(ta, tb, j);
         }
         __syncthreads();  // the next piece reuses the staging buffers
     }
